@@ -1,0 +1,113 @@
+/* spdnn -- layer-by-layer sparse-DNN inference on one AMD MI355X (gfx950).
+ *
+ * The library evaluates, for l = 0 .. L-1,
+ *
+ *     Y_{l+1}[r][j] = min(max( sum_{k<32} Y_l[r][idx_l[j][k]] * val_l[j][k] + bias[j], 0), 32)
+ *
+ * (Section II-A-1, Eq. 1, with the clipped ReLU defined next to it; the steps
+ * are those of Alg. 1, step 3), where Y_l is a dense batch x N feature map,
+ * one feature row per input, and output neuron j of layer l has exactly 32
+ * stored connections (input column idx_l[j][k], weight val_l[j][k]).  After
+ * every layer the rows with no strictly positive output are dropped and the
+ * list of surviving rows is compacted, as the host loop of Listing 1 does; a
+ * dropped row is never evaluated again, which is exact because every bias is
+ * required to be <= 0 (a zero row then stays zero).
+ *
+ * All entry points return 0 (SPDNN_OK) or a negative error code; none throws or
+ * aborts.  spdnn_last_error() gives the message of the calling thread's last
+ * failure.  Device memory is never allocated here: the caller passes arenas
+ * (for example torch tensors) and keeps them alive while the handle uses them.
+ * Everything runs on the HIP stream given to spdnn_create, on the device that
+ * is current when the calls are made.
+ */
+#ifndef SPDNN_H
+#define SPDNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spdnn_model* spdnn_t; /* opaque; owns small host metadata, two HIP events and a
+                                        pinned host array of L+1 counters, nothing the caller allocated */
+
+enum {
+    SPDNN_OK = 0,
+    SPDNN_EINVAL = -1, /* null pointer, N not a multiple of 4 in [32, 65536], L < 1, batch < 0,
+                          misaligned buffer, column index outside [0, N) */
+    SPDNN_EBIAS = -2,  /* some bias[j] > 0 or not finite: dropping all-zero rows would not be exact */
+    SPDNN_EHIP = -3,   /* a HIP runtime call failed; message in spdnn_last_error() */
+    SPDNN_ESIZE = -4   /* an arena is smaller than spdnn_weights_bytes / spdnn_work_bytes says */
+};
+
+enum { SPDNN_HOST = 0, SPDNN_DEVICE = 1 }; /* where the arrays given to spdnn_create live */
+
+/* Bytes of device memory spdnn_create needs for a model of L layers of N neurons
+ * (re-laid weights of all layers, bias, and staging for one raw layer). */
+int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes);
+
+/* Bytes of device memory spdnn_infer needs for up to max_batch rows: two feature
+ * maps of max_batch x N floats (the ping-pong pair of Listing 1) plus row lists
+ * and flags. */
+int spdnn_work_bytes(int32_t N, int32_t max_batch, size_t* bytes);
+
+/* Build a model (once per network; not part of inference time -- the paper's
+ * tiling structures are likewise "constructed once prior to inference",
+ * Section III-A-2).
+ *   idx, val : host arrays of L pointers.  idx[l][j*32+k] = input column of the k-th
+ *              connection of output neuron j of layer l, in [0, N); val[l][j*32+k] its
+ *              weight.  Duplicated columns within a neuron are allowed (they add up).
+ *              The L pointers point to host memory if where == SPDNN_HOST, to device
+ *              memory if where == SPDNN_DEVICE.  Read during the call only.
+ *   bias     : N floats (host or device as `where` says), one per output neuron, the
+ *              same for every layer (Listings 1 and 2 index it by output neuron);
+ *              every entry must be <= 0.
+ *   weights_arena : device memory, 256-byte aligned, >= spdnn_weights_bytes(N, L); owned
+ *              by the caller, used by the handle until spdnn_destroy.
+ *   hip_stream : a hipStream_t (NULL = default stream) on which create and infer enqueue.
+ * On failure *out is NULL. */
+int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx,
+                 const float* const* val, const float* bias, int32_t where,
+                 void* weights_arena, size_t weights_arena_bytes, void* hip_stream);
+
+/* Run all L layers on `batch` feature rows.
+ *   Y0_dev : device, batch x N floats, row-major (row r = input r), 16-byte aligned, finite
+ *            values; not modified.
+ *   work_arena : device memory, 256-byte aligned, >= spdnn_work_bytes(N, batch); contents
+ *            are scratch.
+ *   n_active_host   : host int32, receives the number of rows of Y_L that have a strictly
+ *            positive element (Alg. 1 step 4 works from these rows).
+ *   active_rows_dev : device int32[batch]; first n_active entries = original row numbers of
+ *            those rows, ascending.
+ *   Y_final_dev : device float[batch*N] or NULL; row i of the first n_active rows is row
+ *            active_rows[i] of Y_L.  NULL skips this output.
+ * The call enqueues on the model's stream and returns after the stream has drained (it
+ * must hand back n_active).  batch == 0 is valid and gives n_active = 0.  Calls on one
+ * handle must not overlap. */
+int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
+                size_t work_arena_bytes, int32_t* n_active_host, int32_t* active_rows_dev,
+                float* Y_final_dev);
+
+/* Release the handle (NULL is a no-op).  The arenas stay the caller's. */
+int spdnn_destroy(spdnn_t h);
+
+/* Message of the last failure on the calling thread ("" if none). */
+const char* spdnn_last_error(void);
+
+/* Measurement aid (not part of the paper's method): with profiling on, spdnn_infer brackets
+ * every fused-layer launch with HIP events on the model's stream. */
+int spdnn_set_profiling(spdnn_t h, int32_t on);
+
+/* After an spdnn_infer with profiling on: *layers_run = number of layers that were launched
+ * (inference stops early once no row is active); for l < min(cap, *layers_run),
+ * rows_in[l] = rows active on entry to layer l and fused_ms[l] = duration of that layer's
+ * fused SpMM+bias+ReLU kernel in milliseconds.  Either array may be NULL. */
+int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows_in,
+                      float* fused_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPDNN_H */

@@ -1,0 +1,199 @@
+"""Python binding of the spdnn C-ABI library (include/spdnn.h).
+
+Argument marshalling only: every step of the inference runs in the HIP kernels
+of csrc/.  torch is used to allocate device memory and to provide the stream.
+There is no CPU fallback: if csrc/libspdnn.so is missing or cannot be loaded the
+import of the library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import build as _build
+
+_lib = None
+
+SPDNN_OK = 0
+SPDNN_EINVAL = -1
+SPDNN_EBIAS = -2
+SPDNN_EHIP = -3
+SPDNN_ESIZE = -4
+SPDNN_HOST = 0
+SPDNN_DEVICE = 1
+
+EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
+           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile")
+
+
+class SpdnnError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("spdnn error %d: %s" % (code, msg))
+        self.code = code
+
+
+def lib():
+    """Load csrc/libspdnn.so (build it first with build.build() or __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            raise RuntimeError("%s is missing: build the HIP library first (python -m "
+                               "paper_2007_14152_amd.build); there is no fallback path" % _build.LIB)
+        L = ctypes.CDLL(_build.LIB)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.spdnn_weights_bytes.argtypes = [i32, i32, ctypes.POINTER(sz)]
+        L.spdnn_work_bytes.argtypes = [i32, i32, ctypes.POINTER(sz)]
+        L.spdnn_create.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+                                   i32, vp, sz, vp]
+        L.spdnn_infer.argtypes = [vp, vp, i32, vp, sz, ctypes.POINTER(i32), vp, vp]
+        L.spdnn_destroy.argtypes = [vp]
+        L.spdnn_last_error.argtypes = []
+        L.spdnn_last_error.restype = ctypes.c_char_p
+        L.spdnn_set_profiling.argtypes = [vp, i32]
+        L.spdnn_get_profile.argtypes = [vp, i32, ctypes.POINTER(i32), vp, vp]
+        for n in EXPORTS:
+            if n != "spdnn_last_error":
+                getattr(L, n).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def spdnn_last_error() -> str:
+    return lib().spdnn_last_error().decode()
+
+
+def _check(rc):
+    if rc != SPDNN_OK:
+        raise SpdnnError(rc, spdnn_last_error())
+
+
+def spdnn_weights_bytes(N: int, L: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().spdnn_weights_bytes(N, L, ctypes.byref(out)))
+    return out.value
+
+
+def spdnn_work_bytes(N: int, max_batch: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().spdnn_work_bytes(N, max_batch, ctypes.byref(out)))
+    return out.value
+
+
+def spdnn_create(N, L, idx_ptrs, val_ptrs, bias_ptr, where, arena_ptr, arena_bytes, stream=0):
+    """idx_ptrs / val_ptrs: sequences of L raw addresses (host or device as `where`
+    says); returns the opaque handle (an integer address)."""
+    ip = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in idx_ptrs])
+    vp = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in val_ptrs])
+    h = ctypes.c_void_p(0)
+    _check(lib().spdnn_create(ctypes.byref(h), N, L, ip, vp, ctypes.c_void_p(int(bias_ptr)), where,
+                              ctypes.c_void_p(int(arena_ptr)), arena_bytes, ctypes.c_void_p(int(stream))))
+    return h.value
+
+
+def spdnn_infer(h, y0_ptr, batch, work_ptr, work_bytes, active_rows_ptr, y_final_ptr) -> int:
+    """Returns n_active."""
+    n = ctypes.c_int32(-1)
+    _check(lib().spdnn_infer(ctypes.c_void_p(h), ctypes.c_void_p(int(y0_ptr)), batch,
+                             ctypes.c_void_p(int(work_ptr)), work_bytes, ctypes.byref(n),
+                             ctypes.c_void_p(int(active_rows_ptr)),
+                             ctypes.c_void_p(int(y_final_ptr)) if y_final_ptr else None))
+    return n.value
+
+
+def spdnn_destroy(h) -> None:
+    _check(lib().spdnn_destroy(ctypes.c_void_p(h) if h else None))
+
+
+def spdnn_set_profiling(h, on: bool) -> None:
+    _check(lib().spdnn_set_profiling(ctypes.c_void_p(h), 1 if on else 0))
+
+
+def spdnn_get_profile(h, cap: int):
+    """Returns (layers_run, rows_in[:n], fused_ms[:n]) of the last profiled spdnn_infer."""
+    import numpy as np
+    rows = np.zeros(max(cap, 1), dtype=np.int32)
+    ms = np.zeros(max(cap, 1), dtype=np.float32)
+    run = ctypes.c_int32(0)
+    _check(lib().spdnn_get_profile(ctypes.c_void_p(h), cap, ctypes.byref(run), rows.ctypes.data, ms.ctypes.data))
+    n = min(cap, run.value)
+    return run.value, rows[:n], ms[:n]
+
+
+class Model:
+    """Convenience owner of a handle and its arenas (torch tensors on the GPU).
+
+    idx / val: lists of L arrays [N, 32] -- numpy arrays or CPU torch tensors
+    (copied through the host path) or CUDA torch tensors (device path); bias: [N].
+    """
+
+    def __init__(self, idx, val, bias, device="cuda:0", stream=None):
+        import numpy as np
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        L = len(idx)
+        N = int(bias.shape[0])
+        self.N, self.L = N, L
+        on_dev = hasattr(idx[0], "is_cuda") and idx[0].is_cuda
+        keep = []
+        if on_dev:
+            idx = [a.to(torch.int32).contiguous() for a in idx]
+            val = [a.to(torch.float32).contiguous() for a in val]
+            b = bias.to(self.device, torch.float32).contiguous()
+            ip = [a.data_ptr() for a in idx]
+            vp = [a.data_ptr() for a in val]
+            bp = b.data_ptr()
+            where = SPDNN_DEVICE
+        else:
+            idx = [np.ascontiguousarray(np.asarray(a), dtype=np.int32) for a in idx]
+            val = [np.ascontiguousarray(np.asarray(a), dtype=np.float32) for a in val]
+            b = np.ascontiguousarray(np.asarray(bias), dtype=np.float32)
+            ip = [a.ctypes.data for a in idx]
+            vp = [a.ctypes.data for a in val]
+            bp = b.ctypes.data
+            where = SPDNN_HOST
+        for a, v in zip(idx, val):
+            assert tuple(a.shape) == (N, 32) and tuple(v.shape) == (N, 32)
+        keep += [idx, val, b]
+        nbytes = spdnn_weights_bytes(N, L)
+        with torch.cuda.device(self.device):
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            s = stream if stream is not None else torch.cuda.current_stream(self.device)
+            self.stream = s
+            self.h = spdnn_create(N, L, ip, vp, bp, where, self.arena.data_ptr(), nbytes, s.cuda_stream)
+        self.work = None
+        del keep
+
+    def infer(self, Y0, want_Y=True):
+        """Y0: CUDA float32 [batch, N].  Returns (n_active, active_rows[int32 n], Y[n, N] or None)."""
+        torch = self.torch
+        assert Y0.is_cuda and Y0.dtype == torch.float32 and Y0.is_contiguous()
+        batch = int(Y0.shape[0])
+        assert Y0.shape[1] == self.N
+        with torch.cuda.device(self.device):
+            need = spdnn_work_bytes(self.N, batch)
+            if self.work is None or self.work.numel() < need:
+                self.work = None
+                self.work = torch.empty(need, dtype=torch.uint8, device=self.device)
+            rows = torch.empty(max(batch, 1), dtype=torch.int32, device=self.device)
+            Yf = torch.empty((max(batch, 1), self.N), dtype=torch.float32, device=self.device) if want_Y else None
+            n = spdnn_infer(self.h, Y0.data_ptr(), batch, self.work.data_ptr(), self.work.numel(),
+                            rows.data_ptr(), Yf.data_ptr() if want_Y else 0)
+        return n, rows[:n], (Yf[:n] if want_Y else None)
+
+    def set_profiling(self, on=True):
+        spdnn_set_profiling(self.h, on)
+
+    def profile(self):
+        return spdnn_get_profile(self.h, self.L)
+
+    def close(self):
+        if getattr(self, "h", None):
+            spdnn_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,380 @@
+// Host side of the spdnn C-ABI (see include/spdnn.h): argument checks, arena
+// carving, weight set-up, and the per-layer launch loop.  Every arithmetic step
+// of the inference runs in the kernels of spdnn_kernels.h.
+#include "../../include/spdnn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "spdnn_kernels.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail(SPDNN_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_),    \
+                        __FILE__, __LINE__);                                                  \
+    } while (0)
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+constexpr int kLag = 2;  // the host runs at most this many layers ahead of the GPU
+
+struct LayerDesc {
+    spdnn::LayerWeights w;
+    int multi;     // some block's window is wider than one LDS stage
+    int lds_cols;  // columns the LDS tile must hold for this layer
+};
+
+}  // namespace
+
+struct spdnn_model {
+    int32_t N = 0, L = 0, nblk = 0, G = 1;
+    hipStream_t stream = nullptr;
+    int num_cu = 256;
+    const float* bias_dev = nullptr;
+    std::vector<LayerDesc> layers;
+    int* host_counts = nullptr;  // pinned, L+1 entries: rows active on entry to layer l
+    hipEvent_t lag_ev[kLag] = {nullptr, nullptr};
+    // profiling
+    int profiling = 0;
+    std::vector<hipEvent_t> t0, t1;
+    int32_t prof_layers = 0;
+    std::vector<float> prof_ms;
+    std::vector<int32_t> prof_rows;
+};
+
+namespace {
+
+bool valid_n(int32_t N) { return N >= 32 && N <= 65536 && (N % 4) == 0; }
+
+size_t layer_bytes(int32_t nblk) {
+    const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
+    return up((size_t)nblk * sizeof(int2)) + up(e * sizeof(uint16_t)) + up(e * sizeof(float));
+}
+size_t staging_bytes(int32_t N) {
+    return up((size_t)N * spdnn::kNnz * sizeof(int32_t)) + up((size_t)N * spdnn::kNnz * sizeof(float)) +
+           up(sizeof(int));
+}
+
+struct WorkView {
+    float* Y[2];
+    int* cat[2];
+    int* gid[2];
+    int* flags;
+    int* count;
+};
+size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
+    size_t o = 0;
+    const size_t yb = up((size_t)batch * N * sizeof(float));
+    const size_t lb = up((size_t)batch * sizeof(int));
+    for (int i = 0; i < 2; ++i) {
+        if (v) v->Y[i] = reinterpret_cast<float*>(base + o);
+        o += yb;
+    }
+    for (int i = 0; i < 2; ++i) {
+        if (v) v->cat[i] = reinterpret_cast<int*>(base + o);
+        o += lb;
+    }
+    for (int i = 0; i < 2; ++i) {
+        if (v) v->gid[i] = reinterpret_cast<int*>(base + o);
+        o += lb;
+    }
+    if (v) v->flags = reinterpret_cast<int*>(base + o);
+    o += lb;
+    if (v) v->count = reinterpret_cast<int*>(base + o);
+    o += kAlign;
+    return o;
+}
+
+template <bool MULTI>
+hipError_t allow_big_lds() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_layer_kernel<MULTI>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * spdnn::kCap * 16);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* spdnn_last_error(void) { return g_err.c_str(); }
+
+int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes) {
+    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
+    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+    const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
+    *bytes = up((size_t)N * sizeof(float)) + (size_t)L * layer_bytes(nblk) + staging_bytes(N);
+    return SPDNN_OK;
+}
+
+int spdnn_work_bytes(int32_t N, int32_t max_batch, size_t* bytes) {
+    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
+    if (!valid_n(N) || max_batch < 0) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, batch >= 0");
+    *bytes = carve_work(N, max_batch, nullptr, nullptr);
+    return SPDNN_OK;
+}
+
+int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, const float* const* val,
+                 const float* bias, int32_t where, void* weights_arena, size_t weights_arena_bytes,
+                 void* hip_stream) {
+    if (!out) return fail(SPDNN_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+    if (!idx || !val || !bias || !weights_arena) return fail(SPDNN_EINVAL, "null argument");
+    if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
+    if (reinterpret_cast<uintptr_t>(weights_arena) % kAlign) return fail(SPDNN_EINVAL, "weights_arena must be 256-byte aligned");
+    for (int32_t l = 0; l < L; ++l)
+        if (!idx[l] || !val[l]) return fail(SPDNN_EINVAL, "idx[%d] or val[%d] is NULL", l, l);
+    size_t need = 0;
+    spdnn_weights_bytes(N, L, &need);
+    if (weights_arena_bytes < need)
+        return fail(SPDNN_ESIZE, "weights arena has %zu bytes, %zu needed", weights_arena_bytes, need);
+
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
+
+    // bias: must be <= 0 everywhere, otherwise a dropped (all-zero) row would not stay zero
+    std::vector<float> hb(N);
+    if (where == SPDNN_HOST) {
+        std::memcpy(hb.data(), bias, sizeof(float) * N);
+    } else {
+        HIP_TRY(hipMemcpy(hb.data(), bias, sizeof(float) * N, hipMemcpyDeviceToHost));
+    }
+    for (int32_t j = 0; j < N; ++j)
+        if (!(hb[j] <= 0.0f) || !std::isfinite(hb[j]))
+            return fail(SPDNN_EBIAS, "bias[%d] = %g: every bias must be finite and <= 0", j, (double)hb[j]);
+
+    spdnn_model* m = new (std::nothrow) spdnn_model;
+    if (!m) return fail(SPDNN_EHIP, "out of host memory");
+    struct Guard {
+        spdnn_model* m;
+        ~Guard() {
+            if (m) spdnn_destroy(m);
+        }
+    } guard{m};
+
+    m->N = N;
+    m->L = L;
+    m->nblk = nblk;
+    m->G = (nblk % 4 == 0) ? 4 : (nblk % 3 == 0) ? 3 : (nblk % 2 == 0) ? 2 : 1;
+    m->stream = stream;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    m->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    HIP_TRY(allow_big_lds<false>());
+    HIP_TRY(allow_big_lds<true>());
+    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
+                          hipHostMallocDefault));
+    for (int i = 0; i < kLag; ++i) HIP_TRY(hipEventCreateWithFlags(&m->lag_ev[i], hipEventDisableTiming));
+
+    // carve the arena: bias | L x (win, rel, val) | staging (raw idx, raw val, error flag)
+    char* base = static_cast<char*>(weights_arena);
+    size_t o = 0;
+    float* bias_dev = reinterpret_cast<float*>(base + o);
+    o += up((size_t)N * sizeof(float));
+    HIP_TRY(hipMemcpyAsync(bias_dev, hb.data(), sizeof(float) * N, hipMemcpyHostToDevice, stream));
+    m->bias_dev = bias_dev;
+    const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
+    std::vector<int2*> win_dev(L);
+    m->layers.resize(L);
+    for (int32_t l = 0; l < L; ++l) {
+        int2* win = reinterpret_cast<int2*>(base + o);
+        o += up((size_t)nblk * sizeof(int2));
+        uint16_t* rel = reinterpret_cast<uint16_t*>(base + o);
+        o += up(e * sizeof(uint16_t));
+        float* wv = reinterpret_cast<float*>(base + o);
+        o += up(e * sizeof(float));
+        m->layers[l].w = spdnn::LayerWeights{rel, wv, win};
+        win_dev[l] = win;
+    }
+    int32_t* st_idx = reinterpret_cast<int32_t*>(base + o);
+    o += up((size_t)N * spdnn::kNnz * sizeof(int32_t));
+    float* st_val = reinterpret_cast<float*>(base + o);
+    o += up((size_t)N * spdnn::kNnz * sizeof(float));
+    int* err_dev = reinterpret_cast<int*>(base + o);
+    HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int), stream));
+
+    const size_t raw = (size_t)N * spdnn::kNnz;
+    for (int32_t l = 0; l < L; ++l) {
+        const int32_t* di = idx[l];
+        const float* dv = val[l];
+        if (where == SPDNN_HOST) {
+            HIP_TRY(hipMemcpyAsync(st_idx, idx[l], raw * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+            HIP_TRY(hipMemcpyAsync(st_val, val[l], raw * sizeof(float), hipMemcpyHostToDevice, stream));
+            di = st_idx;
+            dv = st_val;
+        }
+        const LayerDesc& d = m->layers[l];
+        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev);
+        spdnn::pack_weights_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(
+            di, dv, N, win_dev[l], const_cast<uint16_t*>(d.w.rel), const_cast<float*>(d.w.val));
+        HIP_TRY(hipGetLastError());
+        if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
+    }
+    // read back the windows (stage counts, LDS sizes) and the error flag
+    std::vector<int2> hw((size_t)L * nblk);
+    int herr = 0;
+    for (int32_t l = 0; l < L; ++l)
+        HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipMemcpyAsync(&herr, err_dev, sizeof(int), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (herr) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
+    for (int32_t l = 0; l < L; ++l) {
+        int widest = 4;
+        for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[(size_t)l * nblk + b].y);
+        m->layers[l].multi = widest > spdnn::kCap;
+        m->layers[l].lds_cols = std::min(widest, spdnn::kCap);
+    }
+    guard.m = nullptr;
+    *out = m;
+    return SPDNN_OK;
+}
+
+int spdnn_destroy(spdnn_t h) {
+    if (!h) return SPDNN_OK;
+    if (h->host_counts) (void)hipHostFree(h->host_counts);
+    for (int i = 0; i < kLag; ++i)
+        if (h->lag_ev[i]) (void)hipEventDestroy(h->lag_ev[i]);
+    for (hipEvent_t e : h->t0) (void)hipEventDestroy(e);
+    for (hipEvent_t e : h->t1) (void)hipEventDestroy(e);
+    delete h;
+    return SPDNN_OK;
+}
+
+int spdnn_set_profiling(spdnn_t h, int32_t on) {
+    if (!h) return fail(SPDNN_EINVAL, "handle is NULL");
+    if (on && h->t0.empty()) {
+        h->t0.resize(h->L, nullptr);
+        h->t1.resize(h->L, nullptr);
+        for (int32_t l = 0; l < h->L; ++l) {
+            HIP_TRY(hipEventCreate(&h->t0[l]));
+            HIP_TRY(hipEventCreate(&h->t1[l]));
+        }
+    }
+    h->profiling = on ? 1 : 0;
+    return SPDNN_OK;
+}
+
+int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows_in, float* fused_ms) {
+    if (!h || !layers_run) return fail(SPDNN_EINVAL, "null argument");
+    *layers_run = h->prof_layers;
+    const int32_t n = std::min<int32_t>(cap, h->prof_layers);
+    for (int32_t l = 0; l < n; ++l) {
+        if (rows_in) rows_in[l] = h->prof_rows[l];
+        if (fused_ms) fused_ms[l] = l < (int32_t)h->prof_ms.size() ? h->prof_ms[l] : 0.0f;
+    }
+    return SPDNN_OK;
+}
+
+int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena, size_t work_arena_bytes,
+                int32_t* n_active_host, int32_t* active_rows_dev, float* Y_final_dev) {
+    if (!h) return fail(SPDNN_EINVAL, "handle is NULL");
+    if (!n_active_host) return fail(SPDNN_EINVAL, "n_active_host is NULL");
+    if (batch < 0) return fail(SPDNN_EINVAL, "batch < 0");
+    h->prof_layers = 0;
+    if (batch == 0) {
+        *n_active_host = 0;
+        return SPDNN_OK;
+    }
+    if (!Y0_dev || !work_arena || !active_rows_dev) return fail(SPDNN_EINVAL, "null argument");
+    if (reinterpret_cast<uintptr_t>(Y0_dev) % 16) return fail(SPDNN_EINVAL, "Y0 must be 16-byte aligned");
+    if (Y_final_dev && reinterpret_cast<uintptr_t>(Y_final_dev) % 16) return fail(SPDNN_EINVAL, "Y_final must be 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(work_arena) % kAlign) return fail(SPDNN_EINVAL, "work_arena must be 256-byte aligned");
+    const int32_t N = h->N, L = h->L;
+    const size_t need = carve_work(N, batch, nullptr, nullptr);
+    if (work_arena_bytes < need) return fail(SPDNN_ESIZE, "work arena has %zu bytes, %zu needed", work_arena_bytes, need);
+    WorkView wv;
+    carve_work(N, batch, static_cast<char*>(work_arena), &wv);
+    hipStream_t s = h->stream;
+
+    spdnn::init_lists_kernel<<<(batch + 255) / 256, 256, 0, s>>>(wv.cat[0], wv.gid[0], wv.flags, wv.count, batch);
+    h->host_counts[0] = batch;
+    int32_t bound = batch;  // upper bound of the rows active at the layer being launched
+    int32_t run = 0;        // layers launched
+    for (int32_t l = 0; l < L; ++l) {
+        const LayerDesc& d = h->layers[l];
+        const float* Yin = (l == 0) ? Y0_dev : wv.Y[(l - 1) & 1];
+        float* Yout = wv.Y[l & 1];
+        // launch shape: one workgroup per CU; the rows are cut into Q chunks per output block
+        const int32_t ngroups = (bound + spdnn::kRows - 1) / spdnn::kRows;
+        int32_t Q = std::max(1, h->num_cu / h->nblk);
+        Q = std::max(1, std::min(Q, ngroups));
+        const int32_t units = (h->nblk / h->G) * Q;
+        const int32_t grid = (units + 7) / 8 * 8 * h->G;
+        const size_t lds = (size_t)((d.lds_cols + 7) / 8) * 256;
+        if (h->profiling) HIP_TRY(hipEventRecord(h->t0[l], s));
+        if (d.multi)
+            spdnn::fused_layer_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(
+                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
+        else
+            spdnn::fused_layer_kernel<false><<<grid, spdnn::kBlk, lds, s>>>(
+                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
+        if (h->profiling) HIP_TRY(hipEventRecord(h->t1[l], s));
+        spdnn::compact_kernel<<<1, 1024, 0, s>>>(wv.flags, wv.count, wv.gid[l & 1], wv.gid[(l + 1) & 1],
+                                                  wv.cat[(l + 1) & 1], h->host_counts + l + 1);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(h->lag_ev[l % kLag], s));
+        run = l + 1;
+        // feedback with bounded lag: wait for layer l+1-kLag, whose survivor count bounds all later ones
+        if (l + 1 >= kLag) {
+            const int32_t lr = l + 1 - kLag;
+            HIP_TRY(hipEventSynchronize(h->lag_ev[lr % kLag]));
+            bound = h->host_counts[lr + 1];
+            if (bound == 0) break;
+        }
+    }
+    HIP_TRY(hipStreamSynchronize(s));
+    const int32_t n = h->host_counts[run];
+    *n_active_host = n;
+    if (n > 0) {
+        const int32_t lf = run - 1;  // == L-1 here: rows survive only if every layer ran
+        const int* cat_f = wv.cat[(lf + 1) & 1];
+        const int* gid_f = wv.gid[(lf + 1) & 1];
+        HIP_TRY(hipMemcpyAsync(active_rows_dev, gid_f, sizeof(int) * (size_t)n, hipMemcpyDeviceToDevice, s));
+        if (Y_final_dev) {
+            const int n4 = N / 4;
+            const size_t total = (size_t)n * n4;
+            const int g = (int)std::min<size_t>((total + 255) / 256, 65536);
+            spdnn::gather_rows_kernel<<<g, 256, 0, s>>>(reinterpret_cast<const float4*>(wv.Y[lf & 1]), cat_f, n, n4,
+                                                       reinterpret_cast<float4*>(Y_final_dev));
+            HIP_TRY(hipGetLastError());
+        }
+        HIP_TRY(hipStreamSynchronize(s));
+    }
+    if (h->profiling) {
+        h->prof_layers = run;
+        h->prof_ms.assign(run, 0.0f);
+        h->prof_rows.assign(run, 0);
+        for (int32_t l = 0; l < run; ++l) {
+            h->prof_rows[l] = h->host_counts[l];
+            HIP_TRY(hipEventElapsedTime(&h->prof_ms[l], h->t0[l], h->t1[l]));
+        }
+    }
+    return SPDNN_OK;
+}
+
+}  // extern "C"

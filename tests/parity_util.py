@@ -1,0 +1,62 @@
+"""Helpers shared by the GPU parity tests: run the library through its C-ABI
+binding, run the oracle, and compare to the stated bar:
+  * active-row list bit-exact, except rows the oracle marks fragile (largest
+    pre-activation within 1e-4 of zero at some layer while active);
+  * Y within 1e-5 relative or 1e-6 absolute (float32)."""
+import numpy as np
+
+import oracle
+import synth
+
+RTOL = 1e-5
+ATOL = 1e-6
+
+
+def close(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return np.abs(a - b) <= np.maximum(ATOL, RTOL * np.abs(b))
+
+
+def gpu_infer(idx, val, bias, Y0, device="cuda:0", model=None):
+    import torch
+    import paper_2007_14152_amd as sp
+    own = model is None
+    if own:
+        model = sp.Model(idx, val, bias, device=device)
+    y0 = Y0 if hasattr(Y0, "is_cuda") else torch.from_numpy(np.ascontiguousarray(Y0, dtype=np.float32))
+    y0 = y0.to(device).contiguous()
+    n, rows, Y = model.infer(y0)
+    out = (n, rows.cpu().numpy().copy(), Y.cpu().numpy().copy())
+    if own:
+        model.close()
+    return out
+
+
+def check_against_oracle(ref, n, rows, Y, row_ids=None, what=""):
+    """ref: OracleResult for the rows row_ids (None = all rows, ids 0..batch-1).
+    n, rows, Y: the library's output restricted to the same rows (original ids)."""
+    ids = np.arange(len(ref.fragile_layer)) if row_ids is None else np.asarray(row_ids)
+    fragile = set(ids[ref.fragile_layer >= 0].tolist())
+    ora_rows = ids[ref.active_rows] if row_ids is not None else ref.active_rows
+    g, o = set(rows.tolist()), set(ora_rows.tolist())
+    assert n == len(rows)
+    assert np.all(np.diff(rows) > 0), what + ": active rows must ascend"
+    bad = (g ^ o) - fragile
+    assert not bad, "%s: active sets differ on non-fragile rows %s" % (what, sorted(bad)[:10])
+    common = sorted(g & o)
+    if common:
+        gi = np.searchsorted(rows, common)
+        oi = np.searchsorted(ora_rows, common)
+        ok = close(Y[gi], ref.Y[oi])
+        assert ok.all(), "%s: %d values outside tolerance, worst abs %g" % (
+            what, (~ok).sum(), np.abs(Y[gi].astype(np.float64) - ref.Y[oi]).max())
+    return len(common), len(fragile)
+
+
+def config_model(cfg, layers, device=None):
+    c = synth.config(cfg)
+    idx = [synth.gen_layer(c["N"], l, c["seed"], c["window"], device=device) for l in range(layers)]
+    val = [synth.gen_values(c["N"], device=device) for _ in range(layers)]
+    bias = synth.gen_bias(c["N"], c["bias"], device=device)
+    return c, idx, val, bias

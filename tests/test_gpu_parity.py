@@ -1,0 +1,168 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU
+oracle on the same seeded inputs (see parity_util for the bar)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from parity_util import check_against_oracle, close, config_model, gpu_infer
+
+pytestmark = pytest.mark.gpu
+
+
+def rand_model(rng, N, L, distinct=True, sort=True, lo=-0.25, hi=0.5):
+    idx, val = [], []
+    for _ in range(L):
+        if distinct:
+            a = np.stack([rng.choice(N, 32, replace=False) for _ in range(N)])
+        else:
+            a = rng.integers(0, N, size=(N, 32))
+        if sort:
+            a = np.sort(a, axis=1)
+        idx.append(a.astype(np.int32))
+        val.append(rng.uniform(lo, hi, size=(N, 32)).astype(np.float32))
+    bias = -rng.uniform(0.0, 0.3, size=N).astype(np.float32)
+    return idx, val, bias
+
+
+@pytest.mark.parametrize("N,L,batch,distinct,sort", [
+    (32, 3, 5, True, True),        # smallest N, ragged row group
+    (96, 4, 37, True, True),
+    (64, 2, 8, False, False),      # duplicated and unsorted columns
+    (1028, 2, 70, True, True),     # second output block has 4 neurons
+    (2052, 3, 33, True, False),    # three output blocks, unsorted
+    (5000, 2, 9, True, True),      # window wider than one LDS stage
+])
+def test_random_models(N, L, batch, distinct, sort):
+    rng = np.random.default_rng(N * 131 + L)
+    idx, val, bias = rand_model(rng, N, L, distinct, sort)
+    Y0 = rng.uniform(0, 1, size=(batch, N)).astype(np.float32)
+    Y0[batch // 2] = 0
+    ref = oracle.infer(idx, val, bias, Y0)
+    n, rows, Y = gpu_infer(idx, val, bias, Y0)
+    common, _ = check_against_oracle(ref, n, rows, Y, what="random N=%d" % N)
+    assert common > 0
+    if sort and N <= 4096:
+        # same summation order as the oracle: identical bits expected
+        assert np.array_equal(rows, ref.active_rows) and np.array_equal(Y, ref.Y)
+
+
+@pytest.mark.parametrize("layers", [1, 2, 3, 120])
+def test_config0(layers):
+    c, idx, val, bias = config_model(0, layers)
+    Y0 = synth.gen_y0(c["batch"], c["N"], c["seed"])
+    ref = oracle.infer(idx, val, bias, Y0)
+    n, rows, Y = gpu_infer(idx, val, bias, Y0)
+    check_against_oracle(ref, n, rows, Y, what="cfg0 L=%d" % layers)
+    if layers == 1:
+        assert n == 1000
+    if layers == 120:
+        assert n == 0 and ref.n_active == 0
+
+
+@pytest.mark.parametrize("cfg,batch,layers", [(0, 3001, 12), (2, 403, 9), (3, 70, 9), (4, 41, 9)])
+def test_sustained_activity(cfg, batch, layers):
+    """Mixed row densities: part of the rows die in the first layers, the rest
+    saturate at the clip and survive, so compaction sees partial survival."""
+    c, idx, val, bias = config_model(cfg, layers)
+    Y0 = synth.gen_y0(batch, c["N"], c["seed"], density="mixed")
+    ref = oracle.infer(idx, val, bias, Y0)
+    assert 0 < ref.n_active < batch
+    n, rows, Y = gpu_infer(idx, val, bias, Y0)
+    check_against_oracle(ref, n, rows, Y, what="sustained cfg%d" % cfg)
+    assert Y.max() == 32.0
+
+
+@pytest.mark.parametrize("cfg,batch", [(2, 300), (3, 64), (4, 48)])
+@pytest.mark.parametrize("layers", [1, 2])
+def test_config_shapes_first_layers(cfg, batch, layers):
+    c, idx, val, bias = config_model(cfg, layers)
+    Y0 = synth.gen_y0(c["batch"], c["N"], c["seed"], rows=np.arange(batch))
+    ref = oracle.infer(idx, val, bias, Y0)
+    n, rows, Y = gpu_infer(idx, val, bias, Y0)
+    check_against_oracle(ref, n, rows, Y, what="cfg%d L=%d" % (cfg, layers))
+    if layers == 1:
+        assert n == batch
+
+
+def test_identity_and_clip():
+    rng = np.random.default_rng(3)
+    N = 128
+    idx = [rng.integers(0, N, size=(N, 32)).astype(np.int32) for _ in range(2)]
+    val = [np.zeros((N, 32), dtype=np.float32) for _ in range(2)]
+    for a, v in zip(idx, val):
+        slot = rng.integers(0, 32, size=N)
+        a[np.arange(N), slot] = np.arange(N)
+        v[np.arange(N), slot] = 1.0
+    bias = np.zeros(N, dtype=np.float32)
+    Y0 = rng.uniform(-5, 40, size=(11, N)).astype(np.float32)
+    Y0[3] = -2.0
+    n, rows, Y = gpu_infer(idx, val, bias, Y0)
+    expect = np.clip(Y0, 0, 32)
+    keep = np.nonzero((expect > 0).any(1))[0]
+    assert np.array_equal(rows, keep) and np.array_equal(Y, expect[keep])
+
+
+def test_edge_cases():
+    import torch
+    import paper_2007_14152_amd as sp
+    rng = np.random.default_rng(4)
+    N = 64
+    idx, val, bias = rand_model(rng, N, 2, lo=0.0, hi=0.3)
+    m = sp.Model(idx, val, bias)
+    # empty batch
+    n, rows, Y = m.infer(torch.zeros((0, N), device="cuda"))
+    assert n == 0 and rows.numel() == 0
+    # all-zero input: nothing survives
+    n, rows, Y = m.infer(torch.zeros((9, N), device="cuda"))
+    assert n == 0
+    # single row; only the last row alive; same handle reused with shrinking batches
+    Y0 = np.zeros((13, N), dtype=np.float32)
+    Y0[12] = 1.0
+    ref = oracle.infer(idx, val, bias, Y0)
+    for _ in range(2):
+        n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+        check_against_oracle(ref, n, rows, Y, what="last row")
+        assert rows.tolist() == [12]
+    one = np.ones((1, N), dtype=np.float32)
+    ref1 = oracle.infer(idx, val, bias, one)
+    n, rows, Y = gpu_infer(idx, val, bias, one, model=m)
+    check_against_oracle(ref1, n, rows, Y, what="one row")
+    # work arena too small / column out of range
+    need = sp.spdnn_work_bytes(N, 13)
+    w = torch.empty(need, dtype=torch.uint8, device="cuda")
+    y = torch.zeros((13, N), device="cuda")
+    r = torch.zeros(13, dtype=torch.int32, device="cuda")
+    with pytest.raises(sp.SpdnnError) as e:
+        sp.spdnn_infer(m.h, y.data_ptr(), 13, w.data_ptr(), need - 1, r.data_ptr(), 0)
+    assert e.value.code == sp.SPDNN_ESIZE
+    m.close()
+    bad = [a.copy() for a in idx]
+    bad[1][5, 7] = N
+    with pytest.raises(sp.SpdnnError) as e:
+        sp.Model(bad, val, bias)
+    assert e.value.code == sp.SPDNN_EINVAL
+
+
+def test_deterministic_and_device_weights():
+    import torch
+    import paper_2007_14152_amd as sp
+    c, idx, val, bias = config_model(0, 4)
+    Y0 = synth.gen_y0(777, c["N"], c["seed"], density="mixed")
+    a = gpu_infer(idx, val, bias, Y0)
+    b = gpu_infer(idx, val, bias, Y0)
+    assert a[0] == b[0] and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    # weights handed over as device arrays, generated by the torch backend on the GPU
+    _, didx, dval, dbias = config_model(0, 4, device="cuda:0")
+    for h, d in zip(idx, didx):
+        assert np.array_equal(h, d.cpu().numpy())
+    m = sp.Model(didx, dval, dbias)
+    y0 = synth.gen_y0(777, c["N"], c["seed"], density="mixed", device="cuda:0")
+    assert np.array_equal(y0.cpu().numpy(), Y0)
+    n, rows, Y = m.infer(y0)
+    assert n == a[0] and np.array_equal(rows.cpu().numpy(), a[1]) and np.array_equal(Y.cpu().numpy(), a[2])
+    m.set_profiling(True)
+    m.infer(y0)
+    run, rows_in, ms = m.profile()
+    assert run == 4 and rows_in[0] == 777 and np.all(np.diff(rows_in) <= 0) and np.all(ms > 0)
+    m.close()
