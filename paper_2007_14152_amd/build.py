@@ -8,8 +8,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(CSRC, "libspdnn.so")
 SOURCES = [os.path.join(CSRC, "spdnn.hip")]
-HEADERS = [os.path.join(CSRC, "spdnn_kernels.h"),
+HEADERS = [os.path.join(CSRC, "spdnn_kernels.h"), os.path.join(CSRC, "spdnn_order.h"),
            os.path.join(os.path.dirname(_HERE), "include", "spdnn.h")]
+# host build of the connection-ordering routine, for tests of the set-up logic without a GPU
+ORDER_HOST_LIB = os.path.join(CSRC, "libspdnn_order_host.so")
+ORDER_HOST_SRC = os.path.join(CSRC, "spdnn_order_host.cpp")
 
 # Packed-FP32 instructions are switched off for all device code.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -22,6 +25,8 @@ def build(verbose: bool = False, extra=()) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
+    subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", ORDER_HOST_LIB, ORDER_HOST_SRC],
+                   check=True)
     return LIB
 
 

@@ -89,7 +89,7 @@ struct WorkView {
 size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
     size_t o = 0;
     const size_t yb = up((size_t)batch * N * sizeof(float));
-    const size_t lb = up((size_t)batch * sizeof(int));
+    const size_t lb = up(((size_t)batch + 4) * sizeof(int));  // lists are read 4 entries at a time
     for (int i = 0; i < 2; ++i) {
         if (v) v->Y[i] = reinterpret_cast<float*>(base + o);
         o += yb;
@@ -112,7 +112,7 @@ size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
 template <bool MULTI>
 hipError_t allow_big_lds() {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_layer_kernel<MULTI>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * spdnn::kCap * 16);
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)spdnn::tile_pair_bytes(spdnn::kCap));
 }
 
 }  // namespace
@@ -120,6 +120,12 @@ hipError_t allow_big_lds() {
 extern "C" {
 
 const char* spdnn_last_error(void) { return g_err.c_str(); }
+
+#ifdef SPDNN_TIMELINE
+int spdnn_debug_timeline(void* dst) {
+    return hipMemcpyFromSymbol(dst, HIP_SYMBOL(spdnn::spdnn_tl), sizeof(spdnn::spdnn_tl)) == hipSuccess ? 0 : -3;
+}
+#endif
 
 int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes) {
     if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
@@ -187,6 +193,9 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
     m->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     HIP_TRY(allow_big_lds<false>());
     HIP_TRY(allow_big_lds<true>());
+    constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::order_pack_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
                           hipHostMallocDefault));
     for (int i = 0; i < kLag; ++i) HIP_TRY(hipEventCreateWithFlags(&m->lag_ev[i], hipEventDisableTiming));
@@ -230,7 +239,7 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         }
         const LayerDesc& d = m->layers[l];
         spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev);
-        spdnn::pack_weights_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(
+        spdnn::order_pack_kernel<<<nblk, spdnn::kOrderThreads, order_lds, stream>>>(
             di, dv, N, win_dev[l], const_cast<uint16_t*>(d.w.rel), const_cast<float*>(d.w.val));
         HIP_TRY(hipGetLastError());
         if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
@@ -325,7 +334,7 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         Q = std::max(1, std::min(Q, ngroups));
         const int32_t units = (h->nblk / h->G) * Q;
         const int32_t grid = (units + 7) / 8 * 8 * h->G;
-        const size_t lds = (size_t)((d.lds_cols + 7) / 8) * 256;
+        const size_t lds = spdnn::tile_pair_bytes((d.lds_cols + 255) / 256 * 256);  // whole waves of 256 columns
         if (h->profiling) HIP_TRY(hipEventRecord(h->t0[l], s));
         if (d.multi)
             spdnn::fused_layer_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(

@@ -18,6 +18,8 @@
 
 #include <type_traits>
 
+#include "spdnn_order.h"
+
 namespace spdnn {
 
 constexpr int kNnz = 32;     // connections per output neuron
@@ -29,15 +31,57 @@ constexpr float kClip = 32.0f;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Optional per-phase cycle stamps of a few waves of workgroup 0 (development aid,
+// compiled in only with -DSPDNN_TIMELINE).
+#ifdef SPDNN_TIMELINE
+__device__ unsigned long long spdnn_tl[4][64][8];
+#define SPDNN_TL(T_, P_)                                                                     \
+    do {                                                                                     \
+        if (blockIdx.x == SPDNN_TIMELINE && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) % 5 == 0 && (T_) < 64) \
+            spdnn_tl[(threadIdx.x >> 6) / 5][(T_)][(P_)] = clock64();                        \
+    } while (0)
+#else
+#define SPDNN_TL(T_, P_) \
+    do {                 \
+    } while (0)
+#endif
+
 // Byte offset inside the LDS tile pair of stage-local column c, buffer 0.  The two
-// buffers interleave in chunks of 8 columns (128 bytes) so that the second buffer
-// is reached with a constant +128, which fits the instruction's immediate offset.
+// buffers interleave in chunks of 16 columns (256 bytes = one row of the 64 LDS
+// banks), so that a column's 16-byte entry sits in bank quad (c mod 16) in either
+// buffer and the second buffer is reached with a constant +256, which fits the
+// read instruction's immediate offset.
+constexpr int kBufSkew = 256;
 __host__ __device__ inline uint32_t tile_offset(uint32_t c) {
-    return ((c >> 3) << 8) | ((c & 7u) << 4);
+    return ((c >> 4) << 9) | ((c & 15u) << 4);
+}
+// LDS bytes of a tile pair holding `cols` columns.
+__host__ __device__ inline uint32_t tile_pair_bytes(uint32_t cols) { return ((cols + 15u) >> 4) << 9; }
+
+// Lanes of a wave that a 16-byte LDS access serves in the same clock (measured on
+// gfx950 with a pairwise-conflict probe): the wave's 16 quartets of 4 lanes split
+// into four sets, quartets {0,3,5,6}, {1,2,4,7} and the same two shifted by 8.
+// lane_of_group(s, i) = i-th lane (0..15) of set s (0..3) within the wave.
+__host__ __device__ inline int lane_of_group(int s, int i) {
+    const int tbl[2][4] = {{0, 3, 5, 6}, {1, 2, 4, 7}};
+    return (tbl[s & 1][i >> 2] + 8 * (s >> 1)) * 4 + (i & 3);
+}
+
+// Slot (16-byte entry) of stage-local column c inside the LDS tile.  Staging gives
+// lane t of the workgroup columns 4t..4t+3 and writes them with four 16-byte
+// stores; for those stores to be conflict-free the 16 lanes of a set must hit 16
+// different bank quads (slot mod 16) in each store.  Within every span of 128
+// columns (32 lanes) the slot is therefore
+//     set-in-half | column-in-lane | quartet's rank in its set | lane-in-quartet,
+// a permutation of the span; nothing outside the tile code depends on it.
+__host__ __device__ inline uint32_t col_slot(uint32_t c) {
+    const uint32_t a = c & 3u, m = (c >> 2) & 3u, q8 = (c >> 4) & 7u, hi = c >> 7;
+    const uint32_t gr = (0x73261540u >> (4u * q8)) & 7u;  // quartet -> set*4 + rank
+    return (hi << 7) | ((gr >> 2) << 6) | (a << 4) | ((gr & 3u) << 2) | m;
 }
 
 struct LayerWeights {
-    const uint16_t* rel;  // [nblk][32][kBlk] column - c_lo of the block
+    const uint16_t* rel;  // [nblk][32][kBlk] stage << 12 | LDS slot of (column - c_lo) within the stage
     const float* val;     // [nblk][32][kBlk]
     const int2* win;      // [nblk] {c_lo, ncols}, both multiples of 4
 };
@@ -107,7 +151,7 @@ __device__ __forceinline__ void fma_block8(float (&acc)[4], const uint32_t (&o)[
         : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3])
         : [o0] "v"(o[0]), [o1] "v"(o[1]), [o2] "v"(o[2]), [o3] "v"(o[3]), [o4] "v"(o[4]), [o5] "v"(o[5]),
           [o6] "v"(o[6]), [o7] "v"(o[7]), [w0] "v"(w[0]), [w1] "v"(w[1]), [w2] "v"(w[2]), [w3] "v"(w[3]),
-          [w4] "v"(w[4]), [w5] "v"(w[5]), [w6] "v"(w[6]), [w7] "v"(w[7]), [B] "n"(P * 128)
+          [w4] "v"(w[4]), [w5] "v"(w[5]), [w6] "v"(w[6]), [w7] "v"(w[7]), [B] "n"(P * kBufSkew)
         : "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123",
           "v124", "v125", "v126", "v127", "memory");
 #undef SPDNN_FMA4
@@ -174,58 +218,64 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
             if (MULTI)
                 off[k] = (lds_base + tile_offset(rel & (kCap - 1))) | ((rel >> kCapLog2) << 20);
             else
-                off[k] = lds_base + tile_offset(rel);
+                off[k] = lds_base + tile_offset(rel & (kCap - 1));
         }
     }
     const float bj = jok ? bias[j] : 0.0f;
 
     const int T = (g1 - g0) * nstage;  // pipeline steps: (row group, stage) pairs
-    // Staging: lane owns columns tid, tid+1024, tid+2048, tid+3072 of the stage; for
-    // each it fetches the 4 rows (4 coalesced dword loads per row across the wave)
-    // and writes them to LDS as one 16-byte entry.
-    float4 st[4];
-    const uint32_t st_addr = lds_base + tile_offset(tid);  // + i*32768 for column tid + 1024 i
+    // Staging: lane t owns columns 4t..4t+3 of the stage: one 16-byte load per row,
+    // a 4x4 transpose in registers, four 16-byte LDS stores (entry = the 4 rows of
+    // one column).  Waves whose columns lie past the stage's last column skip the
+    // work; inside the last wave, lanes past it re-read the last 4 columns.
+    f32x4 st[kRows];
+    const int wave_col = (tid & ~63) * 4;  // first column of my wave
+    const uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));  // + a*512 for column 4t + a
+    const int cat_last = cat[A - 1];
+    int4 c4 = make_int4(0, 0, 0, 0);  // slots (in Yin) of the 4 rows of the tile to load next
 
+    // cat[] is padded so that the 16-byte read of the last, ragged group stays inside it
+    auto fetch_rows = [&](int t) {
+        const int gi = MULTI ? t / nstage : t;
+        c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + gi) * kRows);
+    };
     auto load_tile = [&](int t) {
         const int gi = MULTI ? t / nstage : t;
         const int s = MULTI ? t - gi * nstage : 0;
-        const float* rowp[kRows];
-#pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            const int row = min((g0 + gi) * kRows + r, A - 1);
-            rowp[r] = Yin + (size_t)cat[row] * N + c_lo + s * kCap;
-        }
-        const int left = ncols - s * kCap;  // columns in this stage (may exceed kCap)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int c = tid + i * kBlk;
-            if (c < left) {
-                st[i].x = rowp[0][c];
-                st[i].y = rowp[1][c];
-                st[i].z = rowp[2][c];
-                st[i].w = rowp[3][c];
-            }
-        }
+        const int left = ncols - s * kCap;  // columns in this stage (a multiple of 4, may exceed kCap)
+        if (wave_col >= left) return;
+        const int row0 = (g0 + gi) * kRows;
+        const size_t coff = (size_t)c_lo + (size_t)s * kCap + (size_t)min(4 * tid, left - 4);
+        st[0] = *reinterpret_cast<const f32x4*>(Yin + (size_t)c4.x * N + coff);
+        st[1] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N + coff);
+        st[2] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N + coff);
+        st[3] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N + coff);
     };
     auto store_tile = [&](int P, int t) {
         const int gi = MULTI ? t / nstage : t;
         const int s = MULTI ? t - gi * nstage : 0;
         const int left = ncols - s * kCap;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int c = tid + i * kBlk;
-            if (c < left)
-                *reinterpret_cast<__attribute__((address_space(3))) f32x4*>(st_addr + i * 32768 + P * 128) =
-                    f32x4{st[i].x, st[i].y, st[i].z, st[i].w};
-        }
+        if (wave_col >= left) return;
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        // The loads of this tile were issued a step ago.  Pin the point where their
+        // results are first touched, otherwise the register shuffles of the transpose
+        // are scheduled right behind the loads and every load turns synchronous.
+        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
+        *reinterpret_cast<lds_f4*>(st_addr + 0 * 512 + P * kBufSkew) = f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
+        *reinterpret_cast<lds_f4*>(st_addr + 1 * 512 + P * kBufSkew) = f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
+        *reinterpret_cast<lds_f4*>(st_addr + 2 * 512 + P * kBufSkew) = f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
+        *reinterpret_cast<lds_f4*>(st_addr + 3 * 512 + P * kBufSkew) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
     };
 
     float acc[kRows] = {0.f, 0.f, 0.f, 0.f};
 
-    auto compute = [&](auto Ptag, int s) {
+    // connections kbeg .. kbeg+15 of the tile in buffer P
+    auto compute = [&](auto Ptag, int s, auto Ktag) {
         constexpr int P = decltype(Ptag)::value;
+        constexpr int kbeg = decltype(Ktag)::value;
 #pragma unroll
-        for (int k0 = 0; k0 < kNnz; k0 += 8) {
+        for (int kk = 0; kk < 16; kk += 8) {
+            const int k0 = kbeg + kk;
             uint32_t o[8];
             float v[8];
 #pragma unroll
@@ -236,7 +286,7 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
                     // a connection outside this stage reads column 0 of the stage (always
                     // loaded) with weight 0: adds exactly 0 for finite features
                     const bool mine = (int)(o[i] >> 20) == s;
-                    o[i] = mine ? (o[i] & 0xFFFFFu) : lds_base;
+                    o[i] = mine ? (o[i] & 0xFFFFFu) : lds_base + tile_offset(col_slot(0));
                     v[i] = mine ? v[i] : 0.0f;
                 }
             }
@@ -244,37 +294,83 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         }
     };
 
+    const int lane = tid & 63;
+    // Exchange between lanes l and l^1 / l^2 of a quartet (DPP quad permutes).
+    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
+    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
+    const bool b0 = lane & 1, b1 = lane & 2;
     auto epilogue = [&](int g) {
-#pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            const int row = g * kRows + r;
-            const float z = acc[r] + bj;
-            const float y = fminf(fmaxf(z, 0.0f), kClip);
-            const bool live = jok && row < A;
-            if (live) Yout[(size_t)row * N + j] = y;
-            const unsigned long long m = __ballot(live && y > 0.0f);
-            if (m != 0ull && (tid & 63) == 0) flags[row] = 1;
-            acc[r] = 0.0f;
+        const int row0 = g * kRows;
+        const int nlive = min(kRows, A - row0);  // rows of this group that exist (>= 1)
+        float y0 = fminf(fmaxf(acc[0] + bj, 0.0f), kClip);
+        float y1 = fminf(fmaxf(acc[1] + bj, 0.0f), kClip);
+        float y2 = fminf(fmaxf(acc[2] + bj, 0.0f), kClip);
+        float y3 = fminf(fmaxf(acc[3] + bj, 0.0f), kClip);
+        acc[0] = acc[1] = acc[2] = acc[3] = 0.0f;
+        // row r has a positive output in this wave -> lane r raises the row's flag
+        const unsigned long long m0 = __ballot(jok && y0 > 0.0f);
+        const unsigned long long m1 = __ballot(jok && y1 > 0.0f);
+        const unsigned long long m2 = __ballot(jok && y2 > 0.0f);
+        const unsigned long long m3 = __ballot(jok && y3 > 0.0f);
+        const unsigned long long mine = lane == 0 ? m0 : lane == 1 ? m1 : lane == 2 ? m2 : m3;
+        if (lane < nlive && mine != 0ull) flags[row0 + lane] = 1;
+        // 4x4 transpose inside each quartet: lane 4q+i holds rows 0..3 of neuron 4q+i and
+        // ends up with row i of neurons 4q..4q+3, which is one 16-byte store.
+        {
+            const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
+            const float r0 = xor2(s0), r1 = xor2(s1);
+            y0 = b1 ? r0 : y0;
+            y1 = b1 ? r1 : y1;
+            y2 = b1 ? y2 : r0;
+            y3 = b1 ? y3 : r1;
         }
+        {
+            const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
+            const float r0 = xor1(s0), r1 = xor1(s1);
+            y0 = b0 ? r0 : y0;
+            y1 = b0 ? y1 : r0;
+            y2 = b0 ? r1 : y2;
+            y3 = b0 ? y3 : r1;
+        }
+        const int r = lane & 3;
+        if (jok && r < nlive)
+            *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
     };
 
-    // One pipeline step with compile-time buffer index P.
+    // One pipeline step with compile-time buffer index P.  On entry tile t is in
+    // buffer P and the registers st hold tile t+1 (or its loads are in flight).
+    // Half way through, tile t+1 goes to the other buffer -- nobody reads that one
+    // before the barrier below -- and the loads of tile t+2 are issued, so they have
+    // a whole step to land and the barrier never waits for global memory.
     auto step = [&](int t, auto Ptag) {
         constexpr int P = decltype(Ptag)::value;
-        const bool more = t + 1 < T;
-        if (more) load_tile(t + 1);
         const int gi = MULTI ? t / nstage : t;
         const int s = MULTI ? t - gi * nstage : 0;
-        compute(Ptag, s);
+        SPDNN_TL(t, 0);
+        if (t + 2 < T) fetch_rows(t + 2);
+        compute(Ptag, s, std::integral_constant<int, 0>{});
+        SPDNN_TL(t, 1);
+        if (t + 1 < T) store_tile(P ^ 1, t + 1);
+        SPDNN_TL(t, 2);
+        if (t + 2 < T) load_tile(t + 2);
+        SPDNN_TL(t, 3);
+        compute(Ptag, s, std::integral_constant<int, 16>{});
+        SPDNN_TL(t, 4);
         if (s == nstage - 1) epilogue(g0 + gi);
-        if (more) store_tile(P ^ 1, t + 1);
+        SPDNN_TL(t, 5);
         __syncthreads();
+        SPDNN_TL(t, 6);
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
 
+    fetch_rows(0);
     load_tile(0);
     store_tile(0, 0);
+    if (T > 1) {
+        fetch_rows(1);
+        load_tile(1);
+    }
     __syncthreads();
     int t = 0;
     for (; t + 1 < T; t += 2) {
@@ -400,29 +496,50 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
     }
 }
 
-__global__ __launch_bounds__(kBlk) void pack_weights_kernel(const int32_t* __restrict__ idx,
-                                                            const float* __restrict__ val, int N,
-                                                            const int2* __restrict__ win,
-                                                            uint16_t* __restrict__ rel,
-                                                            float* __restrict__ wval) {
-    const int tid = threadIdx.x;
+// One thread per set of 16 neurons whose lanes are served together (64 threads =
+// one output block of 16 waves x 4 sets): orders the set's connections for
+// conflict-free LDS reads (spdnn_order.h) and writes them lane-major: entry
+// (block b, step s, lane t) holds the LDS slot of the connection's column (plus
+// the stage number in bits 12 and up) and its weight, for the connection lane t
+// uses at step s.
+constexpr int kOrderThreads = kBlk / kGroup;
+__global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t* __restrict__ idx,
+                                                                   const float* __restrict__ val, int N,
+                                                                   const int2* __restrict__ win,
+                                                                   uint16_t* __restrict__ rel,
+                                                                   float* __restrict__ wval) {
+    extern __shared__ OrderScratch order_scratch[];
     const int b = blockIdx.x;
-    const int j = b * kBlk + tid;
+    const int t = threadIdx.x;
+    const int wave0 = (t >> 2) * 64;  // first lane of this thread's wave inside the block
+    const int set = t & 3;
     const int c_lo = win[b].x;
-    for (int k = 0; k < kNnz; ++k) {
-        const size_t e = ((size_t)b * kNnz + k) * kBlk + tid;
-        int c = c_lo;
-        float v = 0.0f;
-        if (j < N) {
-            c = idx[(size_t)j * kNnz + k];
-            v = val[(size_t)j * kNnz + k];
-            if (c < 0 || c >= N) {  // reported by block_window_kernel; keep the copy in range
-                c = c_lo;
-                v = 0.0f;
-            }
+    auto neuron = [&](int l) -> int { return b * kBlk + wave0 + lane_of_group(set, l); };
+    auto column = [&](int l, int k) -> int {  // out-of-range columns were reported; keep them harmless
+        const int c = idx[(size_t)neuron(l) * kNnz + k];
+        return (c < 0 || c >= N) ? c_lo : c;
+    };
+    order_group(
+        order_scratch[t],
+        [&](int l, int k) -> unsigned {
+            return (neuron(l) < N) ? (col_slot((uint32_t)(column(l, k) - c_lo) & (kCap - 1)) & 15u) : 255u;
+        },
+        [&](int l, int step, int k) {
+            const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
+            const size_t src = (size_t)neuron(l) * kNnz + k;
+            const int c = idx[src];
+            const bool ok = c >= 0 && c < N;
+            const uint32_t r = ok ? (uint32_t)(c - c_lo) : 0u;  // stage number | slot inside the stage
+            rel[e] = (uint16_t)((r & ~(uint32_t)(kCap - 1)) | col_slot(r & (kCap - 1)));
+            wval[e] = ok ? val[src] : 0.0f;
+        });
+    for (int l = 0; l < kGroup; ++l) {
+        if (neuron(l) < N) continue;
+        for (int step = 0; step < kNnz; ++step) {  // lanes past the last neuron: weight 0 on column c_lo
+            const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
+            rel[e] = (uint16_t)col_slot(0);
+            wval[e] = 0.0f;
         }
-        rel[e] = (uint16_t)(c - c_lo);
-        wval[e] = v;
     }
 }
 

@@ -1,0 +1,199 @@
+// Bank-aware ordering of each output neuron's 32 connections (part of the weight
+// set-up, a0).  Plain C++ usable on the host and in device code.
+//
+// Why.  In the fused kernel lane = output neuron and step k of a tile makes every
+// lane read the 16-byte LDS entry of its k-th connection's column.  gfx950 serves
+// 16 lanes of a ds_read_b128 per clock from 64 four-byte banks, i.e. from 16
+// "quads" of 16 bytes; two lanes of the same 16-lane group whose entries fall in
+// the same quad (column mod 16 here) serialise.  The sum over a neuron's
+// connections does not depend on their order, so each group of 16 neighbouring
+// neurons gets its connections re-ordered such that in every step the 16 lanes
+// touch 16 different quads whenever possible.  This plays the role the transposed
+// sliced-ELL of Section III-A-3 plays for coalescing weight reads: a layout
+// decision made once, before inference.
+//
+// How.  32 rounds, one per step.  In each round a maximum bipartite matching
+// lanes <-> quads is built (augmenting paths), quads being offered in priority
+// order: first those whose remaining connections equal or exceed the remaining
+// steps (they must be served now or cost an extra cycle later), then by remaining
+// count.  A lane left unmatched takes a connection from the quad that is least
+// loaded in this round.  Cost = sum over rounds of the largest quad
+// multiplicity; the lower bound is max(32, busiest quad's total).
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define SPDNN_HD __host__ __device__
+#else
+#define SPDNN_HD
+#endif
+
+namespace spdnn {
+
+constexpr int kGroup = 16;  // lanes served per clock by a 16-byte LDS read = quads per 256-byte bank row
+
+// Working memory of one group (1088 bytes).  On the device it lives in LDS.
+struct OrderScratch {
+    uint8_t cnt[kGroup][16];   // connections of lane l still unplaced, per quad
+    uint8_t end[kGroup][16];   // end of quad q's bucket in sorted[l]
+    uint8_t sorted[kGroup][32];  // lane l's connection numbers, bucketed by quad
+    uint16_t adj[16];          // adj[q]: lanes that still have a connection in quad q
+    uint16_t remq[16];         // connections still unplaced in quad q over the whole group
+};
+
+SPDNN_HD inline unsigned nib_get(uint64_t w, int i) { return (unsigned)(w >> (4 * i)) & 15u; }
+SPDNN_HD inline uint64_t nib_set(uint64_t w, int i, unsigned v) {
+    return (w & ~(15ull << (4 * i))) | ((uint64_t)(v & 15u) << (4 * i));
+}
+SPDNN_HD inline int ctz16(unsigned m) {
+    int n = 0;
+    while (!(m & 1u)) {
+        m >>= 1;
+        ++n;
+    }
+    return n;
+}
+
+// quad_of(l, k): quad (0..15) of connection k of lane l, or 255 if lane l has no such
+// connection (lane beyond the last neuron).  emit(l, step, k): connection k of lane l is
+// placed at step `step`.  Every existing connection is emitted exactly once and every
+// lane gets one connection per step.
+template <typename QuadOf, typename Emit>
+SPDNN_HD inline void order_group(OrderScratch& S, QuadOf quad_of, Emit emit) {
+    uint16_t* adj = S.adj;
+    uint16_t* remq = S.remq;
+    for (int q = 0; q < 16; ++q) {
+        adj[q] = 0;
+        remq[q] = 0;
+    }
+    unsigned live = 0;  // lanes that have connections at all
+    for (int l = 0; l < kGroup; ++l) {
+        for (int q = 0; q < 16; ++q) S.cnt[l][q] = 0;
+        for (int k = 0; k < 32; ++k) {
+            const unsigned q = quad_of(l, k);
+            if (q < 16) S.cnt[l][q]++;
+        }
+        unsigned run = 0;
+        for (int q = 0; q < 16; ++q) {
+            run += S.cnt[l][q];
+            S.end[l][q] = (uint8_t)run;
+            if (S.cnt[l][q]) adj[q] |= (uint16_t)(1u << l);
+            remq[q] += S.cnt[l][q];
+        }
+        if (run) live |= 1u << l;
+        // counting sort of the connection numbers by quad (stable)
+        uint8_t fill[16];
+        for (int q = 0; q < 16; ++q) fill[q] = (uint8_t)(S.end[l][q] - S.cnt[l][q]);
+        for (int k = 0; k < 32; ++k) {
+            const unsigned q = quad_of(l, k);
+            if (q < 16) S.sorted[l][fill[q]++] = (uint8_t)k;
+        }
+    }
+    for (int step = 0; step < 32; ++step) {
+        const int left = 32 - step;
+        uint64_t lane_of = 0, quad_of_l = 0, par = 0;  // nibble arrays
+        unsigned mq = 0, ml = 0;                        // matched quads / lanes
+        unsigned done = 0;                              // quads already offered
+        for (int r = 0; r < 16; ++r) {
+            // next quad by priority
+            int q0 = -1;
+            int best = -1;
+            for (int q = 0; q < 16; ++q) {
+                if ((done >> q) & 1u) continue;
+                const int key = (remq[q] >= left ? 4096 : 0) + remq[q];
+                if (key > best) {
+                    best = key;
+                    q0 = q;
+                }
+            }
+            done |= 1u << q0;
+            if (remq[q0] == 0) break;  // the rest are empty too
+            // breadth-first search for an augmenting path from q0 to a free lane
+            uint64_t queue = (uint64_t)q0;
+            int head = 0, tail = 1;
+            unsigned seen = 0;
+            int found = -1;
+            while (head < tail && found < 0) {
+                const int q = (int)nib_get(queue, head++);
+                unsigned cand = adj[q] & ~seen;
+                while (cand) {
+                    const int l = ctz16(cand);
+                    cand &= cand - 1;
+                    seen |= 1u << l;
+                    par = nib_set(par, l, (unsigned)q);
+                    if (!((ml >> l) & 1u)) {
+                        found = l;
+                        break;
+                    }
+                    queue = nib_set(queue, tail++, nib_get(quad_of_l, l));
+                }
+            }
+            if (found < 0) continue;
+            int cur = found;
+            for (;;) {
+                const int q = (int)nib_get(par, cur);
+                const int next = (int)nib_get(lane_of, q);  // meaningful only if q was matched
+                lane_of = nib_set(lane_of, q, (unsigned)cur);
+                quad_of_l = nib_set(quad_of_l, cur, (unsigned)q);
+                ml |= 1u << cur;
+                const bool first = (q == q0);
+                mq |= 1u << q;
+                if (first) break;
+                cur = next;
+            }
+        }
+        // lanes without a quad of their own share the least loaded one they can use
+        uint64_t mult = 0;  // nibble: uses of quad q in this step (saturates at 15)
+        for (int l = 0; l < kGroup; ++l)
+            if ((ml >> l) & 1u) {
+                const int q = (int)nib_get(quad_of_l, l);
+                mult = nib_set(mult, q, nib_get(mult, q) + 1);
+            }
+        for (int l = 0; l < kGroup; ++l) {
+            if (!((live >> l) & 1u) || ((ml >> l) & 1u)) continue;
+            int bq = -1;
+            int bkey = 1 << 30;
+            for (int q = 0; q < 16; ++q) {
+                if (!S.cnt[l][q]) continue;
+                const int key = (int)nib_get(mult, q) * 65536 - ((int)remq[q] - left) * 64 - (int)S.cnt[l][q];
+                if (key < bkey) {
+                    bkey = key;
+                    bq = q;
+                }
+            }
+            quad_of_l = nib_set(quad_of_l, l, (unsigned)bq);
+            ml |= 1u << l;
+            const unsigned m = nib_get(mult, bq);
+            mult = nib_set(mult, bq, m < 15 ? m + 1 : 15);
+        }
+        // place the chosen connections
+        for (int l = 0; l < kGroup; ++l) {
+            if (!((live >> l) & 1u)) continue;
+            const int q = (int)nib_get(quad_of_l, l);
+            const int k = S.sorted[l][S.end[l][q] - S.cnt[l][q]];
+            S.cnt[l][q]--;
+            remq[q]--;
+            if (!S.cnt[l][q]) adj[q] &= (uint16_t)~(1u << l);
+            emit(l, step, k);
+        }
+    }
+}
+
+// Cost model used by tests: LDS cycles of one group's 32 steps (largest quad
+// multiplicity per step, summed).  quad_at(l, step) as placed.
+template <typename QuadAt>
+SPDNN_HD inline int order_cost(QuadAt quad_at) {
+    int total = 0;
+    for (int step = 0; step < 32; ++step) {
+        int m[16] = {0};
+        int mx = 0;
+        for (int l = 0; l < kGroup; ++l) {
+            const unsigned q = quad_at(l, step);
+            if (q < 16 && ++m[q] > mx) mx = m[q];
+        }
+        total += mx;
+    }
+    return total;
+}
+
+}  // namespace spdnn
