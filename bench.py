@@ -28,7 +28,20 @@ def parse():
     ap.add_argument("--density", default=None, help="'mixed' = sustained-activity variant (ours)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-gib", type=float, default=0.0,
+                    help="also run a plain device copy of this many GiB (calibrates rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
+
+
+def measured_traffic(workload_key):
+    """HBM bytes per fused-layer launch from the committed rocprofv3 counter summary
+    (profiles/), if it was taken on this workload; else None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        t = json.load(open(path)).get(workload_key)
+        return float(t["hbm_bytes_per_launch"]) if t else None
+    except Exception:
+        return None
 
 
 def algorithmic_bytes(rows, N):
@@ -94,6 +107,15 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
 
+    if a.copy_probe_gib > 0:
+        n = int(a.copy_probe_gib * (1 << 30)) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            sp.spdnn_copy_probe(dst.data_ptr(), src.data_ptr(), n * 4, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(a.warmup):
         model.infer(y0, want_Y=False)
     model.set_profiling(True)
@@ -131,7 +153,8 @@ def main():
             "n_active_final": int(n_active), "executed_TeraEdges_per_s": executed * a.steps / dt / 1e12,
             "setup_s": t_setup},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic("cfg%d_L%d_batch%d_%s" % (a.config, L, batch, density)),
                      "kernel": "fused_layer_kernel", "launches": int(launches),
                      "avg_launch_ms": sum_ms / max(launches, 1),
                      "algorithmic_bytes_per_launch": sum_bytes / max(launches, 1)},

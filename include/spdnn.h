@@ -107,6 +107,11 @@ int spdnn_set_profiling(spdnn_t h, int32_t on);
 int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows_in,
                       float* fused_ms);
 
+/* Measurement aid: enqueue a plain device-to-device copy kernel of `bytes` bytes (a multiple
+ * of 16; both pointers 16-byte aligned, device memory) on the given stream.  It reads and
+ * writes exactly `bytes` each, which calibrates profiler traffic counters. */
+int spdnn_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ SPDNN_HOST = 0
 SPDNN_DEVICE = 1
 
 EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
-           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile")
+           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_copy_probe")
 
 
 class SpdnnError(RuntimeError):
@@ -51,6 +51,7 @@ def lib():
         L.spdnn_last_error.restype = ctypes.c_char_p
         L.spdnn_set_profiling.argtypes = [vp, i32]
         L.spdnn_get_profile.argtypes = [vp, i32, ctypes.POINTER(i32), vp, vp]
+        L.spdnn_copy_probe.argtypes = [vp, vp, sz, vp]
         for n in EXPORTS:
             if n != "spdnn_last_error":
                 getattr(L, n).restype = ctypes.c_int
@@ -117,6 +118,11 @@ def spdnn_get_profile(h, cap: int):
     _check(lib().spdnn_get_profile(ctypes.c_void_p(h), cap, ctypes.byref(run), rows.ctypes.data, ms.ctypes.data))
     n = min(cap, run.value)
     return run.value, rows[:n], ms[:n]
+
+
+def spdnn_copy_probe(dst_ptr, src_ptr, nbytes, stream=0) -> None:
+    _check(lib().spdnn_copy_probe(ctypes.c_void_p(int(dst_ptr)), ctypes.c_void_p(int(src_ptr)), nbytes,
+                                  ctypes.c_void_p(int(stream))))
 
 
 class Model:

@@ -127,6 +127,17 @@ int spdnn_debug_timeline(void* dst) {
 }
 #endif
 
+int spdnn_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream) {
+    if (!dst_dev || !src_dev || bytes % 16 || reinterpret_cast<uintptr_t>(dst_dev) % 16 ||
+        reinterpret_cast<uintptr_t>(src_dev) % 16)
+        return fail(SPDNN_EINVAL, "copy probe needs non-null 16-byte aligned buffers and a multiple of 16 bytes");
+    if (bytes == 0) return SPDNN_OK;
+    spdnn::copy_probe_kernel<<<8192, 256, 0, reinterpret_cast<hipStream_t>(hip_stream)>>>(
+        static_cast<const float4*>(src_dev), static_cast<float4*>(dst_dev), bytes / 16);
+    HIP_TRY(hipGetLastError());
+    return SPDNN_OK;
+}
+
 int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes) {
     if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
     if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");

@@ -308,12 +308,13 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         float y3 = fminf(fmaxf(acc[3] + bj, 0.0f), kClip);
         acc[0] = acc[1] = acc[2] = acc[3] = 0.0f;
         // row r has a positive output in this wave -> lane r raises the row's flag
-        const unsigned long long m0 = __ballot(jok && y0 > 0.0f);
-        const unsigned long long m1 = __ballot(jok && y1 > 0.0f);
-        const unsigned long long m2 = __ballot(jok && y2 > 0.0f);
-        const unsigned long long m3 = __ballot(jok && y3 > 0.0f);
-        const unsigned long long mine = lane == 0 ? m0 : lane == 1 ? m1 : lane == 2 ? m2 : m3;
-        if (lane < nlive && mine != 0ull) flags[row0 + lane] = 1;
+        // (lanes past the last neuron have zero weights and zero bias, so their y is 0)
+        const unsigned pos = (__builtin_amdgcn_ballot_w64(y0 > 0.0f) != 0ull ? 1u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
+        if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;
+#ifdef SPDNN_TRANSPOSED_STORES
         // 4x4 transpose inside each quartet: lane 4q+i holds rows 0..3 of neuron 4q+i and
         // ends up with row i of neurons 4q..4q+3, which is one 16-byte store.
         {
@@ -335,6 +336,16 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         const int r = lane & 3;
         if (jok && r < nlive)
             *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
+#else
+        // one 4-byte store per row: the wave writes 256 contiguous bytes of each row
+        if (jok) {
+            float* dst = Yout + (size_t)row0 * N + j;
+            dst[0] = y0;
+            if (nlive > 1) dst[(size_t)N] = y1;
+            if (nlive > 2) dst[2 * (size_t)N] = y2;
+            if (nlive > 3) dst[3 * (size_t)N] = y3;
+        }
+#endif
     };
 
     // One pipeline step with compile-time buffer index P.  On entry tile t is in
@@ -541,6 +552,13 @@ __global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t
             wval[e] = 0.0f;
         }
     }
+}
+
+// Plain copy, 16 bytes per lane and iteration: a traffic yardstick for profiler
+// counters (known bytes in, known bytes out).
+__global__ void copy_probe_kernel(const float4* __restrict__ src, float4* __restrict__ dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
 }
 
 }  // namespace spdnn
