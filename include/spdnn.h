@@ -45,8 +45,25 @@ enum {
 enum { SPDNN_HOST = 0, SPDNN_DEVICE = 1 }; /* where the arrays given to spdnn_create live */
 
 /* Bytes of device memory spdnn_create needs for a model of L layers of N neurons
- * (re-laid weights of all layers, bias, and staging for one raw layer). */
+ * (re-laid weights of all layers, bias, and staging for one raw layer), whatever the
+ * sparsity patterns are.  Patterns whose 1024-neuron blocks each touch a narrow range of
+ * input columns need less: see spdnn_weights_bytes_for_window. */
 int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes);
+
+/* Same, for a model in which the input columns used by any block of 1024 consecutive
+ * output neurons span at most widest_window columns (as spdnn_scan_windows reports).  The
+ * tiling of Section III-A-2 stages a block's column range through LDS 4096 columns at a
+ * time; ranges of 3 or more stages use a larger weight layout, which this accounts for.
+ * spdnn_create accepts any arena of at least this size; with a smaller one than
+ * spdnn_weights_bytes says it still works for every pattern, but layers with wider ranges
+ * than the arena was sized for run a slower kernel. */
+int spdnn_weights_bytes_for_window(int32_t N, int32_t L, int32_t widest_window, size_t* bytes);
+
+/* Widest column range (in columns) of any 1024-neuron block of any layer.  idx as for
+ * spdnn_create.  scratch_dev: device memory, 256-byte aligned, at least N*32*4 + 2*N/128 +
+ * 1024 bytes, contents scratch.  Blocks until done.  SPDNN_EINVAL on a column outside [0, N). */
+int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t where, void* scratch_dev,
+                       size_t scratch_bytes, void* hip_stream, int32_t* widest_window);
 
 /* Bytes of device memory spdnn_infer needs for up to max_batch rows: two feature
  * maps of max_batch x N floats (the ping-pong pair of Listing 1) plus row lists
@@ -64,8 +81,9 @@ int spdnn_work_bytes(int32_t N, int32_t max_batch, size_t* bytes);
  *   bias     : N floats (host or device as `where` says), one per output neuron, the
  *              same for every layer (Listings 1 and 2 index it by output neuron);
  *              every entry must be <= 0.
- *   weights_arena : device memory, 256-byte aligned, >= spdnn_weights_bytes(N, L); owned
- *              by the caller, used by the handle until spdnn_destroy.
+ *   weights_arena : device memory, 256-byte aligned, >= spdnn_weights_bytes(N, L) or
+ *              >= spdnn_weights_bytes_for_window(N, L, w) for the model's widest window w;
+ *              owned by the caller, used by the handle until spdnn_destroy.
  *   hip_stream : a hipStream_t (NULL = default stream) on which create and infer enqueue.
  * On failure *out is NULL. */
 int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx,

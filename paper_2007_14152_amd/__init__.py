@@ -23,7 +23,8 @@ SPDNN_HOST = 0
 SPDNN_DEVICE = 1
 
 EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
-           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_copy_probe")
+           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_copy_probe",
+           "spdnn_weights_bytes_for_window", "spdnn_scan_windows")
 
 
 class SpdnnError(RuntimeError):
@@ -52,6 +53,8 @@ def lib():
         L.spdnn_set_profiling.argtypes = [vp, i32]
         L.spdnn_get_profile.argtypes = [vp, i32, ctypes.POINTER(i32), vp, vp]
         L.spdnn_copy_probe.argtypes = [vp, vp, sz, vp]
+        L.spdnn_weights_bytes_for_window.argtypes = [i32, i32, i32, ctypes.POINTER(sz)]
+        L.spdnn_scan_windows.argtypes = [i32, i32, ctypes.POINTER(vp), i32, vp, sz, vp, ctypes.POINTER(i32)]
         for n in EXPORTS:
             if n != "spdnn_last_error":
                 getattr(L, n).restype = ctypes.c_int
@@ -72,6 +75,20 @@ def spdnn_weights_bytes(N: int, L: int) -> int:
     out = ctypes.c_size_t(0)
     _check(lib().spdnn_weights_bytes(N, L, ctypes.byref(out)))
     return out.value
+
+
+def spdnn_weights_bytes_for_window(N: int, L: int, widest_window: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().spdnn_weights_bytes_for_window(N, L, widest_window, ctypes.byref(out)))
+    return out.value
+
+
+def spdnn_scan_windows(N, L, idx_ptrs, where, scratch_ptr, scratch_bytes, stream=0) -> int:
+    ip = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in idx_ptrs])
+    w = ctypes.c_int32(0)
+    _check(lib().spdnn_scan_windows(N, L, ip, where, ctypes.c_void_p(int(scratch_ptr)), scratch_bytes,
+                                    ctypes.c_void_p(int(stream)), ctypes.byref(w)))
+    return w.value
 
 
 def spdnn_work_bytes(N: int, max_batch: int) -> int:
@@ -132,7 +149,7 @@ class Model:
     (copied through the host path) or CUDA torch tensors (device path); bias: [N].
     """
 
-    def __init__(self, idx, val, bias, device="cuda:0", stream=None):
+    def __init__(self, idx, val, bias, device="cuda:0", stream=None, window_hint=None):
         import numpy as np
         import torch
         self.torch = torch
@@ -161,11 +178,16 @@ class Model:
         for a, v in zip(idx, val):
             assert tuple(a.shape) == (N, 32) and tuple(v.shape) == (N, 32)
         keep += [idx, val, b]
-        nbytes = spdnn_weights_bytes(N, L)
         with torch.cuda.device(self.device):
-            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
             s = stream if stream is not None else torch.cuda.current_stream(self.device)
             self.stream = s
+            # size the arena for the patterns' widest column window instead of the worst case
+            scratch = torch.empty(N * 32 * 4 + 2 * N // 128 + 4096, dtype=torch.uint8, device=self.device)
+            self.widest_window = spdnn_scan_windows(N, L, ip, where, scratch.data_ptr(), scratch.numel(),
+                                                    s.cuda_stream)
+            del scratch
+            nbytes = spdnn_weights_bytes_for_window(N, L, window_hint or self.widest_window)
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
             self.h = spdnn_create(N, L, ip, vp, bp, where, self.arena.data_ptr(), nbytes, s.cuda_stream)
         self.work = None
         del keep

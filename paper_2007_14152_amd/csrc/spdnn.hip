@@ -42,9 +42,11 @@ inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 constexpr int kLag = 2;  // the host runs at most this many layers ahead of the GPU
 
+enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2 };
 struct LayerDesc {
     spdnn::LayerWeights w;
-    int multi;     // some block's window is wider than one LDS stage
+    spdnn::WideWeights ww;
+    int mode;      // kSingle: every window fits one LDS stage; kStaged: 2 stages (or fallback); kWide: 3+ stages
     int lds_cols;  // columns the LDS tile must hold for this layer
 };
 
@@ -74,9 +76,23 @@ size_t layer_bytes(int32_t nblk) {
     const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
     return up((size_t)nblk * sizeof(int2)) + up(e * sizeof(uint16_t)) + up(e * sizeof(float));
 }
-size_t staging_bytes(int32_t N) {
+int stages_of(int32_t window) { return (window + spdnn::kCap - 1) / spdnn::kCap; }
+// extra bytes per layer for the wide format with up to `nstage` stages (0 if not needed)
+size_t wide_bytes(int32_t nblk, int nstage) {
+    if (nstage < 3) return 0;
+    const size_t e = (size_t)nblk * nstage * spdnn::wide_steps(nstage) * spdnn::kBlk;
+    const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
+    return up(e * sizeof(uint16_t)) + up(e * sizeof(float)) + up((size_t)nblk * nstage * 16) +
+           up(sp * sizeof(uint16_t)) + up(sp * sizeof(float)) + up((size_t)nblk * 16);
+}
+size_t staging_bytes(int32_t N, int32_t L) {
     return up((size_t)N * spdnn::kNnz * sizeof(int32_t)) + up((size_t)N * spdnn::kNnz * sizeof(float)) +
-           up(sizeof(int));
+           up(sizeof(int) * (size_t)(2 * L + 1));  // error flag, per-layer stage counts, per-layer wide failures
+}
+size_t arena_bytes_for(int32_t N, int32_t L, int nstage_cap) {
+    const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
+    return up((size_t)N * sizeof(float)) + (size_t)L * (layer_bytes(nblk) + wide_bytes(nblk, nstage_cap)) +
+           staging_bytes(N, L);
 }
 
 struct WorkView {
@@ -141,8 +157,54 @@ int spdnn_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* hip
 int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes) {
     if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
     if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+    *bytes = arena_bytes_for(N, L, stages_of(N));
+    return SPDNN_OK;
+}
+
+int spdnn_weights_bytes_for_window(int32_t N, int32_t L, int32_t widest_window, size_t* bytes) {
+    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
+    if (!valid_n(N) || L < 1 || widest_window < 1)
+        return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1, widest_window >= 1");
+    *bytes = arena_bytes_for(N, L, stages_of(std::min(widest_window, N)));
+    return SPDNN_OK;
+}
+
+int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t where, void* scratch_dev,
+                       size_t scratch_bytes, void* hip_stream, int32_t* widest_window) {
+    if (!widest_window) return fail(SPDNN_EINVAL, "widest_window is NULL");
+    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+    if (!idx || !scratch_dev) return fail(SPDNN_EINVAL, "null argument");
+    if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
-    *bytes = up((size_t)N * sizeof(float)) + (size_t)L * layer_bytes(nblk) + staging_bytes(N);
+    const size_t raw = up((size_t)N * spdnn::kNnz * sizeof(int32_t));
+    const size_t need = raw + up((size_t)nblk * sizeof(int2)) + up(sizeof(int));
+    if (scratch_bytes < need) return fail(SPDNN_ESIZE, "scan scratch has %zu bytes, %zu needed", scratch_bytes, need);
+    if (reinterpret_cast<uintptr_t>(scratch_dev) % kAlign) return fail(SPDNN_EINVAL, "scratch must be 256-byte aligned");
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    char* base = static_cast<char*>(scratch_dev);
+    int32_t* st_idx = reinterpret_cast<int32_t*>(base);
+    int2* win = reinterpret_cast<int2*>(base + raw);
+    int* err = reinterpret_cast<int*>(base + raw + up((size_t)nblk * sizeof(int2)));
+    HIP_TRY(hipMemsetAsync(err, 0, sizeof(int), stream));
+    std::vector<int2> hw(nblk);
+    int widest = 4;
+    for (int32_t l = 0; l < L; ++l) {
+        if (!idx[l]) return fail(SPDNN_EINVAL, "idx[%d] is NULL", l);
+        const int32_t* di = idx[l];
+        if (where == SPDNN_HOST) {
+            HIP_TRY(hipMemcpyAsync(st_idx, idx[l], (size_t)N * spdnn::kNnz * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+            di = st_idx;
+        }
+        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win, err);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpyAsync(hw.data(), win, sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[b].y);
+    }
+    int herr = 0;
+    HIP_TRY(hipMemcpy(&herr, err, sizeof(int), hipMemcpyDeviceToHost));
+    if (herr) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
+    *widest_window = widest;
     return SPDNN_OK;
 }
 
@@ -164,10 +226,16 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
     if (reinterpret_cast<uintptr_t>(weights_arena) % kAlign) return fail(SPDNN_EINVAL, "weights_arena must be 256-byte aligned");
     for (int32_t l = 0; l < L; ++l)
         if (!idx[l] || !val[l]) return fail(SPDNN_EINVAL, "idx[%d] or val[%d] is NULL", l, l);
-    size_t need = 0;
-    spdnn_weights_bytes(N, L, &need);
-    if (weights_arena_bytes < need)
-        return fail(SPDNN_ESIZE, "weights arena has %zu bytes, %zu needed", weights_arena_bytes, need);
+    // The arena decides how many stages the wide format may use (0 = none: layers with
+    // wide windows then run the staged kernel, which is slower but needs no extra room).
+    int nstage_cap = stages_of(N);
+    while (nstage_cap > 2 && arena_bytes_for(N, L, nstage_cap) > weights_arena_bytes) --nstage_cap;
+    if (nstage_cap < 3) nstage_cap = 0;
+    {
+        const size_t need = arena_bytes_for(N, L, nstage_cap);
+        if (weights_arena_bytes < need)
+            return fail(SPDNN_ESIZE, "weights arena has %zu bytes, at least %zu needed", weights_arena_bytes, need);
+    }
 
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
@@ -205,8 +273,16 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
     HIP_TRY(allow_big_lds<false>());
     HIP_TRY(allow_big_lds<true>());
     constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
+    constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
+    const int tile_lds = (int)spdnn::tile_pair_bytes(spdnn::kCap);
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::order_pack_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::wide_pack_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
                           hipHostMallocDefault));
     for (int i = 0; i < kLag; ++i) HIP_TRY(hipEventCreateWithFlags(&m->lag_ev[i], hipEventDisableTiming));
@@ -230,15 +306,35 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         o += up(e * sizeof(float));
         m->layers[l].w = spdnn::LayerWeights{rel, wv, win};
         win_dev[l] = win;
+        spdnn::WideWeights ww{};
+        ww.win = win;
+        if (nstage_cap >= 3) {  // room for the wide format; the layer's own stage count strides the arrays
+            const size_t we = (size_t)nblk * nstage_cap * spdnn::wide_steps(nstage_cap) * spdnn::kBlk;
+            const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
+            ww.slot = reinterpret_cast<uint16_t*>(base + o);
+            o += up(we * sizeof(uint16_t));
+            ww.val = reinterpret_cast<float*>(base + o);
+            o += up(we * sizeof(float));
+            ww.nb8 = reinterpret_cast<uint8_t*>(base + o);
+            o += up((size_t)nblk * nstage_cap * 16);
+            ww.spill_col = reinterpret_cast<uint16_t*>(base + o);
+            o += up(sp * sizeof(uint16_t));
+            ww.spill_val = reinterpret_cast<float*>(base + o);
+            o += up(sp * sizeof(float));
+            ww.spill_n = reinterpret_cast<uint8_t*>(base + o);
+            o += up((size_t)nblk * 16);
+        }
+        m->layers[l].ww = ww;
     }
     int32_t* st_idx = reinterpret_cast<int32_t*>(base + o);
     o += up((size_t)N * spdnn::kNnz * sizeof(int32_t));
     float* st_val = reinterpret_cast<float*>(base + o);
     o += up((size_t)N * spdnn::kNnz * sizeof(float));
-    int* err_dev = reinterpret_cast<int*>(base + o);
-    HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int), stream));
+    int* err_dev = reinterpret_cast<int*>(base + o);  // [0] bad column seen; [1 + l] layer l could not use the wide format
+    HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int) * (size_t)(2 * L + 1), stream));
 
     const size_t raw = (size_t)N * spdnn::kNnz;
+    std::vector<int2> hw((size_t)L * nblk);
     for (int32_t l = 0; l < L; ++l) {
         const int32_t* di = idx[l];
         const float* dv = val[l];
@@ -248,27 +344,37 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
             di = st_idx;
             dv = st_val;
         }
-        const LayerDesc& d = m->layers[l];
+        LayerDesc& d = m->layers[l];
         spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev);
         spdnn::order_pack_kernel<<<nblk, spdnn::kOrderThreads, order_lds, stream>>>(
             di, dv, N, win_dev[l], const_cast<uint16_t*>(d.w.rel), const_cast<float*>(d.w.val));
         HIP_TRY(hipGetLastError());
-        if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
-    }
-    // read back the windows (stage counts, LDS sizes) and the error flag
-    std::vector<int2> hw((size_t)L * nblk);
-    int herr = 0;
-    for (int32_t l = 0; l < L; ++l)
+        // the windows decide the layer's kernel; they are small, so read them back now
         HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
-    HIP_TRY(hipMemcpyAsync(&herr, err_dev, sizeof(int), hipMemcpyDeviceToHost, stream));
-    HIP_TRY(hipStreamSynchronize(stream));
-    if (herr) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
-    for (int32_t l = 0; l < L; ++l) {
+        HIP_TRY(hipStreamSynchronize(stream));
         int widest = 4;
         for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[(size_t)l * nblk + b].y);
-        m->layers[l].multi = widest > spdnn::kCap;
-        m->layers[l].lds_cols = std::min(widest, spdnn::kCap);
+        const int nst = stages_of(widest);
+        d.lds_cols = std::min(widest, spdnn::kCap);
+        d.mode = nst <= 1 ? kSingle : kStaged;
+        if (nst >= 3 && nst <= nstage_cap) {
+            d.ww.nstage = nst;
+            spdnn::wide_pack_kernel<<<nblk, spdnn::kOrderThreads, wide_lds, stream>>>(
+                di, dv, N, win_dev[l], nst, const_cast<uint16_t*>(d.ww.slot), const_cast<float*>(d.ww.val),
+                const_cast<uint8_t*>(d.ww.nb8), const_cast<uint16_t*>(d.ww.spill_col),
+                const_cast<float*>(d.ww.spill_val), const_cast<uint8_t*>(d.ww.spill_n), err_dev + 1 + l);
+            HIP_TRY(hipGetLastError());
+            d.mode = kWide;
+        }
+        if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
     }
+    // error flag and the layers whose patterns did not fit the wide format
+    std::vector<int> herr((size_t)L + 1, 0);
+    HIP_TRY(hipMemcpyAsync(herr.data(), err_dev, sizeof(int) * (size_t)(L + 1), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (herr[0]) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
+    for (int32_t l = 0; l < L; ++l)
+        if (m->layers[l].mode == kWide && herr[1 + l]) m->layers[l].mode = kStaged;
     guard.m = nullptr;
     *out = m;
     return SPDNN_OK;
@@ -347,7 +453,13 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         const int32_t grid = (units + 7) / 8 * 8 * h->G;
         const size_t lds = spdnn::tile_pair_bytes((d.lds_cols + 255) / 256 * 256);  // whole waves of 256 columns
         if (h->profiling) HIP_TRY(hipEventRecord(h->t0[l], s));
-        if (d.multi)
+        if (d.mode == kWide && d.ww.nstage > 8)
+            spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(
+                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
+        else if (d.mode == kWide)
+            spdnn::fused_wide_kernel<16><<<grid, spdnn::kBlk, lds, s>>>(
+                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
+        else if (d.mode == kStaged)
             spdnn::fused_layer_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(
                 Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
         else

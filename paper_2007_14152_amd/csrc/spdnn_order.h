@@ -32,13 +32,14 @@ namespace spdnn {
 
 constexpr int kGroup = 16;  // lanes served per clock by a 16-byte LDS read = quads per 256-byte bank row
 
-// Working memory of one group (1088 bytes).  On the device it lives in LDS.
+// Working memory of one group (1104 bytes).  On the device it lives in LDS.
 struct OrderScratch {
     uint8_t cnt[kGroup][16];   // connections of lane l still unplaced, per quad
     uint8_t end[kGroup][16];   // end of quad q's bucket in sorted[l]
     uint8_t sorted[kGroup][32];  // lane l's connection numbers, bucketed by quad
     uint16_t adj[16];          // adj[q]: lanes that still have a connection in quad q
     uint16_t remq[16];         // connections still unplaced in quad q over the whole group
+    uint8_t reml[kGroup];      // connections of lane l still unplaced
 };
 
 SPDNN_HD inline unsigned nib_get(uint64_t w, int i) { return (unsigned)(w >> (4 * i)) & 15u; }
@@ -54,12 +55,14 @@ SPDNN_HD inline int ctz16(unsigned m) {
     return n;
 }
 
-// quad_of(l, k): quad (0..15) of connection k of lane l, or 255 if lane l has no such
-// connection (lane beyond the last neuron).  emit(l, step, k): connection k of lane l is
-// placed at step `step`.  Every existing connection is emitted exactly once and every
-// lane gets one connection per step.
+// quad_of(l, k), k < 32: quad (0..15) of connection k of lane l, or 255 if there is no
+// such connection (a lane may have fewer than 32, or none).  emit(l, step, k):
+// connection k of lane l is placed at step `step` < nsteps.  nsteps must be at least
+// the largest number of connections any lane has; every existing connection is emitted
+// exactly once, at most one per lane and step; a lane with fewer connections than
+// steps sits out the steps in which it would collide.
 template <typename QuadOf, typename Emit>
-SPDNN_HD inline void order_group(OrderScratch& S, QuadOf quad_of, Emit emit) {
+SPDNN_HD inline void order_group(OrderScratch& S, int nsteps, QuadOf quad_of, Emit emit) {
     uint16_t* adj = S.adj;
     uint16_t* remq = S.remq;
     for (int q = 0; q < 16; ++q) {
@@ -81,6 +84,7 @@ SPDNN_HD inline void order_group(OrderScratch& S, QuadOf quad_of, Emit emit) {
             remq[q] += S.cnt[l][q];
         }
         if (run) live |= 1u << l;
+        S.reml[l] = (uint8_t)run;
         // counting sort of the connection numbers by quad (stable)
         uint8_t fill[16];
         for (int q = 0; q < 16; ++q) fill[q] = (uint8_t)(S.end[l][q] - S.cnt[l][q]);
@@ -89,8 +93,8 @@ SPDNN_HD inline void order_group(OrderScratch& S, QuadOf quad_of, Emit emit) {
             if (q < 16) S.sorted[l][fill[q]++] = (uint8_t)k;
         }
     }
-    for (int step = 0; step < 32; ++step) {
-        const int left = 32 - step;
+    for (int step = 0; step < nsteps; ++step) {
+        const int left = nsteps - step;
         uint64_t lane_of = 0, quad_of_l = 0, par = 0;  // nibble arrays
         unsigned mq = 0, ml = 0;                        // matched quads / lanes
         unsigned done = 0;                              // quads already offered
@@ -149,8 +153,10 @@ SPDNN_HD inline void order_group(OrderScratch& S, QuadOf quad_of, Emit emit) {
                 const int q = (int)nib_get(quad_of_l, l);
                 mult = nib_set(mult, q, nib_get(mult, q) + 1);
             }
+        unsigned placed = ml;  // lanes that place a connection in this step
         for (int l = 0; l < kGroup; ++l) {
             if (!((live >> l) & 1u) || ((ml >> l) & 1u)) continue;
+            if ((int)S.reml[l] < left) continue;  // has slack: sits this step out
             int bq = -1;
             int bkey = 1 << 30;
             for (int q = 0; q < 16; ++q) {
@@ -162,18 +168,19 @@ SPDNN_HD inline void order_group(OrderScratch& S, QuadOf quad_of, Emit emit) {
                 }
             }
             quad_of_l = nib_set(quad_of_l, l, (unsigned)bq);
-            ml |= 1u << l;
+            placed |= 1u << l;
             const unsigned m = nib_get(mult, bq);
             mult = nib_set(mult, bq, m < 15 ? m + 1 : 15);
         }
         // place the chosen connections
         for (int l = 0; l < kGroup; ++l) {
-            if (!((live >> l) & 1u)) continue;
+            if (!((placed >> l) & 1u)) continue;
             const int q = (int)nib_get(quad_of_l, l);
             const int k = S.sorted[l][S.end[l][q] - S.cnt[l][q]];
             S.cnt[l][q]--;
             remq[q]--;
             if (!S.cnt[l][q]) adj[q] &= (uint16_t)~(1u << l);
+            if (--S.reml[l] == 0) live &= ~(1u << l);
             emit(l, step, k);
         }
     }

@@ -6,8 +6,9 @@ extern "C" {
 
 // quads: [16][32] quad (0..15) of every connection of 16 neighbouring neurons, 255 = absent.
 // step_of: [16][32] out, step at which connection k of lane l is placed (255 if absent).
+// nsteps: number of steps (>= the largest number of connections of any lane).
 // Returns the cost (sum over steps of the largest quad multiplicity).
-int spdnn_order_group_host(const uint8_t* quads, uint8_t* step_of) {
+int spdnn_order_group_host(const uint8_t* quads, uint8_t* step_of, int nsteps) {
     spdnn::OrderScratch S;
     uint8_t placed[16][32];
     for (int i = 0; i < 16 * 32; ++i) {
@@ -15,7 +16,7 @@ int spdnn_order_group_host(const uint8_t* quads, uint8_t* step_of) {
         (&placed[0][0])[i] = 255;
     }
     spdnn::order_group(
-        S, [&](int l, int k) -> unsigned { return quads[l * 32 + k]; },
+        S, nsteps, [&](int l, int k) -> unsigned { return quads[l * 32 + k]; },
         [&](int l, int step, int k) {
             step_of[l * 32 + k] = (uint8_t)step;
             placed[l][step] = quads[l * 32 + k];

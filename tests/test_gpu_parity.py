@@ -45,7 +45,38 @@ def test_random_models(N, L, batch, distinct, sort):
     assert common > 0
 
 
-@pytest.mark.parametrize("N,batch", [(64, 9), (1028, 21), (5000, 6)])
+@pytest.mark.parametrize("N,L,batch,kind", [
+    (12288, 2, 37, "uniform"),     # 3 stages of 4096 columns: many neurons exceed 16 connections in a stage (spill list)
+    (40000, 2, 13, "uniform"),     # 10 stages: 8 steps per stage
+    (12288, 1, 9, "clustered"),    # every neuron's 32 columns in one stage: does not fit -> staged kernel
+    (16384, 2, 21, "small_arena"), # arena sized for narrow windows -> staged kernel
+])
+def test_wide_windows(N, L, batch, kind):
+    """Layers whose blocks read more than two LDS stages of columns."""
+    import paper_2007_14152_amd as sp
+    rng = np.random.default_rng(N + L)
+    if kind == "clustered":
+        idx = []
+        for _ in range(L):
+            base = rng.integers(0, N // 4096, size=N) * 4096
+            a = np.stack([np.sort(b + rng.choice(4096, 32, replace=False)) for b in base])
+            idx.append(a.astype(np.int32))
+        val = [rng.uniform(0.0, 0.12, size=(N, 32)).astype(np.float32) for _ in range(L)]
+        bias = -rng.uniform(0.0, 0.3, size=N).astype(np.float32)
+    else:
+        idx, val, bias = rand_model(rng, N, L, True, True, lo=0.0, hi=0.12)
+    Y0 = rng.uniform(0, 1, size=(batch, N)).astype(np.float32)
+    Y0[1] = 0
+    ref = oracle.infer(idx, val, bias, Y0)
+    m = sp.Model(idx, val, bias, window_hint=4096 if kind == "small_arena" else None)
+    assert m.widest_window > 8192
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    m.close()
+    common, _ = check_against_oracle(ref, n, rows, Y, what="wide %s N=%d" % (kind, N))
+    assert common > 0
+
+
+@pytest.mark.parametrize("N,batch", [(64, 9), (1028, 21), (5000, 6), (16384, 5)])
 def test_mixed_sign_weights_one_layer(N, batch):
     """Weights of both signs cancel, so the result can be far smaller than the terms
     that were added; the library adds a neuron's 32 products in its own order, and

@@ -13,15 +13,15 @@ from paper_2007_14152_amd import build as hip_build
 @pytest.fixture(scope="module")
 def lib():
     L = ctypes.CDLL(hip_build.ORDER_HOST_LIB)
-    L.spdnn_order_group_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    L.spdnn_order_group_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
     L.spdnn_order_cost_host.argtypes = [ctypes.c_void_p]
     return L
 
 
-def order(lib, quads):
+def order(lib, quads, nsteps=32):
     quads = np.ascontiguousarray(quads, dtype=np.uint8)
     step_of = np.zeros((16, 32), dtype=np.uint8)
-    cost = lib.spdnn_order_group_host(quads.ctypes.data, step_of.ctypes.data)
+    cost = lib.spdnn_order_group_host(quads.ctypes.data, step_of.ctypes.data, nsteps)
     return cost, step_of
 
 
@@ -29,6 +29,7 @@ def brute_cost(quads, step_of):
     total = 0
     for s in range(32):
         q = [quads[l, np.nonzero(step_of[l] == s)[0][0]] for l in range(16) if (step_of[l] == s).any()]
+        q = [x for x in q if x < 16]
         total += np.bincount(q, minlength=16).max() if q else 0
     return int(total)
 
@@ -65,6 +66,29 @@ def test_absent_lanes_are_skipped(lib):
     assert np.all(step_of[5:] == 255)
     assert np.array_equal(np.sort(step_of[:5], axis=1), np.tile(np.arange(32), (5, 1)))
     assert cost >= 32
+
+
+def test_fewer_connections_than_steps(lib):
+    """Lanes with 0..16 connections placed in 16 steps: each connection once, no lane
+    twice in a step, and lanes with slack avoid collisions where they can."""
+    rng = np.random.default_rng(3)
+    for trial in range(30):
+        quads = np.full((16, 32), 255, dtype=np.uint8)
+        counts = rng.integers(0, 17, size=16)
+        for l in range(16):
+            quads[l, :counts[l]] = rng.integers(0, 16, size=counts[l])
+        cost, step_of = order(lib, quads, nsteps=16)
+        for l in range(16):
+            used = step_of[l, :counts[l]]
+            assert np.all(used < 16) and len(set(used.tolist())) == counts[l]
+            assert np.all(step_of[l, counts[l]:] == 255)
+        assert cost == brute_cost(quads, step_of)
+    # 8 connections per lane, all lanes the same 8 quads, 16 steps: slack lets every step be conflict-free
+    quads = np.full((16, 32), 255, dtype=np.uint8)
+    for l in range(16):
+        quads[l, :8] = np.arange(8)
+    cost, _ = order(lib, quads, nsteps=16)
+    assert cost <= 16
 
 
 def test_benchmark_patterns_get_close_to_the_bound(lib):
