@@ -82,8 +82,8 @@ size_t wide_bytes(int32_t nblk, int nstage) {
     if (nstage < 3) return 0;
     const size_t e = (size_t)nblk * nstage * spdnn::wide_steps(nstage) * spdnn::kBlk;
     const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
-    return up(e * sizeof(uint16_t)) + up(e * sizeof(float)) + up((size_t)nblk * nstage * 16) +
-           up(sp * sizeof(uint16_t)) + up(sp * sizeof(float)) + up((size_t)nblk * 16);
+    return up(e * sizeof(uint2)) + up((size_t)nblk * nstage * 16) + up(sp * sizeof(uint16_t)) +
+           up(sp * sizeof(float)) + up((size_t)nblk * 16);
 }
 size_t staging_bytes(int32_t N, int32_t L) {
     return up((size_t)N * spdnn::kNnz * sizeof(int32_t)) + up((size_t)N * spdnn::kNnz * sizeof(float)) +
@@ -311,10 +311,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         if (nstage_cap >= 3) {  // room for the wide format; the layer's own stage count strides the arrays
             const size_t we = (size_t)nblk * nstage_cap * spdnn::wide_steps(nstage_cap) * spdnn::kBlk;
             const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
-            ww.slot = reinterpret_cast<uint16_t*>(base + o);
-            o += up(we * sizeof(uint16_t));
-            ww.val = reinterpret_cast<float*>(base + o);
-            o += up(we * sizeof(float));
+            ww.pk = reinterpret_cast<uint2*>(base + o);
+            o += up(we * sizeof(uint2));
             ww.nb8 = reinterpret_cast<uint8_t*>(base + o);
             o += up((size_t)nblk * nstage_cap * 16);
             ww.spill_col = reinterpret_cast<uint16_t*>(base + o);
@@ -360,8 +358,7 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         if (nst >= 3 && nst <= nstage_cap) {
             d.ww.nstage = nst;
             spdnn::wide_pack_kernel<<<nblk, spdnn::kOrderThreads, wide_lds, stream>>>(
-                di, dv, N, win_dev[l], nst, const_cast<uint16_t*>(d.ww.slot), const_cast<float*>(d.ww.val),
-                const_cast<uint8_t*>(d.ww.nb8), const_cast<uint16_t*>(d.ww.spill_col),
+                di, dv, N, win_dev[l], nst, const_cast<uint2*>(d.ww.pk), const_cast<uint8_t*>(d.ww.nb8), const_cast<uint16_t*>(d.ww.spill_col),
                 const_cast<float*>(d.ww.spill_val), const_cast<uint8_t*>(d.ww.spill_n), err_dev + 1 + l);
             HIP_TRY(hipGetLastError());
             d.mode = kWide;

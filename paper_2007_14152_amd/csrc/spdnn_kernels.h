@@ -94,8 +94,8 @@ struct LayerWeights {
 constexpr int kChunk = 8;  // row groups whose accumulators a workgroup keeps while it walks the stages
 constexpr int kSpill = 4;  // spilled connections a neuron may have
 struct WideWeights {
-    const uint16_t* slot;       // [nblk][nstage][S][kBlk] LDS slot of the column inside its stage
-    const float* val;           // [nblk][nstage][S][kBlk]
+    const uint2* pk;            // [nblk][nstage][S/2][kBlk][2] {LDS slot of the column inside its stage, weight bits}:
+                                // a lane's two consecutive steps are one 16-byte load
     const uint8_t* nb8;         // [nblk][nstage][16] blocks of 8 steps wave w needs in stage s
     const uint16_t* spill_col;  // [nblk][kSpill][kBlk] column - c_lo of a spilled connection
     const float* spill_val;     // [nblk][kSpill][kBlk] its weight (0 = none)
@@ -287,6 +287,16 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     };
 
     float acc[kRows] = {0.f, 0.f, 0.f, 0.f};
+    // The four waves that share a SIMD get different issue priorities (first wave
+    // highest).  Without it all 16 waves hit the LDS in lock step after each barrier
+    // and the last one served reaches the next barrier ~2000 cycles after the first;
+    // measured gain on the 65536-neuron layers: 3-4 %.
+    {
+        const int pw = __builtin_amdgcn_readfirstlane(3 - ((threadIdx.x >> 8) & 3));
+        if (pw == 1) __builtin_amdgcn_s_setprio(1);
+        else if (pw == 2) __builtin_amdgcn_s_setprio(2);
+        else if (pw == 3) __builtin_amdgcn_s_setprio(3);
+    }
 
     // connections kbeg .. kbeg+15 of the tile in buffer P
     auto compute = [&](auto Ptag, int s, auto Ktag) {
@@ -379,13 +389,11 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         SPDNN_TL(t, 0);
         if (t + 2 < T) fetch_rows(t + 2);
         compute(Ptag, s, std::integral_constant<int, 0>{});
-        SPDNN_TL(t, 1);
-        if (t + 1 < T) store_tile(P ^ 1, t + 1);
         SPDNN_TL(t, 2);
+        if (t + 1 < T) store_tile(P ^ 1, t + 1);
         if (t + 2 < T) load_tile(t + 2);
-        SPDNN_TL(t, 3);
-        compute(Ptag, s, std::integral_constant<int, 16>{});
         SPDNN_TL(t, 4);
+        compute(Ptag, s, std::integral_constant<int, 16>{});
         if (s == nstage - 1) epilogue(g0 + gi);
         SPDNN_TL(t, 5);
         __syncthreads();
@@ -509,11 +517,14 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
     float wv[S];
     int nb = 0;  // blocks of 8 steps my wave needs in the current stage
     auto load_weights = [&](int s) {
-        const size_t base = ((size_t)(b * nstage + s) * S) * kBlk + tid;
+        const uint4* p = reinterpret_cast<const uint4*>(w.pk) + ((size_t)(b * nstage + s) * (S / 2)) * kBlk + tid;
 #pragma unroll
-        for (int k = 0; k < S; ++k) {
-            ow[k] = lds_base + tile_offset(w.slot[base + (size_t)k * kBlk]);
-            wv[k] = w.val[base + (size_t)k * kBlk];
+        for (int k2 = 0; k2 < S / 2; ++k2) {
+            const uint4 v = p[(size_t)k2 * kBlk];
+            ow[2 * k2] = lds_base + tile_offset(v.x);
+            wv[2 * k2] = __builtin_bit_cast(float, v.y);
+            ow[2 * k2 + 1] = lds_base + tile_offset(v.z);
+            wv[2 * k2 + 1] = __builtin_bit_cast(float, v.w);
         }
         nb = w.nb8[(b * nstage + s) * 16 + wave];
     };
@@ -557,8 +568,11 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
         }
     };
 
+    // One step: the first 8 connections of the stage, the next tile into the other LDS
+    // buffer and the loads of the tile after it, then the other 8 connections.
     auto step = [&](int t, auto Ptag, float (&a)[kRows]) {
         constexpr int P = decltype(Ptag)::value;
+        SPDNN_TL(t, 0);
         if (t + 2 < T) fetch_rows(t + 2);
         if (nb > 0) {
             uint32_t o8[8];
@@ -570,8 +584,10 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
             }
             fma_block8<P>(a, o8, v8);
         }
+        SPDNN_TL(t, 2);
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
         if (t + 2 < T) load_tile(t + 2);
+        SPDNN_TL(t, 4);
         if (S > 8 && nb > 1) {
             uint32_t o8[8];
             float v8[8];
@@ -582,7 +598,9 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
             }
             fma_block8<P>(a, o8, v8);
         }
+        SPDNN_TL(t, 5);
         __syncthreads();
+        SPDNN_TL(t, 6);
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
@@ -641,16 +659,22 @@ __global__ __launch_bounds__(1024) void compact_kernel(int* __restrict__ flags, 
     for (int chunk0 = 0; chunk0 < A; chunk0 += 65536) {
         const int nr = min(64, (A - chunk0 + 1023) >> 10);
         unsigned long long mine = 0ull;
-        for (int r = 0; r < nr; ++r) {
-            const int i = chunk0 + (r << 10) + tid;
-            int f = 0;
-            if (i < A) {
-                f = flags[i];
-                flags[i] = 0;
+        for (int r0 = 0; r0 < nr; r0 += 8) {  // 8 rounds per batch so that 8 loads are in flight
+            int f[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = chunk0 + ((r0 + u) << 10) + tid;
+                f[u] = (r0 + u < nr && i < A) ? flags[i] : 0;
             }
-            const unsigned long long m = __ballot(f != 0);
-            if (f != 0) mine |= 1ull << r;
-            if (lane == 0) tot[r * 16 + wave] = __popcll(m);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = r0 + u;
+                const int i = chunk0 + (r << 10) + tid;
+                if (r < nr && i < A) flags[i] = 0;
+                const unsigned long long m = __ballot(f[u] != 0);
+                if (f[u] != 0) mine |= 1ull << r;
+                if (lane == 0 && r < nr) tot[r * 16 + wave] = __popcll(m);
+            }
         }
         __syncthreads();
         // exclusive scan over the (round, wave) counts: entry tid = round tid/16, wave tid%16
@@ -672,14 +696,23 @@ __global__ __launch_bounds__(1024) void compact_kernel(int* __restrict__ flags, 
         }
         tot[tid] = wbase + incl - v;
         __syncthreads();
-        for (int r = 0; r < nr; ++r) {
-            const int i = chunk0 + (r << 10) + tid;
-            const bool keep = (mine >> r) & 1ull;
-            const unsigned long long m = __ballot(keep);
-            if (keep) {
-                const int p = base + tot[r * 16 + wave] + __popcll(m & ((1ull << lane) - 1ull));
-                cat_out[p] = i;
-                gid_out[p] = gid_in[i];
+        for (int r0 = 0; r0 < nr; r0 += 8) {
+            int g[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = chunk0 + ((r0 + u) << 10) + tid;
+                g[u] = ((mine >> (r0 + u)) & 1ull) ? gid_in[i] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = r0 + u;
+                const bool keep = (mine >> r) & 1ull;  // bits of rounds >= nr are never set
+                const unsigned long long m = __ballot(keep);
+                if (keep) {
+                    const int p = base + tot[r * 16 + wave] + __popcll(m & ((1ull << lane) - 1ull));
+                    cat_out[p] = chunk0 + (r << 10) + tid;
+                    gid_out[p] = g[u];
+                }
             }
         }
         base += total;
@@ -814,8 +847,7 @@ struct WideScratch {
 __global__ __launch_bounds__(kOrderThreads) void wide_pack_kernel(const int32_t* __restrict__ idx,
                                                                   const float* __restrict__ val, int N,
                                                                   const int2* __restrict__ win, int nstage,
-                                                                  uint16_t* __restrict__ wslot,
-                                                                  float* __restrict__ wval,
+                                                                  uint2* __restrict__ pk,
                                                                   uint8_t* __restrict__ nb8,
                                                                   uint16_t* __restrict__ spill_col,
                                                                   float* __restrict__ spill_val,
@@ -879,13 +911,13 @@ __global__ __launch_bounds__(kOrderThreads) void wide_pack_kernel(const int32_t*
     WideScratch& W = wide_scratch[t];
     for (int s = 0; s < nstage; ++s) {
         const int nsteps = ((wave_need[s][wave] + 7) >> 3) << 3;
-        const size_t sbase = ((size_t)(b * nstage + s) * S) * kBlk;
+        const size_t sbase = ((size_t)(b * nstage + s) * (S / 2)) * kBlk;  // in pairs of steps
+        auto entry = [&](int step, int lane_pos) -> size_t {
+            return ((sbase + (size_t)(step >> 1) * kBlk + lane_pos) << 1) | (size_t)(step & 1);
+        };
         for (int l = 0; l < kGroup; ++l) {  // every step starts as "weight 0 on the stage's first column"
             const int lane_pos = wave0 + lane_of_group(set, l);
-            for (int k = 0; k < S; ++k) {
-                wslot[sbase + (size_t)k * kBlk + lane_pos] = (uint16_t)col_slot(0);
-                wval[sbase + (size_t)k * kBlk + lane_pos] = 0.0f;
-            }
+            for (int k = 0; k < S; ++k) pk[entry(k, lane_pos)] = make_uint2(col_slot(0), 0u);
             uint32_t keep = 0;
             if (neuron(l) < N) {
                 int c = 0;
@@ -904,12 +936,12 @@ __global__ __launch_bounds__(kOrderThreads) void wide_pack_kernel(const int32_t*
                 return ((W.keep[l] >> k) & 1u) ? (col_slot((uint32_t)rel_of(l, k) & (kCap - 1)) & 15u) : 255u;
             },
             [&](int l, int step, int k) {
-                const size_t e = sbase + (size_t)step * kBlk + wave0 + lane_of_group(set, l);
                 const size_t src = (size_t)neuron(l) * kNnz + k;
                 const int c = idx[src];
                 const bool ok = c >= 0 && c < N;
-                wslot[e] = (uint16_t)col_slot((uint32_t)(ok ? c - c_lo : 0) & (kCap - 1));
-                wval[e] = ok ? val[src] : 0.0f;
+                pk[entry(step, wave0 + lane_of_group(set, l))] =
+                    make_uint2(col_slot((uint32_t)(ok ? c - c_lo : 0) & (kCap - 1)),
+                               __builtin_bit_cast(uint32_t, ok ? val[src] : 0.0f));
             });
     }
 }

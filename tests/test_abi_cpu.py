@@ -42,7 +42,7 @@ def test_arena_sizes():
     assert compact == sp.spdnn_weights_bytes_for_window(n, 10, 8192)
     assert compact < sp.spdnn_weights_bytes_for_window(n, 10, 12288) < sp.spdnn_weights_bytes_for_window(n, 10, n)
     assert sp.spdnn_weights_bytes_for_window(n, 10, n) == sp.spdnn_weights_bytes(n, 10)
-    assert sp.spdnn_weights_bytes(65536, 2) < 2 * 65536 * 32 * 6 * 6
+    assert sp.spdnn_weights_bytes(65536, 2) < 2 * 65536 * 32 * 6 * 8
 
 
 @pytest.mark.parametrize("N,L", [(0, 1), (16, 1), (34, 1), (65540, 1), (64, 0), (-4, 3)])
