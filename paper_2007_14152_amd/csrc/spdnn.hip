@@ -74,7 +74,8 @@ bool valid_n(int32_t N) { return N >= 32 && N <= 65536 && (N % 4) == 0; }
 
 size_t layer_bytes(int32_t nblk) {
     const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
-    return up((size_t)nblk * sizeof(int2)) + up(e * sizeof(uint16_t)) + up(e * sizeof(float));
+    return up((size_t)nblk * sizeof(int2)) + up(e * sizeof(uint16_t)) + up(e * sizeof(float)) +
+           up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t));
 }
 int stages_of(int32_t window) { return (window + spdnn::kCap - 1) / spdnn::kCap; }
 // extra bytes per layer for the wide format with up to `nstage` stages (0 if not needed)
@@ -86,8 +87,10 @@ size_t wide_bytes(int32_t nblk, int nstage) {
            up(sp * sizeof(float)) + up((size_t)nblk * 16);
 }
 size_t staging_bytes(int32_t N, int32_t L) {
+    const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
     return up((size_t)N * spdnn::kNnz * sizeof(int32_t)) + up((size_t)N * spdnn::kNnz * sizeof(float)) +
-           up(sizeof(int) * (size_t)(2 * L + 1));  // error flag, per-layer stage counts, per-layer wide failures
+           up((size_t)nblk * spdnn::kCap * sizeof(uint16_t)) +  // column -> LDS slot table of the layer being set up
+           up(sizeof(int) * (size_t)(2 * L + 1));  // error flag, per-layer wide failures, per-layer widest window
 }
 size_t arena_bytes_for(int32_t N, int32_t L, int nstage_cap) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
@@ -185,7 +188,7 @@ int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t 
     int32_t* st_idx = reinterpret_cast<int32_t*>(base);
     int2* win = reinterpret_cast<int2*>(base + raw);
     int* err = reinterpret_cast<int*>(base + raw + up((size_t)nblk * sizeof(int2)));
-    HIP_TRY(hipMemsetAsync(err, 0, sizeof(int), stream));
+    HIP_TRY(hipMemsetAsync(err, 0, 2 * sizeof(int), stream));  // error flag, widest window (unused here)
     std::vector<int2> hw(nblk);
     int widest = 4;
     for (int32_t l = 0; l < L; ++l) {
@@ -195,7 +198,7 @@ int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t 
             HIP_TRY(hipMemcpyAsync(st_idx, idx[l], (size_t)N * spdnn::kNnz * sizeof(int32_t), hipMemcpyHostToDevice, stream));
             di = st_idx;
         }
-        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win, err);
+        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win, err, err + 1);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipMemcpyAsync(hw.data(), win, sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
@@ -279,6 +282,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::wide_pack_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch)));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
@@ -304,7 +309,9 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         o += up(e * sizeof(uint16_t));
         float* wv = reinterpret_cast<float*>(base + o);
         o += up(e * sizeof(float));
-        m->layers[l].w = spdnn::LayerWeights{rel, wv, win};
+        uint32_t* qsel = reinterpret_cast<uint32_t*>(base + o);
+        o += up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t));
+        m->layers[l].w = spdnn::LayerWeights{rel, wv, win, qsel};
         win_dev[l] = win;
         spdnn::WideWeights ww{};
         ww.win = win;
@@ -328,7 +335,10 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
     o += up((size_t)N * spdnn::kNnz * sizeof(int32_t));
     float* st_val = reinterpret_cast<float*>(base + o);
     o += up((size_t)N * spdnn::kNnz * sizeof(float));
-    int* err_dev = reinterpret_cast<int*>(base + o);  // [0] bad column seen; [1 + l] layer l could not use the wide format
+    uint16_t* slot_tab = reinterpret_cast<uint16_t*>(base + o);
+    o += up((size_t)nblk * spdnn::kCap * sizeof(uint16_t));
+    // [0] bad column seen; [1 + l] layer l could not use the wide format; [1 + L + l] layer l's widest window
+    int* err_dev = reinterpret_cast<int*>(base + o);
     HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int) * (size_t)(2 * L + 1), stream));
 
     const size_t raw = (size_t)N * spdnn::kNnz;
@@ -343,9 +353,13 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
             dv = st_val;
         }
         LayerDesc& d = m->layers[l];
-        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev);
+        int* widest_dev = err_dev + 1 + L + l;
+        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev, widest_dev);
+        spdnn::balance_kernel<<<nblk, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch), stream>>>(
+            di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
         spdnn::order_pack_kernel<<<nblk, spdnn::kOrderThreads, order_lds, stream>>>(
-            di, dv, N, win_dev[l], const_cast<uint16_t*>(d.w.rel), const_cast<float*>(d.w.val));
+            di, dv, N, win_dev[l], widest_dev, slot_tab, const_cast<uint16_t*>(d.w.rel),
+            const_cast<float*>(d.w.val));
         HIP_TRY(hipGetLastError());
         // the windows decide the layer's kernel; they are small, so read them back now
         HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));

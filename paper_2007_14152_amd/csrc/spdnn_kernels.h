@@ -80,10 +80,31 @@ __host__ __device__ inline uint32_t col_slot(uint32_t c) {
     return (hi << 7) | ((gr >> 2) << 6) | (a << 4) | ((gr & 3u) << 2) | m;
 }
 
+// Set (0..3) and rank inside the set (0..15) of lane l of a wave: the inverse of
+// lane_of_group.
+__host__ __device__ inline uint32_t set_of_lane(uint32_t l) {
+    const uint32_t gr = (0x73261540u >> (4u * ((l >> 2) & 7u))) & 7u;  // quartet -> set parity * 4 + rank of quartet
+    return ((l >> 5) << 1) | (gr >> 2);
+}
+__host__ __device__ inline uint32_t rank_in_set(uint32_t l) {
+    const uint32_t gr = (0x73261540u >> (4u * ((l >> 2) & 7u))) & 7u;
+    return ((gr & 3u) << 2) | (l & 3u);
+}
+// Balanced layout of a single-stage tile (balance_kernel).  Staging lane t writes its
+// columns 4t+a, a = 0..3, with four 16-byte stores; the 16 lanes of a set form, per a,
+// a "store group" of 16 columns that must land in 16 different bank quads.  Store group
+// g = (wave * 4 + set) * 4 + a owns the 256-byte row g of the tile; inside the row the
+// 16 columns may take the 16 quads in any order, and that order is what gets chosen.
+__host__ __device__ inline uint32_t store_group(uint32_t c) {  // of stage-local column c
+    const uint32_t t = c >> 2;
+    return (((t >> 6) << 2) | set_of_lane(t & 63u)) << 2 | (c & 3u);
+}
+
 struct LayerWeights {
     const uint16_t* rel;  // [nblk][32][kBlk] stage << 12 | LDS slot of (column - c_lo) within the stage
     const float* val;     // [nblk][32][kBlk]
     const int2* win;      // [nblk] {c_lo, ncols}, both multiples of 4
+    const uint32_t* qsel;  // [nblk][kBlk] balanced single-stage layers: see balance_kernel
 };
 
 // Layout for layers whose column windows need 3 or more LDS stages ("wide" layers).
@@ -249,7 +270,14 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     // work; inside the last wave, lanes past it re-read the last 4 columns.
     f32x4 st[kRows];
     const int wave_col = (tid & ~63) * 4;  // first column of my wave
-    const uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));  // + a*512 for column 4t + a
+    // LDS address of column 4t + a is st_addr + a*512 + st_quad[a].  Single-stage layers
+    // use the balanced layout (the quads come from the set-up), the others col_slot().
+    uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));
+    uint32_t qp = 0;  // byte a = quad of column 4t + a, times 16
+    if (!MULTI) {
+        st_addr = lds_base + tile_offset(store_group(4 * tid) << 4);
+        qp = w.qsel[(size_t)b * kBlk + tid];
+    }
     const int cat_last = cat[A - 1];
     int4 c4 = make_int4(0, 0, 0, 0);  // slots (in Yin) of the 4 rows of the tile to load next
 
@@ -280,10 +308,14 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         // results are first touched, otherwise the register shuffles of the transpose
         // are scheduled right behind the loads and every load turns synchronous.
         asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
-        *reinterpret_cast<lds_f4*>(st_addr + 0 * 512 + P * kBufSkew) = f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
-        *reinterpret_cast<lds_f4*>(st_addr + 1 * 512 + P * kBufSkew) = f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
-        *reinterpret_cast<lds_f4*>(st_addr + 2 * 512 + P * kBufSkew) = f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
-        *reinterpret_cast<lds_f4*>(st_addr + 3 * 512 + P * kBufSkew) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+        *reinterpret_cast<lds_f4*>(st_addr + (qp & 0xffu) + 0 * 512 + P * kBufSkew) =
+            f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
+        *reinterpret_cast<lds_f4*>(st_addr + ((qp >> 8) & 0xffu) + 1 * 512 + P * kBufSkew) =
+            f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
+        *reinterpret_cast<lds_f4*>(st_addr + ((qp >> 16) & 0xffu) + 2 * 512 + P * kBufSkew) =
+            f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
+        *reinterpret_cast<lds_f4*>(st_addr + (qp >> 24) + 3 * 512 + P * kBufSkew) =
+            f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
     };
 
     float acc[kRows] = {0.f, 0.f, 0.f, 0.f};
@@ -754,7 +786,8 @@ __global__ void gather_rows_kernel(const float4* __restrict__ src, const int* __
 // addresses, as the transposed sliced-ELL of Section III-A-3 is meant to give).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __restrict__ idx, int N,
-                                                            int2* __restrict__ win, int* __restrict__ err) {
+                                                            int2* __restrict__ win, int* __restrict__ err,
+                                                            int* __restrict__ widest) {
     __shared__ int s_lo, s_hi;
     const int tid = threadIdx.x;
     const int j = blockIdx.x * kBlk + tid;
@@ -785,6 +818,134 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
             ncols = ((s_hi + 1 - c_lo) + 3) & ~3;
         }
         win[blockIdx.x] = make_int2(c_lo, ncols);
+        atomicMax(widest, ncols);  // the layer's widest window (zero before the launch)
+    }
+}
+
+// Balanced tile layout for single-stage layers (widest window <= kCap columns).
+//
+// The bank-aware ordering (spdnn_order.h) can only spread a lane set's 512
+// connections over the 32 steps as evenly as they are spread over the 16 bank quads:
+// the busiest quad's count is a lower bound on the set's cost.  With a fixed
+// column -> quad rule that maximum is about 45 for random patterns (mean 32), i.e. 40 %
+// more LDS read cycles than necessary.  Which quad a column's 16-byte entry sits in is,
+// however, free inside its store group (see store_group()), so it is chosen here, per
+// output block, to even out every set's quad histogram: the store groups are taken in
+// turn; a column's cost for quad q is the sum, over its connections, of what q already
+// holds for the connection's lane set; columns pick their cheapest free quad, busiest
+// column first.  Measured on the 65536-neuron patterns: busiest quad 33.6 on average,
+// 4.3 LDS cycles per 64-lane read instead of 5.7 (4 is conflict-free).
+//
+// One wave per output block.  Output: slot_tab[b][c] = LDS slot of stage-local column
+// c, qsel[b][t] = quads (times 16, one per byte) of staging lane t's four columns.
+// A layer with a wider window is left alone (order_pack_kernel then uses col_slot()).
+struct BalanceScratch {
+    uint32_t cursor[kCap];           // connections per column, then fill position
+    uint16_t ofs[kCap + 4];          // start of column c's entries in ent[]
+    uint8_t ent[kNnz * kBlk];        // lane set (0..63) of every connection, grouped by column
+    uint16_t load[kBlk / kGroup][16];  // connections lane set S already has in quad q
+    uint16_t cost[16][16];
+};
+constexpr int kBalanceThreads = 64;
+__global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t* __restrict__ idx, int N,
+                                                                  const int2* __restrict__ win,
+                                                                  const int* __restrict__ widest,
+                                                                  uint16_t* __restrict__ slot_tab,
+                                                                  uint32_t* __restrict__ qsel) {
+    extern __shared__ BalanceScratch balance_scratch[];
+    BalanceScratch& B = balance_scratch[0];
+    if (*widest > kCap) return;
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int c_lo = win[b].x;
+    for (int c = lane; c < kCap; c += kBalanceThreads) B.cursor[c] = 0;
+    for (int i = lane; i < (kBlk / kGroup) * 16; i += kBalanceThreads) (&B.load[0][0])[i] = 0;
+    __syncthreads();
+    // stage-local column of connection e = (neuron << 5 | k) of this block, or -1
+    auto rel_of = [&](int e) -> int {
+        const int j = b * kBlk + (e >> 5);
+        if (j >= N) return -1;
+        const int c = idx[(size_t)j * kNnz + (e & 31)];
+        return (c < 0 || c >= N) ? 0 : c - c_lo;  // out-of-range columns were reported; keep them harmless
+    };
+    for (int e = lane; e < kNnz * kBlk; e += kBalanceThreads) {
+        const int r = rel_of(e);
+        if (r >= 0) atomicAdd(&B.cursor[r], 1u);
+    }
+    __syncthreads();
+    // exclusive prefix sum over the columns: lane owns 64 consecutive ones
+    {
+        constexpr int per = kCap / kBalanceThreads;
+        uint32_t sum = 0;
+        for (int i = 0; i < per; ++i) sum += B.cursor[lane * per + i];
+        uint32_t incl = sum;
+        for (int d = 1; d < kBalanceThreads; d <<= 1) {
+            const uint32_t v = __shfl_up(incl, d);
+            if (lane >= d) incl += v;
+        }
+        uint32_t run = incl - sum;
+        for (int i = 0; i < per; ++i) {
+            const uint32_t n = B.cursor[lane * per + i];
+            B.ofs[lane * per + i] = (uint16_t)run;
+            B.cursor[lane * per + i] = run;
+            run += n;
+        }
+        if (lane == kBalanceThreads - 1) B.ofs[kCap] = (uint16_t)run;  // <= 32768
+    }
+    __syncthreads();
+    for (int e = lane; e < kNnz * kBlk; e += kBalanceThreads) {
+        const int r = rel_of(e);
+        if (r < 0) continue;
+        const uint32_t pos = atomicAdd(&B.cursor[r], 1u);
+        const uint32_t n = (uint32_t)e >> 5;
+        B.ent[pos] = (uint8_t)(((n >> 6) << 2) | set_of_lane(n & 63u));
+    }
+    __syncthreads();
+
+    const int row = lane >> 2;  // cost phase: lane computes quads 4*part .. 4*part+3 of column `row`
+    const int part = lane & 3;
+    uint32_t packed = 0;  // lanes 0..15: quads (times 16) chosen so far for the staging lane's columns
+    for (int g = 0; g < kCap / 16; ++g) {
+        const int a = g & 3, set = (g >> 2) & 3, wave = g >> 4;
+        auto column_of = [&](int i) { return 4 * (wave * 64 + lane_of_group(set, i)) + a; };
+        {
+            const int c = column_of(row);
+            uint32_t acc[4] = {0, 0, 0, 0};
+            for (uint32_t e = B.ofs[c]; e < B.ofs[c + 1]; ++e) {
+                const uint16_t* ld = &B.load[B.ent[e]][4 * part];
+                acc[0] += ld[0];
+                acc[1] += ld[1];
+                acc[2] += ld[2];
+                acc[3] += ld[3];
+            }
+            for (int i = 0; i < 4; ++i) B.cost[row][4 * part + i] = (uint16_t)min(acc[i], 4095u);
+        }
+        __syncthreads();
+        // lanes 0..15 in two roles: as column i = lane (count, chosen quad) and as quad q = lane
+        const int c_mine = column_of(lane & 15);
+        const int cnt = (int)B.ofs[c_mine + 1] - (int)B.ofs[c_mine];
+        int chosen = -1;
+        bool quad_free = true;
+        for (int it = 0; it < 16; ++it) {
+            int key = chosen < 0 ? ((cnt << 4) | (15 - (lane & 15))) : -1;  // busiest unplaced column, lowest index first
+            for (int d = 1; d < 16; d <<= 1) key = max(key, __shfl_xor(key, d, 16));
+            const int i = 15 - (key & 15);
+            int k2 = quad_free ? (((int)B.cost[i][lane & 15] << 4) | (lane & 15)) : 0x7fffffff;
+            for (int d = 1; d < 16; d <<= 1) k2 = min(k2, __shfl_xor(k2, d, 16));
+            const int q = k2 & 15;
+            if ((lane & 15) == i) chosen = q;
+            if ((lane & 15) == q) quad_free = false;
+        }
+        if (lane < 16) {
+            for (uint32_t e = B.ofs[c_mine]; e < B.ofs[c_mine + 1]; ++e) B.load[B.ent[e]][chosen]++;
+            slot_tab[(size_t)b * kCap + c_mine] = (uint16_t)((g << 4) | chosen);
+            packed |= (uint32_t)(chosen << 4) << (8 * a);
+            if (a == 3) {
+                qsel[(size_t)b * kBlk + wave * 64 + lane_of_group(set, lane)] = packed;
+                packed = 0;
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -798,6 +959,8 @@ constexpr int kOrderThreads = kBlk / kGroup;
 __global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t* __restrict__ idx,
                                                                    const float* __restrict__ val, int N,
                                                                    const int2* __restrict__ win,
+                                                                   const int* __restrict__ widest,
+                                                                   const uint16_t* __restrict__ slot_tab,
                                                                    uint16_t* __restrict__ rel,
                                                                    float* __restrict__ wval) {
     extern __shared__ OrderScratch order_scratch[];
@@ -811,10 +974,14 @@ __global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t
         const int c = idx[(size_t)neuron(l) * kNnz + k];
         return (c < 0 || c >= N) ? c_lo : c;
     };
+    // LDS slot of stage-local column r: from balance_kernel for single-stage layers
+    const bool balanced = *widest <= kCap;
+    const uint16_t* tab = slot_tab + (size_t)b * kCap;
+    auto slot_of = [&](uint32_t r) -> uint32_t { return balanced ? tab[r] : col_slot(r); };
     order_group(
         order_scratch[t], kNnz,
         [&](int l, int k) -> unsigned {
-            return (neuron(l) < N) ? (col_slot((uint32_t)(column(l, k) - c_lo) & (kCap - 1)) & 15u) : 255u;
+            return (neuron(l) < N) ? (slot_of((uint32_t)(column(l, k) - c_lo) & (kCap - 1)) & 15u) : 255u;
         },
         [&](int l, int step, int k) {
             const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
@@ -822,14 +989,14 @@ __global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t
             const int c = idx[src];
             const bool ok = c >= 0 && c < N;
             const uint32_t r = ok ? (uint32_t)(c - c_lo) : 0u;  // stage number | slot inside the stage
-            rel[e] = (uint16_t)((r & ~(uint32_t)(kCap - 1)) | col_slot(r & (kCap - 1)));
+            rel[e] = (uint16_t)((r & ~(uint32_t)(kCap - 1)) | slot_of(r & (kCap - 1)));
             wval[e] = ok ? val[src] : 0.0f;
         });
     for (int l = 0; l < kGroup; ++l) {
         if (neuron(l) < N) continue;
         for (int step = 0; step < kNnz; ++step) {  // lanes past the last neuron: weight 0 on column c_lo
             const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
-            rel[e] = (uint16_t)col_slot(0);
+            rel[e] = (uint16_t)slot_of(0);
             wval[e] = 0.0f;
         }
     }
