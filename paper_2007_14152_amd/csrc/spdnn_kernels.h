@@ -245,9 +245,10 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
 
     // Connections of my output neuron, in registers for the whole kernel.
     // off = LDS byte address (buffer 0) of the column inside its stage; MULTI also
-    // keeps the stage number in bits 20 and up.
+    // keeps the stage numbers, eight 4-bit fields per register.
     uint32_t off[kNnz];
     float wv[kNnz];
+    uint32_t stg[MULTI ? kNnz / 8 : 1] = {};
     {
         const uint16_t* prel = w.rel + (size_t)b * kNnz * kBlk + tid;
         const float* pval = w.val + (size_t)b * kNnz * kBlk + tid;
@@ -255,11 +256,19 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         for (int k = 0; k < kNnz; ++k) {
             const uint32_t rel = prel[k * kBlk];
             wv[k] = pval[k * kBlk];
-            if (MULTI)
-                off[k] = (lds_base + tile_offset(rel & (kCap - 1))) | ((rel >> kCapLog2) << 20);
-            else
-                off[k] = lds_base + tile_offset(rel & (kCap - 1));
+            off[k] = lds_base + tile_offset(rel & (kCap - 1));
+            if (MULTI) stg[k >> 3] |= (rel >> kCapLog2) << (4 * (k & 7));
         }
+    }
+    if (MULTI) {
+        // A connection that belongs to another stage reads its slot of the current tile all
+        // the same and contributes with weight 0.  That is exact as long as whatever lies in
+        // the slot is finite, so the tile pair starts out as zeros (later contents are
+        // activations; slots past a narrow last stage keep older ones).
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        for (uint32_t o = 16u * tid; o < tile_pair_bytes(kCap); o += 16u * kBlk)
+            *reinterpret_cast<lds_f4*>(lds_base + o) = f32x4{0.f, 0.f, 0.f, 0.f};
+        __syncthreads();
     }
     const float bj = jok ? bias[j] : 0.0f;
 
@@ -344,14 +353,17 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
                 o[i] = off[k0 + i];
                 v[i] = wv[k0 + i];
                 if (MULTI) {
-                    // a connection outside this stage reads column 0 of the stage (always
-                    // loaded) with weight 0: adds exactly 0 for finite features
-                    const bool mine = (int)(o[i] >> 20) == s;
-                    o[i] = mine ? (o[i] & 0xFFFFFu) : lds_base + tile_offset(col_slot(0));
-                    v[i] = mine ? v[i] : 0.0f;
+                    // field k of stg is compared through a word that changes with s, so that the
+                    // 32 extracted stage numbers are not kept in registers across the loop
+                    const int k = k0 + i;
+                    const uint32_t x = stg[k >> 3] ^ ((uint32_t)s * 0x11111111u);
+                    v[i] = (x & (15u << (4 * (k & 7)))) == 0u ? v[i] : 0.0f;
                 }
             }
             fma_block8<P>(acc, o, v);
+            // keep each block's masked weights next to their block: hoisted, they would
+            // need 32 more registers
+            if (MULTI) __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -375,7 +387,6 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
                              (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
                              (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
         if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;
-#ifdef SPDNN_TRANSPOSED_STORES
         // 4x4 transpose inside each quartet: lane 4q+i holds rows 0..3 of neuron 4q+i and
         // ends up with row i of neurons 4q..4q+3, which is one 16-byte store.
         {
@@ -397,16 +408,6 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         const int r = lane & 3;
         if (jok && r < nlive)
             *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
-#else
-        // one 4-byte store per row: the wave writes 256 contiguous bytes of each row
-        if (jok) {
-            float* dst = Yout + (size_t)row0 * N + j;
-            dst[0] = y0;
-            if (nlive > 1) dst[(size_t)N] = y1;
-            if (nlive > 2) dst[2 * (size_t)N] = y2;
-            if (nlive > 3) dst[3 * (size_t)N] = y3;
-        }
-#endif
     };
 
     // One pipeline step with compile-time buffer index P.  On entry tile t is in
