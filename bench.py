@@ -20,8 +20,8 @@ HBM_PEAK_GBS = 8000.0       # MI355X published peak HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 0..4")
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch (debug)")

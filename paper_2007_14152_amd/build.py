@@ -9,6 +9,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(CSRC, "libspdnn.so")
 SOURCES = [os.path.join(CSRC, "spdnn.hip")]
 HEADERS = [os.path.join(CSRC, "spdnn_kernels.h"), os.path.join(CSRC, "spdnn_order.h"),
+           os.path.join(CSRC, "spdnn_layout.h"),
            os.path.join(os.path.dirname(_HERE), "include", "spdnn.h")]
 # host build of the connection-ordering routine, for tests of the set-up logic without a GPU
 ORDER_HOST_LIB = os.path.join(CSRC, "libspdnn_order_host.so")

@@ -1,5 +1,7 @@
-// Host build of the connection-ordering routine (spdnn_order.h), so that the
-// set-up logic can be tested without a GPU.  Not used by the inference path.
+// Host build of the connection-ordering routine (spdnn_order.h) and of the tile
+// layout functions (spdnn_layout.h), so that the set-up logic can be tested without a
+// GPU.  Not used by the inference path.
+#include "spdnn_layout.h"
 #include "spdnn_order.h"
 
 extern "C" {
@@ -28,5 +30,14 @@ int spdnn_order_group_host(const uint8_t* quads, uint8_t* step_of, int nsteps) {
 int spdnn_order_cost_host(const uint8_t* quads) {
     return spdnn::order_cost([&](int l, int step) -> unsigned { return quads[l * 32 + step]; });
 }
+
+// Tile layout functions, one call per value.
+uint32_t spdnn_tile_offset_host(uint32_t slot) { return spdnn::tile_offset(slot); }
+uint32_t spdnn_tile_pair_bytes_host(uint32_t cols) { return spdnn::tile_pair_bytes(cols); }
+int spdnn_lane_of_group_host(int set, int rank) { return spdnn::lane_of_group(set, rank); }
+uint32_t spdnn_set_of_lane_host(uint32_t lane) { return spdnn::set_of_lane(lane); }
+uint32_t spdnn_rank_in_set_host(uint32_t lane) { return spdnn::rank_in_set(lane); }
+uint32_t spdnn_col_slot_host(uint32_t c) { return spdnn::col_slot(c); }
+uint32_t spdnn_store_group_host(uint32_t c) { return spdnn::store_group(c); }
 
 }  // extern "C"

@@ -1,0 +1,87 @@
+"""Tile layout of the fused kernels (csrc/spdnn_layout.h), checked on the host build.
+
+What the kernels rely on: the lane sets are a partition of the wave; the fixed and the
+balanced column -> slot rules are permutations of the tile; the four columns of a
+staging lane sit 512 bytes apart; and the 16 lanes that a 16-byte LDS store serves
+together hit 16 different bank quads.
+"""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+
+from paper_2007_14152_amd import build as _build
+
+KCAP = 4096
+
+
+@pytest.fixture(scope="module")
+def lay():
+    if not os.path.exists(_build.ORDER_HOST_LIB):
+        _build.build()
+    L = ctypes.CDLL(_build.ORDER_HOST_LIB)
+    u32 = ctypes.c_uint32
+    for name in ("tile_offset", "tile_pair_bytes", "set_of_lane", "rank_in_set", "col_slot", "store_group"):
+        f = getattr(L, "spdnn_%s_host" % name)
+        f.argtypes = [u32]
+        f.restype = u32
+    L.spdnn_lane_of_group_host.argtypes = [ctypes.c_int, ctypes.c_int]
+    L.spdnn_lane_of_group_host.restype = ctypes.c_int
+    return L
+
+
+def test_lane_sets_partition_the_wave(lay):
+    lanes = [lay.spdnn_lane_of_group_host(s, i) for s in range(4) for i in range(16)]
+    assert sorted(lanes) == list(range(64))
+    for s in range(4):
+        for i in range(16):
+            l = lay.spdnn_lane_of_group_host(s, i)
+            assert lay.spdnn_set_of_lane_host(l) == s and lay.spdnn_rank_in_set_host(l) == i
+    # the sets are whole quartets: {0,3,5,6}, {1,2,4,7} and both shifted by 8
+    quartets = [sorted({lay.spdnn_lane_of_group_host(s, i) >> 2 for i in range(16)}) for s in range(4)]
+    assert quartets == [[0, 3, 5, 6], [1, 2, 4, 7], [8, 11, 13, 14], [9, 10, 12, 15]]
+
+
+def test_tile_offset_interleaves_buffers_in_256_byte_rows(lay):
+    off = np.array([lay.spdnn_tile_offset_host(c) for c in range(KCAP)])
+    assert np.all(off % 16 == 0)
+    assert len(set(off.tolist())) == KCAP
+    assert np.all((off >> 4) % 16 == np.arange(KCAP) % 16)        # bank quad = slot mod 16
+    assert np.all((off // 256) % 2 == 0)                             # buffer 1 = +256
+    assert off.max() + 256 + 16 <= lay.spdnn_tile_pair_bytes_host(KCAP) == 2 * KCAP * 16
+    assert lay.spdnn_tile_pair_bytes_host(1) == 512 and lay.spdnn_tile_pair_bytes_host(1024) == 32768
+
+
+def test_fixed_layout_is_a_conflict_free_permutation(lay):
+    slot = np.array([lay.spdnn_col_slot_host(c) for c in range(KCAP)])
+    assert sorted(slot.tolist()) == list(range(KCAP))
+    # columns 4t .. 4t+3 of a staging lane: 512 bytes apart
+    off = np.array([lay.spdnn_tile_offset_host(int(s)) for s in slot])
+    for a in range(1, 4):
+        assert np.all(off[a::4] == off[0::4] + 512 * a)
+    # every store (fixed a) of every lane set hits 16 different quads
+    for wave in range(KCAP // 256):
+        for s in range(4):
+            lanes = [lay.spdnn_lane_of_group_host(s, i) for i in range(16)]
+            for a in range(4):
+                quads = {int(slot[4 * (wave * 64 + l) + a]) & 15 for l in lanes}
+                assert len(quads) == 16
+
+
+def test_store_groups_of_the_balanced_layout(lay):
+    grp = np.array([lay.spdnn_store_group_host(c) for c in range(KCAP)])
+    assert grp.min() == 0 and grp.max() == KCAP // 16 - 1
+    assert np.all(np.bincount(grp) == 16)
+    # a group = the columns 4t+a of the 16 lanes of one set of one wave
+    for g in range(KCAP // 16):
+        cols = np.nonzero(grp == g)[0]
+        assert len({int(c) & 3 for c in cols}) == 1
+        lanes = sorted(int(c) >> 2 for c in cols)
+        wave = lanes[0] >> 6
+        s = lay.spdnn_set_of_lane_host(lanes[0] & 63)
+        assert lanes == sorted(wave * 64 + lay.spdnn_lane_of_group_host(s, i) for i in range(16))
+    # a lane's four columns own consecutive 256-byte rows of the tile
+    off0 = np.array([lay.spdnn_tile_offset_host(int(g) << 4) for g in grp])
+    for a in range(1, 4):
+        assert np.all(off0[a::4] == off0[0::4] + 512 * a)
