@@ -155,7 +155,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic("cfg%d_L%d_batch%d_%s" % (a.config, L, batch, density)),
-                     "kernel": "fused_layer_kernel", "launches": int(launches),
+                     "kernel": sp.KERNEL_NAMES[model.layer_kernel(0)], "launches": int(launches),
                      "avg_launch_ms": sum_ms / max(launches, 1),
                      "algorithmic_bytes_per_launch": sum_bytes / max(launches, 1)},
     }

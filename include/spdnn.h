@@ -125,6 +125,20 @@ int spdnn_set_profiling(spdnn_t h, int32_t on);
 int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows_in,
                       float* fused_ms);
 
+/* Measurement and test aid: which of the library's fused kernels layer l runs on, chosen at
+ * spdnn_create from the layer's pattern (Section III-A-2's shared-memory stages) and weights:
+ * SPDNN_KERNEL_SINGLE  every 1024-neuron block's column window fits one LDS stage;
+ * SPDNN_KERNEL_STAGED  two stages (or a wider pattern that does not fit the wide format);
+ * SPDNN_KERNEL_WIDE    three or more stages;
+ * SPDNN_KERNEL_PAIR    one stage, every connection of the layer has the same weight and N is a
+ *                      multiple of 2048: two output neurons per lane.
+ * Returns SPDNN_EINVAL for a NULL handle or pointer or l outside [0, L). */
+#define SPDNN_KERNEL_SINGLE 0
+#define SPDNN_KERNEL_STAGED 1
+#define SPDNN_KERNEL_WIDE 2
+#define SPDNN_KERNEL_PAIR 3
+int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind);
+
 /* Measurement aid: enqueue a plain device-to-device copy kernel of `bytes` bytes (a multiple
  * of 16; both pointers 16-byte aligned, device memory) on the given stream.  It reads and
  * writes exactly `bytes` each, which calibrates profiler traffic counters. */

@@ -21,10 +21,16 @@ SPDNN_EHIP = -3
 SPDNN_ESIZE = -4
 SPDNN_HOST = 0
 SPDNN_DEVICE = 1
+SPDNN_KERNEL_SINGLE = 0
+SPDNN_KERNEL_STAGED = 1
+SPDNN_KERNEL_WIDE = 2
+SPDNN_KERNEL_PAIR = 3
 
 EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
            "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_copy_probe",
-           "spdnn_weights_bytes_for_window", "spdnn_scan_windows")
+           "spdnn_weights_bytes_for_window", "spdnn_scan_windows", "spdnn_layer_kernel")
+KERNEL_NAMES = {0: "fused_layer_kernel<false>", 1: "fused_layer_kernel<true>", 2: "fused_wide_kernel",
+                3: "fused_pair_kernel"}
 
 
 class SpdnnError(RuntimeError):
@@ -55,6 +61,7 @@ def lib():
         L.spdnn_copy_probe.argtypes = [vp, vp, sz, vp]
         L.spdnn_weights_bytes_for_window.argtypes = [i32, i32, i32, ctypes.POINTER(sz)]
         L.spdnn_scan_windows.argtypes = [i32, i32, ctypes.POINTER(vp), i32, vp, sz, vp, ctypes.POINTER(i32)]
+        L.spdnn_layer_kernel.argtypes = [vp, i32, ctypes.POINTER(i32)]
         for n in EXPORTS:
             if n != "spdnn_last_error":
                 getattr(L, n).restype = ctypes.c_int
@@ -137,6 +144,13 @@ def spdnn_get_profile(h, cap: int):
     return run.value, rows[:n], ms[:n]
 
 
+def spdnn_layer_kernel(h, l: int) -> int:
+    """Kernel kind (SPDNN_KERNEL_*: 0 single, 1 staged, 2 wide, 3 pair) of layer l."""
+    k = ctypes.c_int32(-1)
+    _check(lib().spdnn_layer_kernel(ctypes.c_void_p(h), l, ctypes.byref(k)))
+    return k.value
+
+
 def spdnn_copy_probe(dst_ptr, src_ptr, nbytes, stream=0) -> None:
     _check(lib().spdnn_copy_probe(ctypes.c_void_p(int(dst_ptr)), ctypes.c_void_p(int(src_ptr)), nbytes,
                                   ctypes.c_void_p(int(stream))))
@@ -214,6 +228,9 @@ class Model:
 
     def profile(self):
         return spdnn_get_profile(self.h, self.L)
+
+    def layer_kernel(self, l):
+        return spdnn_layer_kernel(self.h, l)
 
     def close(self):
         if getattr(self, "h", None):

@@ -42,12 +42,15 @@ inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 constexpr int kLag = 2;  // the host runs at most this many layers ahead of the GPU
 
-enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2 };
+enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2, kPair = 3 };
 struct LayerDesc {
     spdnn::LayerWeights w;
     spdnn::WideWeights ww;
-    int mode;      // kSingle: every window fits one LDS stage; kStaged: 2 stages (or fallback); kWide: 3+ stages
+    // kSingle: every window fits one LDS stage; kStaged: 2 stages (or fallback); kWide: 3+ stages;
+    // kPair: one stage, one weight for the whole layer, two output neurons per lane
+    int mode;
     int lds_cols;  // columns the LDS tile must hold for this layer
+    float wuni;    // kPair: the layer's weight
 };
 
 }  // namespace
@@ -90,7 +93,7 @@ size_t staging_bytes(int32_t N, int32_t L) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
     return up((size_t)N * spdnn::kNnz * sizeof(int32_t)) + up((size_t)N * spdnn::kNnz * sizeof(float)) +
            up((size_t)nblk * spdnn::kCap * sizeof(uint16_t)) +  // column -> LDS slot table of the layer being set up
-           up(sizeof(int) * (size_t)(2 * L + 1));  // error flag, per-layer wide failures, per-layer widest window
+           up(sizeof(int) * (size_t)(5 * L + 1));  // error flag; per layer: wide failure, widest window, weights differ, pair info[2]
 }
 size_t arena_bytes_for(int32_t N, int32_t L, int nstage_cap) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
@@ -282,8 +285,12 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::wide_pack_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch)));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<1>)));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<2>)));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
@@ -337,9 +344,10 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
     o += up((size_t)N * spdnn::kNnz * sizeof(float));
     uint16_t* slot_tab = reinterpret_cast<uint16_t*>(base + o);
     o += up((size_t)nblk * spdnn::kCap * sizeof(uint16_t));
-    // [0] bad column seen; [1 + l] layer l could not use the wide format; [1 + L + l] layer l's widest window
+    // [0] bad column seen; [1 + l] layer l could not use the wide format; [1 + L + l] layer l's widest window;
+    // [1 + 2L + l] layer l has more than one weight value; [1 + 3L + 2l] {two neurons per lane possible, weight bits}
     int* err_dev = reinterpret_cast<int*>(base + o);
-    HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int) * (size_t)(2 * L + 1), stream));
+    HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int) * (size_t)(5 * L + 1), stream));
 
     const size_t raw = (size_t)N * spdnn::kNnz;
     std::vector<int2> hw((size_t)L * nblk);
@@ -354,21 +362,34 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         }
         LayerDesc& d = m->layers[l];
         int* widest_dev = err_dev + 1 + L + l;
-        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev, widest_dev);
-        spdnn::balance_kernel<<<nblk, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch), stream>>>(
-            di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
+        int* pair_dev = err_dev + 1 + 3 * L + 2 * l;
+        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev, widest_dev, dv,
+                                                                       err_dev + 1 + 2 * L + l);
+        spdnn::pair_merge_kernel<<<1, 64, 0, stream>>>(win_dev[l], nblk, N, dv, err_dev + 1 + 2 * L + l, widest_dev,
+                                                       pair_dev);
+        HIP_TRY(hipGetLastError());
+        // the windows decide the layer's kernel and its set-up; they are small, so read them back now
+        int pair_info[2] = {0, 0};
+        HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipMemcpyAsync(pair_info, pair_dev, sizeof(pair_info), hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        const int pair = pair_info[0];
+        if (pair)
+            spdnn::balance_kernel<2><<<nblk / 2, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<2>), stream>>>(
+                di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
+        else
+            spdnn::balance_kernel<1><<<nblk, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<1>), stream>>>(
+                di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
         spdnn::order_pack_kernel<<<nblk, spdnn::kOrderThreads, order_lds, stream>>>(
-            di, dv, N, win_dev[l], widest_dev, slot_tab, const_cast<uint16_t*>(d.w.rel),
+            di, dv, N, win_dev[l], widest_dev, slot_tab, pair, const_cast<uint16_t*>(d.w.rel),
             const_cast<float*>(d.w.val));
         HIP_TRY(hipGetLastError());
-        // the windows decide the layer's kernel; they are small, so read them back now
-        HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
-        HIP_TRY(hipStreamSynchronize(stream));
         int widest = 4;
         for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[(size_t)l * nblk + b].y);
         const int nst = stages_of(widest);
         d.lds_cols = std::min(widest, spdnn::kCap);
-        d.mode = nst <= 1 ? kSingle : kStaged;
+        d.mode = pair ? kPair : nst <= 1 ? kSingle : kStaged;
+        std::memcpy(&d.wuni, &pair_info[1], sizeof(float));
         if (nst >= 3 && nst <= nstage_cap) {
             d.ww.nstage = nst;
             spdnn::wide_pack_kernel<<<nblk, spdnn::kOrderThreads, wide_lds, stream>>>(
@@ -416,6 +437,16 @@ int spdnn_set_profiling(spdnn_t h, int32_t on) {
     return SPDNN_OK;
 }
 
+int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind) {
+    if (!h || !kind) return fail(SPDNN_EINVAL, "null argument");
+    if (l < 0 || l >= h->L) return fail(SPDNN_EINVAL, "layer %d outside [0, %d)", l, h->L);
+    static_assert(kSingle == SPDNN_KERNEL_SINGLE && kStaged == SPDNN_KERNEL_STAGED && kWide == SPDNN_KERNEL_WIDE &&
+                      kPair == SPDNN_KERNEL_PAIR,
+                  "layer modes are the header's kernel kinds");
+    *kind = h->layers[l].mode;
+    return SPDNN_OK;
+}
+
 int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows_in, float* fused_ms) {
     if (!h || !layers_run) return fail(SPDNN_EINVAL, "null argument");
     *layers_run = h->prof_layers;
@@ -458,13 +489,19 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         float* Yout = wv.Y[l & 1];
         // launch shape: one workgroup per CU; the rows are cut into Q chunks per output block
         const int32_t ngroups = (bound + spdnn::kRows - 1) / spdnn::kRows;
-        int32_t Q = std::max(1, h->num_cu / h->nblk);
+        // kPair: the workgroups' column blocks are pairs of output blocks
+        const int32_t ncb = d.mode == kPair ? h->nblk / 2 : h->nblk;
+        const int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1) : h->G;
+        int32_t Q = std::max(1, h->num_cu / ncb);
         Q = std::max(1, std::min(Q, ngroups));
-        const int32_t units = (h->nblk / h->G) * Q;
-        const int32_t grid = (units + 7) / 8 * 8 * h->G;
+        const int32_t units = (ncb / G) * Q;
+        const int32_t grid = (units + 7) / 8 * 8 * G;
         const size_t lds = spdnn::tile_pair_bytes((d.lds_cols + 255) / 256 * 256);  // whole waves of 256 columns
         if (h->profiling) HIP_TRY(hipEventRecord(h->t0[l], s));
-        if (d.mode == kWide && d.ww.nstage > 8)
+        if (d.mode == kPair)
+            spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
+                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
+        else if (d.mode == kWide && d.ww.nstage > 8)
             spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(
                 Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
         else if (d.mode == kWide)

@@ -144,6 +144,115 @@ __device__ __forceinline__ void fma_block8(float (&acc)[4], const uint32_t (&o)[
 #undef SPDNN_FMA4
 }
 
+// Sixteen connections of one output neuron whose layer has one weight for all its
+// connections (held in a scalar register): acc[r] = fma(tile[col_k][r], w, acc[r]),
+// k = 0..15 in that order, four 16-byte LDS reads in flight throughout.
+template <int P>
+__device__ __forceinline__ void fma_block16s(float (&acc)[4], const uint32_t (&o)[16], float w) {
+    asm volatile(
+        "ds_read_b128 v[112:115], %[o0] offset:%[B]\n\t"
+        "ds_read_b128 v[116:119], %[o1] offset:%[B]\n\t"
+        "ds_read_b128 v[120:123], %[o2] offset:%[B]\n\t"
+        "ds_read_b128 v[124:127], %[o3] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v112\n\t"
+        "v_fmac_f32 %[a1], %[w], v113\n\t"
+        "v_fmac_f32 %[a2], %[w], v114\n\t"
+        "v_fmac_f32 %[a3], %[w], v115\n\t"
+        "ds_read_b128 v[112:115], %[o4] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v116\n\t"
+        "v_fmac_f32 %[a1], %[w], v117\n\t"
+        "v_fmac_f32 %[a2], %[w], v118\n\t"
+        "v_fmac_f32 %[a3], %[w], v119\n\t"
+        "ds_read_b128 v[116:119], %[o5] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "ds_read_b128 v[120:123], %[o6] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        "ds_read_b128 v[124:127], %[o7] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v112\n\t"
+        "v_fmac_f32 %[a1], %[w], v113\n\t"
+        "v_fmac_f32 %[a2], %[w], v114\n\t"
+        "v_fmac_f32 %[a3], %[w], v115\n\t"
+        "ds_read_b128 v[112:115], %[o8] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v116\n\t"
+        "v_fmac_f32 %[a1], %[w], v117\n\t"
+        "v_fmac_f32 %[a2], %[w], v118\n\t"
+        "v_fmac_f32 %[a3], %[w], v119\n\t"
+        "ds_read_b128 v[116:119], %[o9] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "ds_read_b128 v[120:123], %[o10] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        "ds_read_b128 v[124:127], %[o11] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v112\n\t"
+        "v_fmac_f32 %[a1], %[w], v113\n\t"
+        "v_fmac_f32 %[a2], %[w], v114\n\t"
+        "v_fmac_f32 %[a3], %[w], v115\n\t"
+        "ds_read_b128 v[112:115], %[o12] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v116\n\t"
+        "v_fmac_f32 %[a1], %[w], v117\n\t"
+        "v_fmac_f32 %[a2], %[w], v118\n\t"
+        "v_fmac_f32 %[a3], %[w], v119\n\t"
+        "ds_read_b128 v[116:119], %[o13] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "ds_read_b128 v[120:123], %[o14] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        "ds_read_b128 v[124:127], %[o15] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v112\n\t"
+        "v_fmac_f32 %[a1], %[w], v113\n\t"
+        "v_fmac_f32 %[a2], %[w], v114\n\t"
+        "v_fmac_f32 %[a3], %[w], v115\n\t"
+        "s_waitcnt lgkmcnt(2)\n\t"
+        "v_fmac_f32 %[a0], %[w], v116\n\t"
+        "v_fmac_f32 %[a1], %[w], v117\n\t"
+        "v_fmac_f32 %[a2], %[w], v118\n\t"
+        "v_fmac_f32 %[a3], %[w], v119\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3])
+        : [o0] "v"(o[0]), [o1] "v"(o[1]), [o2] "v"(o[2]), [o3] "v"(o[3]), [o4] "v"(o[4]), [o5] "v"(o[5]), [o6] "v"(o[6]), [o7] "v"(o[7]), [o8] "v"(o[8]), [o9] "v"(o[9]), [o10] "v"(o[10]), [o11] "v"(o[11]), [o12] "v"(o[12]), [o13] "v"(o[13]), [o14] "v"(o[14]), [o15] "v"(o[15]),
+          [w] "s"(w), [B] "n"(P * kBufSkew)
+        : "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123",
+          "v124", "v125", "v126", "v127", "memory");
+}
+
 // ---------------------------------------------------------------------------
 // a1: fused SpMM + bias + clipped ReLU for one layer (Eq. 1), plus the per-row
 // "has a positive output" flag that Listings 1 and 2 keep in active[].
@@ -385,6 +494,178 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     fetch_rows(0);
     load_tile(0);
     store_tile(0, 0);
+    if (T > 1) {
+        fetch_rows(1);
+        load_tile(1);
+    }
+    __syncthreads();
+    int t = 0;
+    for (; t + 1 < T; t += 2) {
+        step(t, P0{});
+        step(t + 1, P1{});
+    }
+    if (t < T) step(t, P0{});
+}
+
+// ---------------------------------------------------------------------------
+// a1 for layers whose connections all carry the same weight (the challenge networks:
+// 1/16 everywhere) and whose windows allow it: two output neurons per lane.
+//
+// With the weight in a scalar register a neuron needs 32 registers instead of 64, so
+// a lane takes neurons j and j + 1024 of a 2048-neuron unit (output blocks 2u and
+// 2u+1, set up with one common window and one common tile layout).  A staged tile
+// then serves 2048 outputs: half the tile loads, LDS tile writes and L2 -> CU bytes
+// per output.  Same pipeline as fused_layer_kernel<false>; nunit = number of units.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlk) void fused_pair_kernel(
+    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
+    int* __restrict__ flags, const int* __restrict__ count_ptr, LayerWeights w,
+    const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
+    extern __shared__ float4 lds4[];
+    const int tid = threadIdx.x;
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int unit = (slot / G) * 8 + xcd;
+    const int sub = slot - (slot / G) * G;
+    const int ngrp = nunit / G;
+    if (unit >= ngrp * Q) return;
+    const int q = unit / ngrp;
+    const int u = (unit - q * ngrp) * G + sub;
+    const int b = 2 * u;  // first of the unit's two output blocks
+
+    const int A = *count_ptr;
+    const int ngroups = (A + kRows - 1) / kRows;
+    const int per = (ngroups + Q - 1) / Q;
+    const int g0 = q * per;
+    const int g1 = min(ngroups, g0 + per);
+    if (g0 >= g1) return;
+
+    const int jA = b * kBlk + tid, jB = jA + kBlk;  // N is a multiple of 2048 here: both exist
+    const int2 win = w.win[b];
+    const int c_lo = win.x;
+    const int ncols = win.y;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
+
+    uint32_t offA[kNnz], offB[kNnz];
+    {
+        const uint16_t* prel = w.rel + (size_t)b * kNnz * kBlk + tid;
+#pragma unroll
+        for (int k = 0; k < kNnz; ++k) {
+            offA[k] = lds_base + tile_offset(prel[k * kBlk]);
+            offB[k] = lds_base + tile_offset(prel[(kNnz + k) * kBlk]);
+        }
+    }
+    const float bjA = bias[jA], bjB = bias[jB];
+
+    const int T = g1 - g0;
+    f32x4 st[kRows];
+    const int wave_col = (tid & ~63) * 4;
+    const uint32_t st_addr = lds_base + tile_offset(store_group(4 * tid) << 4);
+    const uint32_t qp = w.qsel[(size_t)b * kBlk + tid];
+    const int cat_last = cat[A - 1];
+    int4 c4 = make_int4(0, 0, 0, 0);
+
+    auto fetch_rows = [&](int t) { c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + t) * kRows); };
+    auto load_tile = [&](int t) {
+        if (wave_col >= ncols) return;
+        const int row0 = (g0 + t) * kRows;
+        const size_t coff = (size_t)c_lo + (size_t)min(4 * tid, ncols - 4);
+        st[0] = *reinterpret_cast<const f32x4*>(Yin + (size_t)c4.x * N + coff);
+        st[1] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N + coff);
+        st[2] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N + coff);
+        st[3] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N + coff);
+    };
+    auto store_tile = [&](int P) {
+        if (wave_col >= ncols) return;
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));  // first touch of the loaded tile
+        *reinterpret_cast<lds_f4*>(st_addr + (qp & 0xffu) + 0 * 512 + P * kBufSkew) =
+            f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
+        *reinterpret_cast<lds_f4*>(st_addr + ((qp >> 8) & 0xffu) + 1 * 512 + P * kBufSkew) =
+            f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
+        *reinterpret_cast<lds_f4*>(st_addr + ((qp >> 16) & 0xffu) + 2 * 512 + P * kBufSkew) =
+            f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
+        *reinterpret_cast<lds_f4*>(st_addr + (qp >> 24) + 3 * 512 + P * kBufSkew) =
+            f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+    };
+
+    float accA[kRows] = {0.f, 0.f, 0.f, 0.f}, accB[kRows] = {0.f, 0.f, 0.f, 0.f};
+    {
+        const int pw = __builtin_amdgcn_readfirstlane(3 - ((threadIdx.x >> 8) & 3));
+        if (pw == 1) __builtin_amdgcn_s_setprio(1);
+        else if (pw == 2) __builtin_amdgcn_s_setprio(2);
+        else if (pw == 3) __builtin_amdgcn_s_setprio(3);
+    }
+    auto compute = [&](auto Ptag, float (&acc)[kRows], const uint32_t (&off)[kNnz], auto Ktag) {
+        constexpr int P = decltype(Ptag)::value;
+        constexpr int k0 = decltype(Ktag)::value;
+        uint32_t o[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[i] = off[k0 + i];
+        fma_block16s<P>(acc, o, wuni);
+    };
+
+    const int lane = tid & 63;
+    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
+    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
+    const bool b0 = lane & 1, b1 = lane & 2;
+    // bias, clip, 4x4 transpose inside the lane quartet, one 16-byte store; returns the rows with a positive output
+    auto finish = [&](float (&acc)[kRows], float bj, int j, int row0, int nlive) -> unsigned {
+        float y0 = fminf(fmaxf(acc[0] + bj, 0.0f), kClip);
+        float y1 = fminf(fmaxf(acc[1] + bj, 0.0f), kClip);
+        float y2 = fminf(fmaxf(acc[2] + bj, 0.0f), kClip);
+        float y3 = fminf(fmaxf(acc[3] + bj, 0.0f), kClip);
+        acc[0] = acc[1] = acc[2] = acc[3] = 0.0f;
+        const unsigned pos = (__builtin_amdgcn_ballot_w64(y0 > 0.0f) != 0ull ? 1u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
+        {
+            const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
+            const float r0 = xor2(s0), r1 = xor2(s1);
+            y0 = b1 ? r0 : y0;
+            y1 = b1 ? r1 : y1;
+            y2 = b1 ? y2 : r0;
+            y3 = b1 ? y3 : r1;
+        }
+        {
+            const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
+            const float r0 = xor1(s0), r1 = xor1(s1);
+            y0 = b0 ? r0 : y0;
+            y1 = b0 ? y1 : r0;
+            y2 = b0 ? r1 : y2;
+            y3 = b0 ? y3 : r1;
+        }
+        const int r = lane & 3;
+        if (r < nlive)
+            *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
+        return pos;
+    };
+
+    // One step: neuron A's 32 connections, tile t+1 into the other buffer and the loads of
+    // tile t+2, neuron B's 32 connections, both epilogues.
+    using K0 = std::integral_constant<int, 0>;
+    using K16 = std::integral_constant<int, 16>;
+    auto step = [&](int t, auto Ptag) {
+        constexpr int P = decltype(Ptag)::value;
+        if (t + 2 < T) fetch_rows(t + 2);
+        compute(Ptag, accA, offA, K0{});
+        compute(Ptag, accA, offA, K16{});
+        if (t + 1 < T) store_tile(P ^ 1);
+        if (t + 2 < T) load_tile(t + 2);
+        compute(Ptag, accB, offB, K0{});
+        compute(Ptag, accB, offB, K16{});
+        const int row0 = (g0 + t) * kRows;
+        const int nlive = min(kRows, A - row0);
+        const unsigned pos = finish(accA, bjA, jA, row0, nlive) | finish(accB, bjB, jB, row0, nlive);
+        if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;
+        __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    fetch_rows(0);
+    load_tile(0);
+    store_tile(0);
     if (T > 1) {
         fetch_rows(1);
         load_tile(1);
@@ -735,7 +1016,9 @@ __global__ void gather_rows_kernel(const float4* __restrict__ src, const int* __
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __restrict__ idx, int N,
                                                             int2* __restrict__ win, int* __restrict__ err,
-                                                            int* __restrict__ widest) {
+                                                            int* __restrict__ widest,
+                                                            const float* __restrict__ val = nullptr,
+                                                            int* __restrict__ nonuniform = nullptr) {
     __shared__ int s_lo, s_hi;
     const int tid = threadIdx.x;
     const int j = blockIdx.x * kBlk + tid;
@@ -755,6 +1038,12 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
                 hi = max(hi, c);
             }
         }
+        if (val) {  // does the whole layer use one weight (bit for bit)?
+            const uint32_t w0 = __builtin_bit_cast(uint32_t, val[0]);
+            bool same = true;
+            for (int k = 0; k < kNnz; ++k) same = same && __builtin_bit_cast(uint32_t, val[(size_t)j * kNnz + k]) == w0;
+            if (!same) *nonuniform = 1;
+        }
     }
     atomicMin(&s_lo, lo);
     atomicMax(&s_hi, hi);
@@ -767,6 +1056,42 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
         }
         win[blockIdx.x] = make_int2(c_lo, ncols);
         atomicMax(widest, ncols);  // the layer's widest window (zero before the launch)
+    }
+}
+
+// Can the layer run two output neurons per lane (fused_pair_kernel)?  Yes if all its
+// weights are equal, N is a multiple of 2048 and the windows of output blocks 2u and
+// 2u+1 together span at most kCap columns for every u.  Then both blocks of a unit get
+// the common window.  info[0] = 1/0, info[1] = the weight's bits.  One workgroup.
+__global__ __launch_bounds__(64) void pair_merge_kernel(int2* __restrict__ win, int nblk, int N,
+                                                        const float* __restrict__ val,
+                                                        const int* __restrict__ nonuniform,
+                                                        int* __restrict__ widest, int* __restrict__ info) {
+    __shared__ int s_max;
+    const int t = threadIdx.x;
+    if (t == 0) s_max = 0;
+    __syncthreads();
+    const bool candidate = *nonuniform == 0 && (N % (2 * kBlk)) == 0;
+    if (candidate) {
+        for (int u = t; u < nblk / 2; u += 64) {
+            const int2 a = win[2 * u], c = win[2 * u + 1];
+            const int lo = min(a.x, c.x), hi = max(a.x + a.y, c.x + c.y);
+            atomicMax(&s_max, hi - lo);
+        }
+    }
+    __syncthreads();
+    const bool ok = candidate && s_max <= kCap;
+    if (ok) {
+        for (int u = t; u < nblk / 2; u += 64) {
+            const int2 a = win[2 * u], c = win[2 * u + 1];
+            const int lo = min(a.x, c.x), hi = max(a.x + a.y, c.x + c.y);
+            win[2 * u] = win[2 * u + 1] = make_int2(lo, hi - lo);
+        }
+        if (t == 0) atomicMax(widest, s_max);
+    }
+    if (t == 0) {
+        info[0] = ok ? 1 : 0;
+        info[1] = __builtin_bit_cast(int, val[0]);
     }
 }
 
@@ -787,36 +1112,40 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
 // One wave per output block.  Output: slot_tab[b][c] = LDS slot of stage-local column
 // c, qsel[b][t] = quads (times 16, one per byte) of staging lane t's four columns.
 // A layer with a wider window is left alone (order_pack_kernel then uses col_slot()).
+// UB = output blocks per unit: 1, or 2 for layers that run two neurons per lane (the
+// two blocks then share window, tile layout and staging quads, stored under the first).
+template <int UB>
 struct BalanceScratch {
-    uint32_t cursor[kCap];           // connections per column, then fill position
-    uint16_t ofs[kCap + 4];          // start of column c's entries in ent[]
-    uint8_t ent[kNnz * kBlk];        // lane set (0..63) of every connection, grouped by column
-    uint16_t load[kBlk / kGroup][16];  // connections lane set S already has in quad q
+    uint32_t cursor[kCap];                 // connections per column, then fill position
+    uint32_t ofs[kCap + 4];                // start of column c's entries in ent[]
+    uint8_t ent[UB * kNnz * kBlk];         // lane set (0..64*UB-1) of every connection, grouped by column
+    uint16_t load[UB * kBlk / kGroup][16];  // connections lane set S already has in quad q
     uint16_t cost[16][16];
 };
 constexpr int kBalanceThreads = 64;
+template <int UB>
 __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t* __restrict__ idx, int N,
                                                                   const int2* __restrict__ win,
                                                                   const int* __restrict__ widest,
                                                                   uint16_t* __restrict__ slot_tab,
                                                                   uint32_t* __restrict__ qsel) {
-    extern __shared__ BalanceScratch balance_scratch[];
-    BalanceScratch& B = balance_scratch[0];
+    extern __shared__ char balance_scratch[];
+    BalanceScratch<UB>& B = *reinterpret_cast<BalanceScratch<UB>*>(balance_scratch);
     if (*widest > kCap) return;
-    const int b = blockIdx.x;
+    const int b = blockIdx.x * UB;
     const int lane = threadIdx.x;
     const int c_lo = win[b].x;
     for (int c = lane; c < kCap; c += kBalanceThreads) B.cursor[c] = 0;
-    for (int i = lane; i < (kBlk / kGroup) * 16; i += kBalanceThreads) (&B.load[0][0])[i] = 0;
+    for (int i = lane; i < UB * (kBlk / kGroup) * 16; i += kBalanceThreads) (&B.load[0][0])[i] = 0;
     __syncthreads();
-    // stage-local column of connection e = (neuron << 5 | k) of this block, or -1
+    // stage-local column of connection e = (neuron << 5 | k) of this unit, or -1
     auto rel_of = [&](int e) -> int {
         const int j = b * kBlk + (e >> 5);
         if (j >= N) return -1;
         const int c = idx[(size_t)j * kNnz + (e & 31)];
         return (c < 0 || c >= N) ? 0 : c - c_lo;  // out-of-range columns were reported; keep them harmless
     };
-    for (int e = lane; e < kNnz * kBlk; e += kBalanceThreads) {
+    for (int e = lane; e < UB * kNnz * kBlk; e += kBalanceThreads) {
         const int r = rel_of(e);
         if (r >= 0) atomicAdd(&B.cursor[r], 1u);
     }
@@ -834,14 +1163,14 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
         uint32_t run = incl - sum;
         for (int i = 0; i < per; ++i) {
             const uint32_t n = B.cursor[lane * per + i];
-            B.ofs[lane * per + i] = (uint16_t)run;
+            B.ofs[lane * per + i] = run;
             B.cursor[lane * per + i] = run;
             run += n;
         }
-        if (lane == kBalanceThreads - 1) B.ofs[kCap] = (uint16_t)run;  // <= 32768
+        if (lane == kBalanceThreads - 1) B.ofs[kCap] = run;
     }
     __syncthreads();
-    for (int e = lane; e < kNnz * kBlk; e += kBalanceThreads) {
+    for (int e = lane; e < UB * kNnz * kBlk; e += kBalanceThreads) {
         const int r = rel_of(e);
         if (r < 0) continue;
         const uint32_t pos = atomicAdd(&B.cursor[r], 1u);
@@ -909,6 +1238,7 @@ __global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t
                                                                    const int2* __restrict__ win,
                                                                    const int* __restrict__ widest,
                                                                    const uint16_t* __restrict__ slot_tab,
+                                                                   int pair,  // the layer's tile layout is per two blocks
                                                                    uint16_t* __restrict__ rel,
                                                                    float* __restrict__ wval) {
     extern __shared__ OrderScratch order_scratch[];
@@ -924,7 +1254,7 @@ __global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t
     };
     // LDS slot of stage-local column r: from balance_kernel for single-stage layers
     const bool balanced = *widest <= kCap;
-    const uint16_t* tab = slot_tab + (size_t)b * kCap;
+    const uint16_t* tab = slot_tab + (size_t)(pair ? (b & ~1) : b) * kCap;
     auto slot_of = [&](uint32_t r) -> uint32_t { return balanced ? tab[r] : col_slot(r); };
     order_group(
         order_scratch[t], kNnz,

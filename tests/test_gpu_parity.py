@@ -220,3 +220,68 @@ def test_deterministic_and_device_weights():
     run, rows_in, ms = m.profile()
     assert run == 4 and rows_in[0] == 777 and np.all(np.diff(rows_in) <= 0) and np.all(ms > 0)
     m.close()
+
+
+def _uniform_model(rng, N, L, window, w=0.0625):
+    """Every neuron: 32 distinct columns inside the 'window'-wide span its 'window'-aligned group of
+    neurons shares; one weight for all connections."""
+    idx = []
+    for _ in range(L):
+        base = (np.arange(N) // window) * window
+        a = np.stack([b + rng.choice(min(window, N - b), 32, replace=False) for b in base])
+        idx.append(np.sort(a, axis=1).astype(np.int32))
+    val = [np.full((N, 32), w, dtype=np.float32) for _ in range(L)]
+    bias = np.full(N, -0.05, dtype=np.float32)
+    return idx, val, bias
+
+
+@pytest.mark.parametrize("N,L,batch,window,w", [
+    (2048, 3, 21, 2048, 0.0625),    # one unit of two output blocks
+    (6144, 2, 13, 2048, 0.0625),    # three units
+    (8192, 3, 50, 4096, 0.0625),    # two units share a window
+    (4096, 2, 9, 4096, 0.07),       # a weight that is not a power of two
+    (4096, 2, 1, 1024, -0.03),      # one negative weight for all: rows die after the first layer
+])
+def test_two_neurons_per_lane(N, L, batch, window, w):
+    """Layers with a single weight value run on the kernel with two output neurons per
+    lane; one different weight sends the same model to the one-neuron kernel.  Both
+    must agree with the oracle."""
+    import paper_2007_14152_amd as sp
+    rng = np.random.default_rng(N * 7 + L)
+    idx, val, bias = _uniform_model(rng, N, L, window, w)
+    Y0 = (rng.uniform(0, 1, size=(batch, N)) < 0.3).astype(np.float32)
+    ref = oracle.infer(idx, val, bias, Y0)
+    m = sp.Model(idx, val, bias)
+    assert [m.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_PAIR] * L
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    m.close()
+    check_against_oracle(ref, n, rows, Y, what="pair N=%d" % N)
+    # the same model with one weight changed by one ulp-ish amount in every layer: no longer uniform
+    val2 = [v.copy() for v in val]
+    for v in val2:
+        v[N // 2, 5] = np.float32(w) * np.float32(1.0 + 2.0 ** -20)
+    ref2 = oracle.infer(idx, val2, bias, Y0)
+    m2 = sp.Model(idx, val2, bias)
+    assert [m2.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_SINGLE] * L
+    n2, rows2, Y2 = gpu_infer(idx, val2, bias, Y0, model=m2)
+    m2.close()
+    check_against_oracle(ref2, n2, rows2, Y2, what="single N=%d" % N)
+
+
+def test_kernel_choice():
+    """Which fused kernel a layer gets (spdnn_layer_kernel)."""
+    import paper_2007_14152_amd as sp
+    rng = np.random.default_rng(5)
+    cases = [
+        (1024, 1024, sp.SPDNN_KERNEL_SINGLE),    # uniform weight, but N is not a multiple of 2048
+        (4096, 4096, sp.SPDNN_KERNEL_PAIR),
+        (8192, 8192, sp.SPDNN_KERNEL_STAGED),    # two LDS stages
+        (16384, 16384, sp.SPDNN_KERNEL_WIDE),     # four stages
+    ]
+    for N, window, kind in cases:
+        idx, val, bias = _uniform_model(rng, N, 1, window)
+        m = sp.Model(idx, val, bias)
+        assert m.layer_kernel(0) == kind, (N, window, m.layer_kernel(0))
+        with pytest.raises(sp.SpdnnError):
+            m.layer_kernel(1)
+        m.close()
