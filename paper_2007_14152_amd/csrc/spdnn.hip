@@ -42,12 +42,12 @@ inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 constexpr int kLag = 2;  // the host runs at most this many layers ahead of the GPU
 
-enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2, kPair = 3 };
+enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2, kPair = 3, kWidePair = 4 };
 struct LayerDesc {
     spdnn::LayerWeights w;
     spdnn::WideWeights ww;
     // kSingle: every window fits one LDS stage; kStaged: 2 stages (or fallback); kWide: 3+ stages;
-    // kPair: one stage, one weight for the whole layer, two output neurons per lane
+    // kPair: one stage, one weight for the whole layer, two output neurons per lane; kWidePair: the same for 3-8 stages
     int mode;
     int lds_cols;  // columns the LDS tile must hold for this layer
     float wuni;    // kPair: the layer's weight
@@ -87,7 +87,8 @@ size_t wide_bytes(int32_t nblk, int nstage) {
     const size_t e = (size_t)nblk * nstage * spdnn::wide_steps(nstage) * spdnn::kBlk;
     const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
     return up(e * sizeof(uint2)) + up((size_t)nblk * nstage * 16) + up(sp * sizeof(uint16_t)) +
-           up(sp * sizeof(float)) + up((size_t)nblk * 16);
+           up(sp * sizeof(float)) + up((size_t)nblk * 16) +
+           (spdnn::wide_steps(nstage) == 16 ? up(e * sizeof(uint16_t)) : 0);  // last: compact slots (3-8 stages)
 }
 size_t staging_bytes(int32_t N, int32_t L) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
@@ -291,6 +292,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<2>)));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + 2 * spdnn::kBufSkew));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
@@ -335,6 +338,10 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
             o += up(sp * sizeof(float));
             ww.spill_n = reinterpret_cast<uint8_t*>(base + o);
             o += up((size_t)nblk * 16);
+            if (spdnn::wide_steps(nstage_cap) == 16) {
+                ww.ps = reinterpret_cast<uint4*>(base + o);
+                o += up(we * sizeof(uint16_t));
+            }
         }
         m->layers[l].ww = ww;
     }
@@ -373,7 +380,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipMemcpyAsync(pair_info, pair_dev, sizeof(pair_info), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
-        const int pair = pair_info[0];
+        const int pair = pair_info[0] == 1;        // two neurons per lane, single stage
+        const bool wide_pair = pair_info[0] == 2;  // ... if the layer also fits the wide format
         if (pair)
             spdnn::balance_kernel<2><<<nblk / 2, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<2>), stream>>>(
                 di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
@@ -397,6 +405,13 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
                 const_cast<float*>(d.ww.spill_val), const_cast<uint8_t*>(d.ww.spill_n), err_dev + 1 + l);
             HIP_TRY(hipGetLastError());
             d.mode = kWide;
+            if (wide_pair && spdnn::wide_steps(nst) == 16 && d.ww.ps) {
+                const size_t n_out = (size_t)nblk * nst * 2 * spdnn::kBlk;
+                spdnn::wide_slots_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, stream>>>(
+                    d.ww.pk, const_cast<uint4*>(d.ww.ps), n_out);
+                HIP_TRY(hipGetLastError());
+                d.mode = kWidePair;
+            }
         }
         if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
     }
@@ -406,7 +421,7 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
     HIP_TRY(hipStreamSynchronize(stream));
     if (herr[0]) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
     for (int32_t l = 0; l < L; ++l)
-        if (m->layers[l].mode == kWide && herr[1 + l]) m->layers[l].mode = kStaged;
+        if ((m->layers[l].mode == kWide || m->layers[l].mode == kWidePair) && herr[1 + l]) m->layers[l].mode = kStaged;
     guard.m = nullptr;
     *out = m;
     return SPDNN_OK;
@@ -441,7 +456,7 @@ int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind) {
     if (!h || !kind) return fail(SPDNN_EINVAL, "null argument");
     if (l < 0 || l >= h->L) return fail(SPDNN_EINVAL, "layer %d outside [0, %d)", l, h->L);
     static_assert(kSingle == SPDNN_KERNEL_SINGLE && kStaged == SPDNN_KERNEL_STAGED && kWide == SPDNN_KERNEL_WIDE &&
-                      kPair == SPDNN_KERNEL_PAIR,
+                      kPair == SPDNN_KERNEL_PAIR && kWidePair == SPDNN_KERNEL_WIDE_PAIR,
                   "layer modes are the header's kernel kinds");
     *kind = h->layers[l].mode;
     return SPDNN_OK;
@@ -490,8 +505,11 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         // launch shape: one workgroup per CU; the rows are cut into Q chunks per output block
         const int32_t ngroups = (bound + spdnn::kRows - 1) / spdnn::kRows;
         // kPair: the workgroups' column blocks are pairs of output blocks
-        const int32_t ncb = d.mode == kPair ? h->nblk / 2 : h->nblk;
-        const int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1) : h->G;
+        const bool two = d.mode == kPair || d.mode == kWidePair;
+        const int32_t ncb = two ? h->nblk / 2 : h->nblk;
+        const int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1)
+                          : d.mode == kWidePair ? ((ncb % 4 == 0) ? 4 : (ncb % 3 == 0) ? 3 : (ncb % 2 == 0) ? 2 : 1)
+                                                : h->G;
         int32_t Q = std::max(1, h->num_cu / ncb);
         Q = std::max(1, std::min(Q, ngroups));
         const int32_t units = (ncb / G) * Q;
@@ -501,6 +519,9 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         if (d.mode == kPair)
             spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
                 Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
+        else if (d.mode == kWidePair)  // + the all-zero entries behind the tile pair
+            spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + 2 * spdnn::kBufSkew, s>>>(
+                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
         else if (d.mode == kWide && d.ww.nstage > 8)
             spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(
                 Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);

@@ -70,7 +70,11 @@ struct WideWeights {
     const uint8_t* spill_n;     // [nblk][16] most spilled connections of any lane of wave w
     const int2* win;            // [nblk] {c_lo, ncols}
     int nstage;
+    const uint4* ps;            // [nblk][nstage][S/8][kBlk] eight 16-bit LDS slots (0xFFFF = none) per 16-byte load:
+                                // the compact form fused_wide_pair_kernel reads (layers with a single weight value)
 };
+constexpr int kChunkPair = 4;        // row groups per chunk when a lane holds two neurons
+constexpr uint32_t kNoSlot = 0xFFFFu;
 __host__ __device__ inline int wide_steps(int nstage) { return nstage > 8 ? 8 : 16; }
 
 // Eight connections of one output neuron applied to the four rows of an LDS
@@ -248,6 +252,65 @@ __device__ __forceinline__ void fma_block16s(float (&acc)[4], const uint32_t (&o
         "v_fmac_f32 %[a3], %[w], v127\n\t"
         : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3])
         : [o0] "v"(o[0]), [o1] "v"(o[1]), [o2] "v"(o[2]), [o3] "v"(o[3]), [o4] "v"(o[4]), [o5] "v"(o[5]), [o6] "v"(o[6]), [o7] "v"(o[7]), [o8] "v"(o[8]), [o9] "v"(o[9]), [o10] "v"(o[10]), [o11] "v"(o[11]), [o12] "v"(o[12]), [o13] "v"(o[13]), [o14] "v"(o[14]), [o15] "v"(o[15]),
+          [w] "s"(w), [B] "n"(P * kBufSkew)
+        : "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123",
+          "v124", "v125", "v126", "v127", "memory");
+}
+
+// Eight connections, one scalar weight (see fma_block16s).
+template <int P>
+__device__ __forceinline__ void fma_block8s(float (&acc)[4], const uint32_t (&o)[8], float w) {
+    asm volatile(
+        "ds_read_b128 v[112:115], %[o0] offset:%[B]\n\t"
+        "ds_read_b128 v[116:119], %[o1] offset:%[B]\n\t"
+        "ds_read_b128 v[120:123], %[o2] offset:%[B]\n\t"
+        "ds_read_b128 v[124:127], %[o3] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v112\n\t"
+        "v_fmac_f32 %[a1], %[w], v113\n\t"
+        "v_fmac_f32 %[a2], %[w], v114\n\t"
+        "v_fmac_f32 %[a3], %[w], v115\n\t"
+        "ds_read_b128 v[112:115], %[o4] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v116\n\t"
+        "v_fmac_f32 %[a1], %[w], v117\n\t"
+        "v_fmac_f32 %[a2], %[w], v118\n\t"
+        "v_fmac_f32 %[a3], %[w], v119\n\t"
+        "ds_read_b128 v[116:119], %[o5] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "ds_read_b128 v[120:123], %[o6] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        "ds_read_b128 v[124:127], %[o7] offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v112\n\t"
+        "v_fmac_f32 %[a1], %[w], v113\n\t"
+        "v_fmac_f32 %[a2], %[w], v114\n\t"
+        "v_fmac_f32 %[a3], %[w], v115\n\t"
+        "s_waitcnt lgkmcnt(2)\n\t"
+        "v_fmac_f32 %[a0], %[w], v116\n\t"
+        "v_fmac_f32 %[a1], %[w], v117\n\t"
+        "v_fmac_f32 %[a2], %[w], v118\n\t"
+        "v_fmac_f32 %[a3], %[w], v119\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3])
+        : [o0] "v"(o[0]), [o1] "v"(o[1]), [o2] "v"(o[2]), [o3] "v"(o[3]), [o4] "v"(o[4]), [o5] "v"(o[5]), [o6] "v"(o[6]), [o7] "v"(o[7]),
           [w] "s"(w), [B] "n"(P * kBufSkew)
         : "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123",
           "v124", "v125", "v126", "v127", "memory");
@@ -892,6 +955,236 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// a1 for wide layers with one weight for the whole layer: two output neurons per lane
+// (j and j + 1024 of a 2048-neuron unit), as in fused_pair_kernel.  The stage's
+// connections are read in a compact form (16-bit LDS slots, no weights), a step that a
+// neuron does not fill reads an all-zero LDS entry kept behind the tile pair, and a
+// chunk is kChunkPair = 4 row groups so that the 32 accumulators per lane stay.  Every
+// staged tile serves 2048 outputs: half the tile traffic per output of
+// fused_wide_kernel.  S = 16 steps per stage only (3 to 8 stages).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
+    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
+    int* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
+    const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
+    constexpr int S = 16;
+    extern __shared__ float4 lds4[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    const int xcd = blockIdx.x & 7;
+    const int slotid = blockIdx.x >> 3;
+    const int unit = (slotid / G) * 8 + xcd;
+    const int sub = slotid - (slotid / G) * G;
+    const int ngrp = nunit / G;
+    if (unit >= ngrp * Q) return;
+    const int q = unit / ngrp;
+    const int u = (unit - q * ngrp) * G + sub;
+    const int b = 2 * u;  // first of the unit's two output blocks (same window for both)
+
+    const int A = *count_ptr;
+    const int ngroups = (A + kRows - 1) / kRows;
+    const int per = (ngroups + Q - 1) / Q;
+    const int g0 = q * per;
+    const int g1 = min(ngroups, g0 + per);
+    if (g0 >= g1) return;
+
+    const int jA = b * kBlk + tid, jB = jA + kBlk;  // N is a multiple of 2048 here
+    const int2 win = w.win[b];
+    const int c_lo = win.x;
+    const int ncols = win.y;
+    const int nstage = w.nstage;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
+    const uint32_t zero_addr = lds_base + tile_pair_bytes(kCap);  // 16 zero bytes here and 256 bytes further
+    if (tid < 2) {
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        *reinterpret_cast<lds_f4*>(zero_addr + tid * kBufSkew) = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const float bjA = bias[jA], bjB = bias[jB];
+
+    const int nchunk = (g1 - g0 + kChunkPair - 1) / kChunkPair;
+    const int per_chunk = nstage * kChunkPair;
+    const int T = nchunk * per_chunk;  // steps: (chunk, stage, tile); tiles past g1 repeat the last group
+
+    f32x4 st[kRows];
+    const int wave_col = (tid & ~63) * 4;
+    const uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));
+    const int cat_last = cat[A - 1];
+    int4 c4 = make_int4(0, 0, 0, 0);
+
+    auto group_of = [&](int t, int& s) -> int {
+        const int c = t / per_chunk;
+        const int rem = t - c * per_chunk;
+        s = rem / kChunkPair;
+        return min(g0 + c * kChunkPair + (rem - s * kChunkPair), g1 - 1);
+    };
+    auto fetch_rows = [&](int t) {
+        int s;
+        const int g = group_of(t, s);
+        c4 = *reinterpret_cast<const int4*>(cat + (size_t)g * kRows);
+    };
+    auto load_tile = [&](int t) {
+        int s;
+        const int g = group_of(t, s);
+        const int left = ncols - s * kCap;
+        if (wave_col >= left) return;
+        const int row0 = g * kRows;
+        const size_t coff = (size_t)c_lo + (size_t)s * kCap + (size_t)min(4 * tid, left - 4);
+        st[0] = *reinterpret_cast<const f32x4*>(Yin + (size_t)c4.x * N + coff);
+        st[1] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N + coff);
+        st[2] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N + coff);
+        st[3] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N + coff);
+    };
+    auto store_tile = [&](int P, int t) {
+        int s;
+        (void)group_of(t, s);
+        const int left = ncols - s * kCap;
+        if (wave_col >= left) return;
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
+        *reinterpret_cast<lds_f4*>(st_addr + 0 * 512 + P * kBufSkew) = f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
+        *reinterpret_cast<lds_f4*>(st_addr + 1 * 512 + P * kBufSkew) = f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
+        *reinterpret_cast<lds_f4*>(st_addr + 2 * 512 + P * kBufSkew) = f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
+        *reinterpret_cast<lds_f4*>(st_addr + 3 * 512 + P * kBufSkew) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+    };
+
+    float accA[kChunkPair][kRows], accB[kChunkPair][kRows];
+#pragma unroll
+    for (int i = 0; i < kChunkPair; ++i)
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) accA[i][r] = accB[i][r] = 0.0f;
+
+    uint32_t owA[S], owB[S];
+    int nbA = 0, nbB = 0;  // blocks of 8 steps my wave needs in the current stage, per neuron
+    auto unpack8 = [&](const uint4 v, uint32_t* o) {
+        const uint32_t x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = x[i] & 0xFFFFu, hi = x[i] >> 16;
+            o[2 * i] = lo == kNoSlot ? zero_addr : lds_base + tile_offset(lo);
+            o[2 * i + 1] = hi == kNoSlot ? zero_addr : lds_base + tile_offset(hi);
+        }
+    };
+    auto load_weights = [&](int s) {
+        const uint4* pA = w.ps + ((size_t)(b * nstage + s) * (S / 8)) * kBlk + tid;
+        const uint4* pB = w.ps + ((size_t)((b + 1) * nstage + s) * (S / 8)) * kBlk + tid;
+        unpack8(pA[0], owA);
+        unpack8(pA[kBlk], owA + 8);
+        unpack8(pB[0], owB);
+        unpack8(pB[kBlk], owB + 8);
+        nbA = w.nb8[(b * nstage + s) * 16 + wave];
+        nbB = w.nb8[((b + 1) * nstage + s) * 16 + wave];
+    };
+
+    const int nspillA = w.spill_n[b * 16 + wave], nspillB = w.spill_n[(b + 1) * 16 + wave];
+    // spilled connections (gathered from global memory), bias, clip, store of one neuron's 4 rows
+    auto finish = [&](float (&a)[kRows], float bj, int j, int blk, int nspill, int g, int nlive) -> unsigned {
+        const int row0 = g * kRows;
+        if (nspill > 0) {
+            const int4 cg = *reinterpret_cast<const int4*>(cat + (size_t)g * kRows);
+            const float* p0 = Yin + (size_t)cg.x * N + c_lo;
+            const float* p1 = Yin + (size_t)(nlive > 1 ? cg.y : cat_last) * N + c_lo;
+            const float* p2 = Yin + (size_t)(nlive > 2 ? cg.z : cat_last) * N + c_lo;
+            const float* p3 = Yin + (size_t)(nlive > 3 ? cg.w : cat_last) * N + c_lo;
+            for (int e = 0; e < nspill; ++e) {
+                const size_t se = ((size_t)blk * kSpill + e) * kBlk + tid;
+                const int col = w.spill_col[se];
+                const float v = w.spill_val[se];
+                a[0] = __builtin_fmaf(p0[col], v, a[0]);
+                a[1] = __builtin_fmaf(p1[col], v, a[1]);
+                a[2] = __builtin_fmaf(p2[col], v, a[2]);
+                a[3] = __builtin_fmaf(p3[col], v, a[3]);
+            }
+        }
+        const float y0 = fminf(fmaxf(a[0] + bj, 0.0f), kClip);
+        const float y1 = fminf(fmaxf(a[1] + bj, 0.0f), kClip);
+        const float y2 = fminf(fmaxf(a[2] + bj, 0.0f), kClip);
+        const float y3 = fminf(fmaxf(a[3] + bj, 0.0f), kClip);
+        a[0] = a[1] = a[2] = a[3] = 0.0f;
+        const unsigned pos = (__builtin_amdgcn_ballot_w64(y0 > 0.0f) != 0ull ? 1u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
+        float* dst = Yout + (size_t)row0 * N + j;
+        dst[0] = y0;
+        if (nlive > 1) dst[(size_t)N] = y1;
+        if (nlive > 2) dst[2 * (size_t)N] = y2;
+        if (nlive > 3) dst[3 * (size_t)N] = y3;
+        return pos;
+    };
+
+    auto block = [&](auto Ptag, float (&a)[kRows], const uint32_t* o) {
+        constexpr int P = decltype(Ptag)::value;
+        uint32_t o8[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) o8[k] = o[k];
+        fma_block8s<P>(a, o8, wuni);
+    };
+    // One step: neuron A's first 8 steps of the stage, the next tile into the other LDS
+    // buffer and the loads of the tile after it, then A's other 8 and B's 16.
+    auto step = [&](int t, auto Ptag, float (&aA)[kRows], float (&aB)[kRows]) {
+        constexpr int P = decltype(Ptag)::value;
+        if (t + 2 < T) fetch_rows(t + 2);
+        if (nbA > 0) block(Ptag, aA, owA);
+        if (t + 1 < T) store_tile(P ^ 1, t + 1);
+        if (t + 2 < T) load_tile(t + 2);
+        if (nbA > 1) block(Ptag, aA, owA + 8);
+        if (nbB > 0) block(Ptag, aB, owB);
+        if (nbB > 1) block(Ptag, aB, owB + 8);
+        __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+
+    fetch_rows(0);
+    load_tile(0);
+    store_tile(0, 0);
+    fetch_rows(1);
+    load_tile(1);
+    __syncthreads();
+    int t = 0;
+    for (int c = 0; c < nchunk; ++c) {
+        for (int s = 0; s < nstage; ++s) {
+            load_weights(s);
+#pragma unroll
+            for (int i = 0; i < kChunkPair; i += 2) {
+                step(t, P0{}, accA[i], accB[i]);
+                step(t + 1, P1{}, accA[i + 1], accB[i + 1]);
+                t += 2;
+            }
+        }
+        const int gbase = g0 + c * kChunkPair;
+#pragma unroll
+        for (int i = 0; i < kChunkPair; ++i)
+            if (gbase + i < g1) {
+                const int g = gbase + i;
+                const int nlive = min(kRows, A - g * kRows);
+                const unsigned pos = finish(accA[i], bjA, jA, b, nspillA, g, nlive) |
+                                     finish(accB[i], bjB, jB, b + 1, nspillB, g, nlive);
+                if (lane < nlive && ((pos >> lane) & 1u)) flags[g * kRows + lane] = 1;
+            }
+    }
+}
+
+// Compact form of a wide layer's steps for fused_wide_pair_kernel: the 16-bit LDS slot
+// of every step, 0xFFFF where the step carries no connection (weight 0 in pk).  One
+// thread per 16-byte output (eight steps of one lane).
+__global__ void wide_slots_kernel(const uint2* __restrict__ pk, uint4* __restrict__ ps, size_t n_out) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // = ((block*nstage + stage)*2 + octet)*kBlk + lane
+    if (i >= n_out) return;
+    const size_t lane = i % kBlk, bo = i / kBlk;                      // bo = (block*nstage + stage)*2 + octet
+    uint32_t h[8];
+    for (int k = 0; k < 8; ++k) {
+        // step 8*octet + k of this lane: pk index ((bs*8 + step/2)*kBlk + lane)*2 + step%2, bs = bo/2, step = 8*(bo%2)+k
+        const size_t step = 8 * (bo & 1) + k;
+        const uint2 e = pk[((((bo >> 1) * 8 + (step >> 1)) * kBlk + lane) << 1) | (step & 1)];
+        h[k] = e.y == 0u ? kNoSlot : (e.x & 0xFFFFu);
+    }
+    ps[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
+// ---------------------------------------------------------------------------
 // a2: active-row compaction (the host loop of Listing 1 between two layers,
 // moved onto the GPU).  Stable filter of the A rows whose flag is set:
 // cat_out[p] = slot in the buffer just written, gid_out[p] = original row id,
@@ -1059,10 +1352,12 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
     }
 }
 
-// Can the layer run two output neurons per lane (fused_pair_kernel)?  Yes if all its
-// weights are equal, N is a multiple of 2048 and the windows of output blocks 2u and
-// 2u+1 together span at most kCap columns for every u.  Then both blocks of a unit get
-// the common window.  info[0] = 1/0, info[1] = the weight's bits.  One workgroup.
+// Can the layer run two output neurons per lane?  Yes if all its weights are equal, N
+// is a multiple of 2048 and either the windows of output blocks 2u and 2u+1 together
+// span at most kCap columns for every u (info[0] = 1: fused_pair_kernel) or every block
+// needs 3 or more stages anyway (info[0] = 2: fused_wide_pair_kernel, if the pattern fits
+// the wide format).  Then both blocks of a unit get their common window.  info[0] = 0
+// otherwise; info[1] = the weight's bits.  One workgroup.
 __global__ __launch_bounds__(64) void pair_merge_kernel(int2* __restrict__ win, int nblk, int N,
                                                         const float* __restrict__ val,
                                                         const int* __restrict__ nonuniform,
@@ -1080,7 +1375,13 @@ __global__ __launch_bounds__(64) void pair_merge_kernel(int2* __restrict__ win, 
         }
     }
     __syncthreads();
-    const bool ok = candidate && s_max <= kCap;
+    // 1: one stage suffices for every unit; 2: every block needs 3 or more stages on its own
+    // (the wide format, which also profits from common windows); otherwise hands off
+    int s_min = 1 << 30;
+    for (int bb = 0; bb < nblk; ++bb) s_min = min(s_min, win[bb].y);
+    const int mode = !candidate ? 0 : s_max <= kCap ? 1 : s_min > 2 * kCap ? 2 : 0;
+    const bool ok = mode != 0;
+    __syncthreads();
     if (ok) {
         for (int u = t; u < nblk / 2; u += 64) {
             const int2 a = win[2 * u], c = win[2 * u + 1];
@@ -1090,7 +1391,7 @@ __global__ __launch_bounds__(64) void pair_merge_kernel(int2* __restrict__ win, 
         if (t == 0) atomicMax(widest, s_max);
     }
     if (t == 0) {
-        info[0] = ok ? 1 : 0;
+        info[0] = mode;
         info[1] = __builtin_bit_cast(int, val[0]);
     }
 }

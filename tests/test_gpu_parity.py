@@ -276,7 +276,8 @@ def test_kernel_choice():
         (1024, 1024, sp.SPDNN_KERNEL_SINGLE),    # uniform weight, but N is not a multiple of 2048
         (4096, 4096, sp.SPDNN_KERNEL_PAIR),
         (8192, 8192, sp.SPDNN_KERNEL_STAGED),    # two LDS stages
-        (16384, 16384, sp.SPDNN_KERNEL_WIDE),     # four stages
+        (16384, 16384, sp.SPDNN_KERNEL_WIDE_PAIR),  # four stages, one weight
+        (17408, 17408, sp.SPDNN_KERNEL_WIDE),       # five stages, N not a multiple of 2048
     ]
     for N, window, kind in cases:
         idx, val, bias = _uniform_model(rng, N, 1, window)
@@ -285,3 +286,34 @@ def test_kernel_choice():
         with pytest.raises(sp.SpdnnError):
             m.layer_kernel(1)
         m.close()
+
+
+@pytest.mark.parametrize("N,L,batch", [
+    (16384, 2, 19),    # four stages
+    (18432, 2, 6),     # the last stage is narrower than the others
+    (32768, 1, 5),     # eight stages
+])
+def test_wide_two_neurons_per_lane(N, L, batch):
+    """Wide layers with a single weight value: two output neurons per lane, compact
+    slots, zero entry for unused steps, spill list.  One different weight sends the
+    model to the one-neuron wide kernel."""
+    import paper_2007_14152_amd as sp
+    rng = np.random.default_rng(N + 3 * L)
+    idx, val, bias = _uniform_model(rng, N, L, N)
+    Y0 = (rng.uniform(0, 1, size=(batch, N)) < 0.3).astype(np.float32)
+    ref = oracle.infer(idx, val, bias, Y0)
+    m = sp.Model(idx, val, bias)
+    assert [m.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_WIDE_PAIR] * L
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    m.close()
+    common, _ = check_against_oracle(ref, n, rows, Y, what="wide pair N=%d" % N)
+    assert common > 0
+    val2 = [v.copy() for v in val]
+    for v in val2:
+        v[7, 0] = np.float32(0.0625 * (1.0 + 2.0 ** -20))
+    ref2 = oracle.infer(idx, val2, bias, Y0)
+    m2 = sp.Model(idx, val2, bias)
+    assert [m2.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_WIDE] * L
+    n2, rows2, Y2 = gpu_infer(idx, val2, bias, Y0, model=m2)
+    m2.close()
+    check_against_oracle(ref2, n2, rows2, Y2, what="wide N=%d" % N)
