@@ -507,9 +507,16 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         // kPair: the workgroups' column blocks are pairs of output blocks
         const bool two = d.mode == kPair || d.mode == kWidePair;
         const int32_t ncb = two ? h->nblk / 2 : h->nblk;
-        const int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1)
-                          : d.mode == kWidePair ? ((ncb % 4 == 0) ? 4 : (ncb % 3 == 0) ? 3 : (ncb % 2 == 0) ? 2 : 1)
-                                                : h->G;
+        // Workgroups that read the same rows go to one XCD (32 CUs, one L2).  In a wide layer every
+        // column block reads whole rows: as many of them as possible share an XCD, so that a row is
+        // fetched from memory once, not once per XCD.
+        int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1) : h->G;
+        if (d.mode == kWide || d.mode == kWidePair)
+            for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
+                if (ncb % g == 0) {
+                    G = g;
+                    break;
+                }
         int32_t Q = std::max(1, h->num_cu / ncb);
         Q = std::max(1, std::min(Q, ngroups));
         const int32_t units = (ncb / G) * Q;
