@@ -2,8 +2,10 @@
 
 One step = one spdnn_infer over the whole synthetic batch (all layers: fused
 SpMM+bias+clipped-ReLU, active-row compaction, buffer swap, final gather) with
-inputs and weights already resident in HBM.  Prints one JSON line; see the design doc
-for the meaning of every field.
+inputs and weights already resident in HBM.  Prints one JSON line: value = nominal
+edges (batch*N*32*L) per second; roofline = algorithmic bytes of the fused-kernel
+launches (rows*N*8 + N*32*6 each) over their summed durations, against peak HBM
+bandwidth; cpu_baseline = the oracle on a seeded sample of rows of the same workload.
 """
 import argparse
 import json

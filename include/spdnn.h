@@ -59,8 +59,9 @@ int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes);
  * than the arena was sized for run a slower kernel. */
 int spdnn_weights_bytes_for_window(int32_t N, int32_t L, int32_t widest_window, size_t* bytes);
 
-/* Widest column range (in columns) of any 1024-neuron block of any layer.  idx as for
- * spdnn_create.  scratch_dev: device memory, 256-byte aligned, at least N*32*4 + 2*N/128 +
+/* Widest column range (in columns) of any 1024-neuron block of any layer -- when N is a
+ * multiple of 2048, of any aligned pair of such blocks, which is what layers that run two
+ * neurons per lane use.  idx as for spdnn_create.  scratch_dev: device memory, 256-byte aligned, at least N*32*4 + 2*N/128 +
  * 1024 bytes, contents scratch.  Blocks until done.  SPDNN_EINVAL on a column outside [0, N). */
 int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t where, void* scratch_dev,
                        size_t scratch_bytes, void* hip_stream, int32_t* widest_window);

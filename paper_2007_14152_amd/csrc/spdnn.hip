@@ -207,6 +207,13 @@ int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t 
         HIP_TRY(hipMemcpyAsync(hw.data(), win, sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
         for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[b].y);
+        // layers that run two neurons per lane give blocks 2u and 2u+1 their common window
+        if (N % (2 * spdnn::kBlk) == 0)
+            for (int32_t b = 0; b + 1 < nblk; b += 2) {
+                const int lo = std::min(hw[b].x, hw[b + 1].x);
+                const int hi = std::max(hw[b].x + hw[b].y, hw[b + 1].x + hw[b + 1].y);
+                widest = std::max(widest, hi - lo);
+            }
     }
     int herr = 0;
     HIP_TRY(hipMemcpy(&herr, err, sizeof(int), hipMemcpyDeviceToHost));
