@@ -50,7 +50,8 @@ struct LayerDesc {
     // kPair: one stage, one weight for the whole layer, two output neurons per lane; kWidePair: the same for 3-8 stages
     int mode;
     int lds_cols;  // columns the LDS tile must hold for this layer
-    float wuni;    // kPair: the layer's weight
+    float wuni;    // kPair, kWidePair: the layer's weight
+    bool pair4;    // kWidePair: 3 or 4 stages -> slot lists resident in registers
 };
 
 }  // namespace
@@ -88,7 +89,8 @@ size_t wide_bytes(int32_t nblk, int nstage) {
     const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
     return up(e * sizeof(uint2)) + up((size_t)nblk * nstage * 16) + up(sp * sizeof(uint16_t)) +
            up(sp * sizeof(float)) + up((size_t)nblk * 16) +
-           (spdnn::wide_steps(nstage) == 16 ? up(e * sizeof(uint16_t)) : 0);  // last: compact slots (3-8 stages)
+           (spdnn::wide_steps(nstage) == 16 ? up(e * sizeof(uint16_t)) + up(sp * sizeof(uint16_t))
+                                            : 0);  // last: compact slots and spills (3-8 stages)
 }
 size_t staging_bytes(int32_t N, int32_t L) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
@@ -301,6 +303,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + 2 * spdnn::kBufSkew));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
@@ -348,6 +352,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
             if (spdnn::wide_steps(nstage_cap) == 16) {
                 ww.ps = reinterpret_cast<uint4*>(base + o);
                 o += up(we * sizeof(uint16_t));
+                ww.sp16 = reinterpret_cast<uint16_t*>(base + o);
+                o += up(sp * sizeof(uint16_t));
             }
         }
         m->layers[l].ww = ww;
@@ -416,8 +422,12 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
                 const size_t n_out = (size_t)nblk * nst * 2 * spdnn::kBlk;
                 spdnn::wide_slots_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, stream>>>(
                     d.ww.pk, const_cast<uint4*>(d.ww.ps), n_out);
+                const size_t n_sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
+                spdnn::wide_spill16_kernel<<<(unsigned)((n_sp + 255) / 256), 256, 0, stream>>>(
+                    d.ww.spill_col, d.ww.spill_val, const_cast<uint16_t*>(d.ww.sp16), n_sp);
                 HIP_TRY(hipGetLastError());
                 d.mode = kWidePair;
+                d.pair4 = nst <= 4;
             }
         }
         if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
@@ -533,7 +543,10 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         if (d.mode == kPair)
             spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
                 Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
-        else if (d.mode == kWidePair)  // + the all-zero entries behind the tile pair
+        else if (d.mode == kWidePair && d.pair4)  // + the all-zero entries and the spill table behind the tile pair
+            spdnn::fused_wide_pair4_kernel<<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
+                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+        else if (d.mode == kWidePair)
             spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + 2 * spdnn::kBufSkew, s>>>(
                 Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
         else if (d.mode == kWide && d.ww.nstage > 8)

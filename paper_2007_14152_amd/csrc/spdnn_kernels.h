@@ -72,6 +72,8 @@ struct WideWeights {
     int nstage;
     const uint4* ps;            // [nblk][nstage][S/8][kBlk] eight 16-bit LDS slots (0xFFFF = none) per 16-byte load:
                                 // the compact form fused_wide_pair_kernel reads (layers with a single weight value)
+    const uint16_t* sp16;       // [nblk][kSpill][kBlk] spilled connections as stage << 14 | (LDS tile byte offset >> 4)
+                                // (0xFFFF = none), for fused_wide_pair4_kernel
 };
 constexpr int kChunkPair = 4;        // row groups per chunk when a lane holds two neurons
 constexpr uint32_t kNoSlot = 0xFFFFu;
@@ -314,6 +316,76 @@ __device__ __forceinline__ void fma_block8s(float (&acc)[4], const uint32_t (&o)
           [w] "s"(w), [B] "n"(P * kBufSkew)
         : "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123",
           "v124", "v125", "v126", "v127", "memory");
+}
+
+// Eight connections whose LDS addresses are packed two per register as (byte address >> 4)
+// in 16 bits each, one scalar weight.  An SDWA shift turns a half into the byte address,
+// written into the first register of the read's own destination.  sh4 (scalar) holds 4.  Two reads
+// in flight (with 16 waves per CU the LDS stays busy at this depth, and the kernel that
+// uses this block needs the registers).
+template <int P>
+__device__ __forceinline__ void fma_block8ps(float (&acc)[4], uint32_t p0, uint32_t p1, uint32_t p2, uint32_t p3,
+                                             float w, uint32_t sh4) {
+    asm volatile(
+        "v_lshlrev_b32_sdwa v120, %[s4], %[p0] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b128 v[120:123], v120 offset:%[B]\n\t"
+        "v_lshlrev_b32_sdwa v124, %[s4], %[p0] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b128 v[124:127], v124 offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "v_lshlrev_b32_sdwa v120, %[s4], %[p1] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b128 v[120:123], v120 offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        "v_lshlrev_b32_sdwa v124, %[s4], %[p1] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b128 v[124:127], v124 offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "v_lshlrev_b32_sdwa v120, %[s4], %[p2] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b128 v[120:123], v120 offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        "v_lshlrev_b32_sdwa v124, %[s4], %[p2] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b128 v[124:127], v124 offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "v_lshlrev_b32_sdwa v120, %[s4], %[p3] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b128 v[120:123], v120 offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        "v_lshlrev_b32_sdwa v124, %[s4], %[p3] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b128 v[124:127], v124 offset:%[B]\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_fmac_f32 %[a2], %[w], v122\n\t"
+        "v_fmac_f32 %[a3], %[w], v123\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_fmac_f32 %[a2], %[w], v126\n\t"
+        "v_fmac_f32 %[a3], %[w], v127\n\t"
+        : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3])
+        : [p0] "v"(p0), [p1] "v"(p1), [p2] "v"(p2), [p3] "v"(p3), [w] "s"(w), [s4] "s"(sh4), [B] "n"(P * kBufSkew)
+        : "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "memory");
 }
 
 // ---------------------------------------------------------------------------
@@ -1167,6 +1239,245 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// a1 for wide layers of 3 or 4 stages with one weight for the whole layer: two output
+// neurons per lane with the slot lists of ALL stages resident in registers (two 16-bit
+// LDS addresses per register: 4 stages x 16 steps x 2 neurons = 64 registers), so that
+// nothing but tiles is read inside the loop and a stage never waits for its step list.
+// A step is (row group, stage); every row group takes 4 steps (the last one idle when
+// there are 3 stages, which keeps the tile buffers alternating).  Unused steps read the
+// all-zero entry behind the tile pair.  The connections beyond the 16 steps of a stage
+// (up to kSpill per neuron) sit in a small LDS table and are read from the tile in their
+// stage's step like the others.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
+    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
+    int* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
+    const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
+    constexpr int S = 16, NS = 4;
+    extern __shared__ float4 lds4[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    const int xcd = blockIdx.x & 7;
+    const int slotid = blockIdx.x >> 3;
+    const int unit = (slotid / G) * 8 + xcd;
+    const int sub = slotid - (slotid / G) * G;
+    const int ngrp = nunit / G;
+    if (unit >= ngrp * Q) return;
+    const int q = unit / ngrp;
+    const int u = (unit - q * ngrp) * G + sub;
+    const int b = 2 * u;
+
+    const int A = *count_ptr;
+    const int ngroups = (A + kRows - 1) / kRows;
+    const int per = (ngroups + Q - 1) / Q;
+    const int g0 = q * per;
+    const int g1 = min(ngroups, g0 + per);
+    if (g0 >= g1) return;
+
+    const int jA = b * kBlk + tid;  // neuron B is jA + kBlk; N is a multiple of 2048 here
+    const int2 win = w.win[b];
+    const int c_lo = win.x;
+    const int ncols = win.y;
+    const int nstage = w.nstage;  // 3 or 4
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
+    const uint32_t zero_addr = lds_base + tile_pair_bytes(kCap);  // 16 zero bytes here and 256 bytes further
+    if (tid < 2) {
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        *reinterpret_cast<lds_f4*>(zero_addr + tid * kBufSkew) = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const float bjA = bias[jA], bjB = bias[jA + kBlk];
+    uint32_t sh4 = 4;
+    asm volatile("" : "+s"(sh4));  // the shift count of fma_block8ps, kept in a scalar register
+
+    // step lists of both neurons, all stages: word i of stage s = steps 2i, 2i+1 as (LDS byte address >> 4)
+    uint32_t pA[NS * S / 2], pB[NS * S / 2];
+    int nbA[NS], nbB[NS];  // blocks of 8 steps my wave needs per stage and neuron
+    {
+        const uint32_t zero16 = zero_addr >> 4, base16 = lds_base >> 4;
+        auto conv = [&](uint32_t two) -> uint32_t {
+            const uint32_t lo = two & 0xFFFFu, hi = two >> 16;
+            const uint32_t a = lo == kNoSlot ? zero16 : base16 + (tile_offset(lo) >> 4);
+            const uint32_t c = hi == kNoSlot ? zero16 : base16 + (tile_offset(hi) >> 4);
+            return a | (c << 16);
+        };
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (s < nstage) {
+                const uint4* qA = w.ps + ((size_t)(b * nstage + s) * (S / 8)) * kBlk + tid;
+                const uint4* qB = w.ps + ((size_t)((b + 1) * nstage + s) * (S / 8)) * kBlk + tid;
+#pragma unroll
+                for (int o = 0; o < 2; ++o) {
+                    const uint4 va = qA[o * kBlk], vb = qB[o * kBlk];
+                    pA[s * 8 + o * 4 + 0] = conv(va.x);
+                    pA[s * 8 + o * 4 + 1] = conv(va.y);
+                    pA[s * 8 + o * 4 + 2] = conv(va.z);
+                    pA[s * 8 + o * 4 + 3] = conv(va.w);
+                    pB[s * 8 + o * 4 + 0] = conv(vb.x);
+                    pB[s * 8 + o * 4 + 1] = conv(vb.y);
+                    pB[s * 8 + o * 4 + 2] = conv(vb.z);
+                    pB[s * 8 + o * 4 + 3] = conv(vb.w);
+                }
+                nbA[s] = __builtin_amdgcn_readfirstlane((int)w.nb8[(b * nstage + s) * 16 + wave]);
+                nbB[s] = __builtin_amdgcn_readfirstlane((int)w.nb8[((b + 1) * nstage + s) * 16 + wave]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pA[s * 8 + i] = pB[s * 8 + i] = zero16 | (zero16 << 16);
+                nbA[s] = nbB[s] = 0;
+            }
+        }
+    }
+
+    // Spilled connections: entry e of neuron A (B) of lane t at spill_tab + ((2e (+1)) * kBlk + t) * 2,
+    // stage << 14 | (LDS byte address >> 4), 0xFFFF = none.
+    const uint32_t spill_tab = zero_addr + 2 * kBufSkew;
+    const int nspillA = w.spill_n[b * 16 + wave], nspillB = w.spill_n[(b + 1) * 16 + wave];
+    bool anyA[NS] = {false, false, false, false}, anyB[NS] = {false, false, false, false};
+    {
+        using lds_u16 = __attribute__((address_space(3))) uint16_t;
+#pragma unroll
+        for (int e = 0; e < kSpill; ++e) {
+            const uint32_t va = w.sp16[((size_t)b * kSpill + e) * kBlk + tid];
+            const uint32_t vb = w.sp16[((size_t)(b + 1) * kSpill + e) * kBlk + tid];
+            *reinterpret_cast<lds_u16*>(spill_tab + ((2 * e) * kBlk + tid) * 2) = (uint16_t)va;
+            *reinterpret_cast<lds_u16*>(spill_tab + ((2 * e + 1) * kBlk + tid) * 2) = (uint16_t)vb;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                anyA[s] = anyA[s] || __builtin_amdgcn_ballot_w64(va != 0xFFFFu && (va >> 14) == (uint32_t)s) != 0ull;
+                anyB[s] = anyB[s] || __builtin_amdgcn_ballot_w64(vb != 0xFFFFu && (vb >> 14) == (uint32_t)s) != 0ull;
+            }
+        }
+    }
+    auto spilled = [&](auto Ptag, float (&acc)[kRows], int which, int nspill, int s) {
+        constexpr int P = decltype(Ptag)::value;
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        using lds_u16 = __attribute__((address_space(3))) uint16_t;
+        for (int e = 0; e < nspill; ++e) {
+            const uint32_t v = *reinterpret_cast<const lds_u16*>(spill_tab + ((2 * e + which) * kBlk + tid) * 2);
+            const uint32_t addr = (v != 0xFFFFu && (v >> 14) == (uint32_t)s) ? lds_base + ((v & 0x3FFFu) << 4) : zero_addr;
+            const f32x4 y = *reinterpret_cast<const lds_f4*>(addr + P * kBufSkew);
+            acc[0] = __builtin_fmaf(y.x, wuni, acc[0]);
+            acc[1] = __builtin_fmaf(y.y, wuni, acc[1]);
+            acc[2] = __builtin_fmaf(y.z, wuni, acc[2]);
+            acc[3] = __builtin_fmaf(y.w, wuni, acc[3]);
+        }
+    };
+
+    const int T = (g1 - g0) * NS;  // steps; step t = (row group t / 4, stage t % 4)
+    f32x4 st[kRows];
+    const int wave_col = (tid & ~63) * 4;
+    const uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));
+    const int cat_last = cat[A - 1];
+    int4 c4 = make_int4(0, 0, 0, 0);
+
+    auto fetch_rows = [&](int t) { c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + (t >> 2)) * kRows); };
+    // column (in floats) of my four staged columns: the same in every full stage, clamped in a narrower last one
+    const uint32_t col_full = (uint32_t)(c_lo + 4 * tid);
+    const uint32_t col_last = (uint32_t)(c_lo + (nstage - 1) * kCap + min(4 * tid, ncols - (nstage - 1) * kCap - 4));
+    auto load_tile = [&](int t) {
+        const int s = t & 3;
+        const int left = ncols - s * kCap;  // <= 0 for the idle fourth step of a 3-stage layer
+        if (wave_col >= left) return;
+        const int row0 = (g0 + (t >> 2)) * kRows;
+        const uint32_t col = s == nstage - 1 ? col_last : col_full + (uint32_t)(s * kCap);
+        const float* r0 = Yin + (size_t)c4.x * N;  // row bases are the same for the whole workgroup
+        const float* r1 = Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N;
+        const float* r2 = Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N;
+        const float* r3 = Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N;
+        st[0] = *reinterpret_cast<const f32x4*>(r0 + col);
+        st[1] = *reinterpret_cast<const f32x4*>(r1 + col);
+        st[2] = *reinterpret_cast<const f32x4*>(r2 + col);
+        st[3] = *reinterpret_cast<const f32x4*>(r3 + col);
+    };
+    auto store_tile = [&](int P, int t) {
+        const int left = ncols - (t & 3) * kCap;
+        if (wave_col >= left) return;
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
+        *reinterpret_cast<lds_f4*>(st_addr + 0 * 512 + P * kBufSkew) = f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
+        *reinterpret_cast<lds_f4*>(st_addr + 1 * 512 + P * kBufSkew) = f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
+        *reinterpret_cast<lds_f4*>(st_addr + 2 * 512 + P * kBufSkew) = f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
+        *reinterpret_cast<lds_f4*>(st_addr + 3 * 512 + P * kBufSkew) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+    };
+
+    float accA[kRows] = {0.f, 0.f, 0.f, 0.f}, accB[kRows] = {0.f, 0.f, 0.f, 0.f};
+    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
+    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
+    const bool b0 = lane & 1, b1 = lane & 2;
+    // bias, clip, 4x4 transpose inside the lane quartet, one 16-byte store
+    auto finish = [&](float (&a)[kRows], float bj, int j, int g, int nlive) -> unsigned {
+        const int row0 = g * kRows;
+        float y0 = fminf(fmaxf(a[0] + bj, 0.0f), kClip);
+        float y1 = fminf(fmaxf(a[1] + bj, 0.0f), kClip);
+        float y2 = fminf(fmaxf(a[2] + bj, 0.0f), kClip);
+        float y3 = fminf(fmaxf(a[3] + bj, 0.0f), kClip);
+        a[0] = a[1] = a[2] = a[3] = 0.0f;
+        const unsigned pos = (__builtin_amdgcn_ballot_w64(y0 > 0.0f) != 0ull ? 1u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
+                             (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
+        {
+            const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
+            const float r0 = xor2(s0), r1 = xor2(s1);
+            y0 = b1 ? r0 : y0;
+            y1 = b1 ? r1 : y1;
+            y2 = b1 ? y2 : r0;
+            y3 = b1 ? y3 : r1;
+        }
+        {
+            const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
+            const float r0 = xor1(s0), r1 = xor1(s1);
+            y0 = b0 ? r0 : y0;
+            y1 = b0 ? y1 : r0;
+            y2 = b0 ? r1 : y2;
+            y3 = b0 ? y3 : r1;
+        }
+        const int r = lane & 3;
+        if (r < nlive)
+            *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
+        return pos;
+    };
+
+    // One step with compile-time tile buffer P and stage s.
+    auto step = [&](int t, auto Ptag, auto Stag) {
+        constexpr int P = decltype(Ptag)::value;
+        constexpr int s = decltype(Stag)::value;
+        if (t + 2 < T) fetch_rows(t + 2);
+        if (nbA[s] > 0) fma_block8ps<P>(accA, pA[s * 8 + 0], pA[s * 8 + 1], pA[s * 8 + 2], pA[s * 8 + 3], wuni, sh4);
+        if (t + 1 < T) store_tile(P ^ 1, t + 1);
+        if (t + 2 < T) load_tile(t + 2);
+        if (nbA[s] > 1) fma_block8ps<P>(accA, pA[s * 8 + 4], pA[s * 8 + 5], pA[s * 8 + 6], pA[s * 8 + 7], wuni, sh4);
+        if (nbB[s] > 0) fma_block8ps<P>(accB, pB[s * 8 + 0], pB[s * 8 + 1], pB[s * 8 + 2], pB[s * 8 + 3], wuni, sh4);
+        if (nbB[s] > 1) fma_block8ps<P>(accB, pB[s * 8 + 4], pB[s * 8 + 5], pB[s * 8 + 6], pB[s * 8 + 7], wuni, sh4);
+        if (anyA[s]) spilled(Ptag, accA, 0, nspillA, s);
+        if (anyB[s]) spilled(Ptag, accB, 1, nspillB, s);
+        if (s >= 2 && s == nstage - 1) {  // s is a compile-time constant: no epilogue code in the first two steps
+            const int g = g0 + (t >> 2);
+            const int nlive = min(kRows, A - g * kRows);
+            const unsigned pos = finish(accA, bjA, jA, g, nlive) | finish(accB, bjB, jA + kBlk, g, nlive);
+            if (lane < nlive && ((pos >> lane) & 1u)) flags[g * kRows + lane] = 1;
+        }
+        __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+
+    fetch_rows(0);
+    load_tile(0);
+    store_tile(0, 0);
+    fetch_rows(1);
+    load_tile(1);
+    __syncthreads();
+    for (int t = 0; t < T; t += NS) {
+        step(t, P0{}, std::integral_constant<int, 0>{});
+        step(t + 1, P1{}, std::integral_constant<int, 1>{});
+        step(t + 2, P0{}, std::integral_constant<int, 2>{});
+        step(t + 3, P1{}, std::integral_constant<int, 3>{});
+    }
+}
+
 // Compact form of a wide layer's steps for fused_wide_pair_kernel: the 16-bit LDS slot
 // of every step, 0xFFFF where the step carries no connection (weight 0 in pk).  One
 // thread per 16-byte output (eight steps of one lane).
@@ -1182,6 +1493,21 @@ __global__ void wide_slots_kernel(const uint2* __restrict__ pk, uint4* __restric
         h[k] = e.y == 0u ? kNoSlot : (e.x & 0xFFFFu);
     }
     ps[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
+// Spilled connections in the form fused_wide_pair4_kernel keeps in LDS: stage << 14 | (tile byte
+// offset of the column's entry >> 4), 0xFFFF where the list has no entry.  One thread per entry.
+constexpr int kPair4LdsExtra = 2 * kBufSkew + 2 * kSpill * kBlk * 2;  // zero entries + spill table behind the tile pair
+__global__ void wide_spill16_kernel(const uint16_t* __restrict__ spill_col, const float* __restrict__ spill_val,
+                                    uint16_t* __restrict__ sp16, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // (block * kSpill + e) * kBlk + lane
+    if (i >= n) return;
+    uint32_t out = 0xFFFFu;
+    if (spill_val[i] != 0.0f) {  // weight 0 = no connection
+        const uint32_t rel = spill_col[i];  // column - c_lo: stage << 12 | column inside the stage
+        out = ((rel >> kCapLog2) << 14) | (tile_offset(col_slot(rel & (kCap - 1))) >> 4);
+    }
+    sp16[i] = (uint16_t)out;
 }
 
 // ---------------------------------------------------------------------------

@@ -317,3 +317,28 @@ def test_wide_two_neurons_per_lane(N, L, batch):
     n2, rows2, Y2 = gpu_infer(idx, val2, bias, Y0, model=m2)
     m2.close()
     check_against_oracle(ref2, n2, rows2, Y2, what="wide N=%d" % N)
+
+
+def test_wide_two_neurons_per_lane_three_stages():
+    """Three LDS stages (the fourth step of every row group is idle): every neuron has 11, 11
+    and 10 connections in the three 4096-column stages, a few neurons 17 + 15 + 0 (one spilled)."""
+    import paper_2007_14152_amd as sp
+    N, L, batch = 12288, 2, 10
+    rng = np.random.default_rng(77)
+    idx = []
+    for _ in range(L):
+        a = np.empty((N, 32), dtype=np.int64)
+        for j in range(N):
+            counts = (17, 15, 0) if j % 997 == 0 else (11, 11, 10)
+            a[j] = np.concatenate([s0 * 4096 + rng.choice(4096, c, replace=False) for s0, c in enumerate(counts)])
+        idx.append(np.sort(a, axis=1).astype(np.int32))
+    val = [np.full((N, 32), 0.0625, dtype=np.float32) for _ in range(L)]
+    bias = np.full(N, -0.05, dtype=np.float32)
+    Y0 = (rng.uniform(0, 1, size=(batch, N)) < 0.3).astype(np.float32)
+    ref = oracle.infer(idx, val, bias, Y0)
+    m = sp.Model(idx, val, bias)
+    assert [m.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_WIDE_PAIR] * L
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    m.close()
+    common, _ = check_against_oracle(ref, n, rows, Y, what="wide pair, 3 stages")
+    assert common > 0
