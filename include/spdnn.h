@@ -133,13 +133,16 @@ int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows
  * SPDNN_KERNEL_WIDE    three or more stages;
  * SPDNN_KERNEL_PAIR    one stage, every connection of the layer has the same weight and N is a
  *                      multiple of 2048: two output neurons per lane;
- * SPDNN_KERNEL_WIDE_PAIR  the same for three to eight stages.
+ * SPDNN_KERNEL_WIDE_PAIR  the same for five to eight stages;
+ * SPDNN_KERNEL_WIDE_PAIR4 the same for three or four stages (the step lists of all stages stay in
+ *                      registers).
  * Returns SPDNN_EINVAL for a NULL handle or pointer or l outside [0, L). */
 #define SPDNN_KERNEL_SINGLE 0
 #define SPDNN_KERNEL_STAGED 1
 #define SPDNN_KERNEL_WIDE 2
 #define SPDNN_KERNEL_PAIR 3
 #define SPDNN_KERNEL_WIDE_PAIR 4
+#define SPDNN_KERNEL_WIDE_PAIR4 5
 int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind);
 
 /* Measurement aid: enqueue a plain device-to-device copy kernel of `bytes` bytes (a multiple

@@ -26,12 +26,13 @@ SPDNN_KERNEL_STAGED = 1
 SPDNN_KERNEL_WIDE = 2
 SPDNN_KERNEL_PAIR = 3
 SPDNN_KERNEL_WIDE_PAIR = 4
+SPDNN_KERNEL_WIDE_PAIR4 = 5
 
 EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
            "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_copy_probe",
            "spdnn_weights_bytes_for_window", "spdnn_scan_windows", "spdnn_layer_kernel")
 KERNEL_NAMES = {0: "fused_layer_kernel<false>", 1: "fused_layer_kernel<true>", 2: "fused_wide_kernel",
-                3: "fused_pair_kernel", 4: "fused_wide_pair_kernel"}
+                3: "fused_pair_kernel", 4: "fused_wide_pair_kernel", 5: "fused_wide_pair4_kernel"}
 
 
 class SpdnnError(RuntimeError):
@@ -146,7 +147,7 @@ def spdnn_get_profile(h, cap: int):
 
 
 def spdnn_layer_kernel(h, l: int) -> int:
-    """Kernel kind (SPDNN_KERNEL_*: 0 single, 1 staged, 2 wide, 3 pair, 4 wide pair) of layer l."""
+    """Kernel kind (SPDNN_KERNEL_*: 0 single, 1 staged, 2 wide, 3 pair, 4 wide pair, 5 wide pair of 3-4 stages) of layer l."""
     k = ctypes.c_int32(-1)
     _check(lib().spdnn_layer_kernel(ctypes.c_void_p(h), l, ctypes.byref(k)))
     return k.value

@@ -475,7 +475,7 @@ int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind) {
     static_assert(kSingle == SPDNN_KERNEL_SINGLE && kStaged == SPDNN_KERNEL_STAGED && kWide == SPDNN_KERNEL_WIDE &&
                       kPair == SPDNN_KERNEL_PAIR && kWidePair == SPDNN_KERNEL_WIDE_PAIR,
                   "layer modes are the header's kernel kinds");
-    *kind = h->layers[l].mode;
+    *kind = (h->layers[l].mode == kWidePair && h->layers[l].pair4) ? SPDNN_KERNEL_WIDE_PAIR4 : h->layers[l].mode;
     return SPDNN_OK;
 }
 

@@ -276,7 +276,7 @@ def test_kernel_choice():
         (1024, 1024, sp.SPDNN_KERNEL_SINGLE),    # uniform weight, but N is not a multiple of 2048
         (4096, 4096, sp.SPDNN_KERNEL_PAIR),
         (8192, 8192, sp.SPDNN_KERNEL_STAGED),    # two LDS stages
-        (16384, 16384, sp.SPDNN_KERNEL_WIDE_PAIR),  # four stages, one weight
+        (16384, 16384, sp.SPDNN_KERNEL_WIDE_PAIR4),  # four stages, one weight
         (17408, 17408, sp.SPDNN_KERNEL_WIDE),       # five stages, N not a multiple of 2048
     ]
     for N, window, kind in cases:
@@ -303,7 +303,8 @@ def test_wide_two_neurons_per_lane(N, L, batch):
     Y0 = (rng.uniform(0, 1, size=(batch, N)) < 0.3).astype(np.float32)
     ref = oracle.infer(idx, val, bias, Y0)
     m = sp.Model(idx, val, bias)
-    assert [m.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_WIDE_PAIR] * L
+    want = sp.SPDNN_KERNEL_WIDE_PAIR4 if N <= 16384 else sp.SPDNN_KERNEL_WIDE_PAIR
+    assert [m.layer_kernel(l) for l in range(L)] == [want] * L
     n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
     m.close()
     common, _ = check_against_oracle(ref, n, rows, Y, what="wide pair N=%d" % N)
@@ -337,7 +338,7 @@ def test_wide_two_neurons_per_lane_three_stages():
     Y0 = (rng.uniform(0, 1, size=(batch, N)) < 0.3).astype(np.float32)
     ref = oracle.infer(idx, val, bias, Y0)
     m = sp.Model(idx, val, bias)
-    assert [m.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_WIDE_PAIR] * L
+    assert [m.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_WIDE_PAIR4] * L
     n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
     m.close()
     common, _ = check_against_oracle(ref, n, rows, Y, what="wide pair, 3 stages")
