@@ -1519,11 +1519,12 @@ __global__ void wide_spill16_kernel(const uint16_t* __restrict__ spill_col, cons
 // stream sync.
 //
 // One workgroup, three phases per 65536 rows, so that no phase is a chain of
-// dependent round trips: (1) every thread reads its flag in each of up to 64
-// rounds of 1024 rows (all loads in flight together), remembers them as bits and
-// a wave64 ballot gives each wave's count per round; (2) the 64 x 16 counts are
-// scanned once by the whole workgroup; (3) every thread re-derives its rank from
-// a ballot of its remembered bit and writes its rows out.
+// dependent round trips: (1) every thread reads its flag and its row number in each
+// of up to 64 rounds of 1024 rows (16 loads in flight at a time), remembers the
+// flags as bits and a wave64 ballot gives each wave's count per round; (2) the
+// 64 x 16 counts are scanned once by the whole workgroup; (3) every thread
+// re-derives its rank from a ballot of its remembered bit and writes its rows out
+// (no loads left in this phase).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void compact_kernel(int* __restrict__ flags, int* __restrict__ count,
                                                        const int* __restrict__ gid_in,
@@ -1539,12 +1540,17 @@ __global__ __launch_bounds__(1024) void compact_kernel(int* __restrict__ flags, 
     for (int chunk0 = 0; chunk0 < A; chunk0 += 65536) {
         const int nr = min(64, (A - chunk0 + 1023) >> 10);
         unsigned long long mine = 0ull;
-        for (int r0 = 0; r0 < nr; r0 += 8) {  // 8 rounds per batch so that 8 loads are in flight
+        int g[64];  // original row number of my row of round r (all loop indices below are compile-time)
+#pragma unroll
+        for (int r0 = 0; r0 < 64; r0 += 8) {  // 8 rounds per batch: 16 loads in flight
+            if (r0 >= nr) continue;
             int f[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int i = chunk0 + ((r0 + u) << 10) + tid;
-                f[u] = (r0 + u < nr && i < A) ? flags[i] : 0;
+                const bool ok = r0 + u < nr && i < A;
+                f[u] = ok ? flags[i] : 0;
+                g[r0 + u] = ok ? gid_in[i] : 0;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
@@ -1576,23 +1582,15 @@ __global__ __launch_bounds__(1024) void compact_kernel(int* __restrict__ flags, 
         }
         tot[tid] = wbase + incl - v;
         __syncthreads();
-        for (int r0 = 0; r0 < nr; r0 += 8) {
-            int g[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = chunk0 + ((r0 + u) << 10) + tid;
-                g[u] = ((mine >> (r0 + u)) & 1ull) ? gid_in[i] : 0;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int r = r0 + u;
-                const bool keep = (mine >> r) & 1ull;  // bits of rounds >= nr are never set
-                const unsigned long long m = __ballot(keep);
-                if (keep) {
-                    const int p = base + tot[r * 16 + wave] + __popcll(m & ((1ull << lane) - 1ull));
-                    cat_out[p] = chunk0 + (r << 10) + tid;
-                    gid_out[p] = g[u];
-                }
+        for (int r = 0; r < 64; ++r) {
+            if (r >= nr) continue;
+            const bool keep = (mine >> r) & 1ull;
+            const unsigned long long m = __ballot(keep);
+            if (keep) {
+                const int p = base + tot[r * 16 + wave] + __popcll(m & ((1ull << lane) - 1ull));
+                cat_out[p] = chunk0 + (r << 10) + tid;
+                gid_out[p] = g[r];
             }
         }
         base += total;
