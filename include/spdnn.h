@@ -53,7 +53,7 @@ int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes);
 /* Same, for a model in which the input columns used by any block of 1024 consecutive
  * output neurons span at most widest_window columns (as spdnn_scan_windows reports).  The
  * tiling of Section III-A-2 stages a block's column range through LDS 4096 columns at a
- * time; ranges of 3 or more stages use a larger weight layout, which this accounts for.
+ * time; ranges of 2 or more stages use a larger weight layout, which this accounts for.
  * spdnn_create accepts any arena of at least this size; with a smaller one than
  * spdnn_weights_bytes says it still works for every pattern, but layers with wider ranges
  * than the arena was sized for run a slower kernel. */
@@ -134,7 +134,7 @@ int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows
  * SPDNN_KERNEL_PAIR    one stage, every connection of the layer has the same weight and N is a
  *                      multiple of 2048: two output neurons per lane;
  * SPDNN_KERNEL_WIDE_PAIR  the same for five to eight stages;
- * SPDNN_KERNEL_WIDE_PAIR4 the same for three or four stages (the step lists of all stages stay in
+ * SPDNN_KERNEL_WIDE_PAIR4 the same for two to four stages (the step lists of all stages stay in
  *                      registers).
  * Returns SPDNN_EINVAL for a NULL handle or pointer or l outside [0, L). */
 #define SPDNN_KERNEL_SINGLE 0

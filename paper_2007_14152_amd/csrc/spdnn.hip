@@ -83,14 +83,22 @@ size_t layer_bytes(int32_t nblk) {
 }
 int stages_of(int32_t window) { return (window + spdnn::kCap - 1) / spdnn::kCap; }
 // extra bytes per layer for the wide format with up to `nstage` stages (0 if not needed)
+// Steps per neuron the wide format needs at most, for a layer of 2 .. nstage stages (an
+// arena sized for nstage stages also holds layers with fewer, which may use more steps per stage).
+size_t wide_steps_max(int nstage) {
+    size_t m = 0;
+    for (int n = 2; n <= nstage; ++n) m = std::max(m, (size_t)n * spdnn::wide_steps(n));
+    return m;
+}
+bool wide_has_slots(int nstage) { return nstage <= 8; }  // the compact 16-bit form exists for 2..8 stages
 size_t wide_bytes(int32_t nblk, int nstage) {
-    if (nstage < 3) return 0;
-    const size_t e = (size_t)nblk * nstage * spdnn::wide_steps(nstage) * spdnn::kBlk;
+    if (nstage < 2) return 0;
+    const size_t e = (size_t)nblk * wide_steps_max(nstage) * spdnn::kBlk;
     const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
     return up(e * sizeof(uint2)) + up((size_t)nblk * nstage * 16) + up(sp * sizeof(uint16_t)) +
            up(sp * sizeof(float)) + up((size_t)nblk * 16) +
-           (spdnn::wide_steps(nstage) == 16 ? up(e * sizeof(uint16_t)) + up(sp * sizeof(uint16_t))
-                                            : 0);  // last: compact slots and spills (3-8 stages)
+           (wide_has_slots(nstage) ? up(e * sizeof(uint16_t)) + up(sp * sizeof(uint16_t))
+                                   : 0);  // last: compact slots and spills
 }
 size_t staging_bytes(int32_t N, int32_t L) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
@@ -245,8 +253,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
     // The arena decides how many stages the wide format may use (0 = none: layers with
     // wide windows then run the staged kernel, which is slower but needs no extra room).
     int nstage_cap = stages_of(N);
-    while (nstage_cap > 2 && arena_bytes_for(N, L, nstage_cap) > weights_arena_bytes) --nstage_cap;
-    if (nstage_cap < 3) nstage_cap = 0;
+    while (nstage_cap > 1 && arena_bytes_for(N, L, nstage_cap) > weights_arena_bytes) --nstage_cap;
+    if (nstage_cap < 2) nstage_cap = 0;
     {
         const size_t need = arena_bytes_for(N, L, nstage_cap);
         if (weights_arena_bytes < need)
@@ -303,7 +311,9 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + 2 * spdnn::kBufSkew));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel),
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<4, 16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<2, 32>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
@@ -336,8 +346,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         win_dev[l] = win;
         spdnn::WideWeights ww{};
         ww.win = win;
-        if (nstage_cap >= 3) {  // room for the wide format; the layer's own stage count strides the arrays
-            const size_t we = (size_t)nblk * nstage_cap * spdnn::wide_steps(nstage_cap) * spdnn::kBlk;
+        if (nstage_cap >= 2) {  // room for the wide format; the layer's own stage count strides the arrays
+            const size_t we = (size_t)nblk * wide_steps_max(nstage_cap) * spdnn::kBlk;
             const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
             ww.pk = reinterpret_cast<uint2*>(base + o);
             o += up(we * sizeof(uint2));
@@ -349,7 +359,7 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
             o += up(sp * sizeof(float));
             ww.spill_n = reinterpret_cast<uint8_t*>(base + o);
             o += up((size_t)nblk * 16);
-            if (spdnn::wide_steps(nstage_cap) == 16) {
+            if (wide_has_slots(nstage_cap)) {
                 ww.ps = reinterpret_cast<uint4*>(base + o);
                 o += up(we * sizeof(uint16_t));
                 ww.sp16 = reinterpret_cast<uint16_t*>(base + o);
@@ -411,17 +421,19 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
         d.lds_cols = std::min(widest, spdnn::kCap);
         d.mode = pair ? kPair : nst <= 1 ? kSingle : kStaged;
         std::memcpy(&d.wuni, &pair_info[1], sizeof(float));
-        if (nst >= 3 && nst <= nstage_cap) {
+        // the wide format: 3 and more stages, or 2 stages when the layer can run two neurons per lane
+        if ((nst >= 3 || (nst == 2 && wide_pair && d.ww.ps)) && nst <= nstage_cap) {
             d.ww.nstage = nst;
             spdnn::wide_pack_kernel<<<nblk, spdnn::kOrderThreads, wide_lds, stream>>>(
                 di, dv, N, win_dev[l], nst, const_cast<uint2*>(d.ww.pk), const_cast<uint8_t*>(d.ww.nb8), const_cast<uint16_t*>(d.ww.spill_col),
                 const_cast<float*>(d.ww.spill_val), const_cast<uint8_t*>(d.ww.spill_n), err_dev + 1 + l);
             HIP_TRY(hipGetLastError());
             d.mode = kWide;
-            if (wide_pair && spdnn::wide_steps(nst) == 16 && d.ww.ps) {
-                const size_t n_out = (size_t)nblk * nst * 2 * spdnn::kBlk;
+            if (wide_pair && spdnn::wide_steps(nst) >= 16 && d.ww.ps) {
+                const int S = spdnn::wide_steps(nst);
+                const size_t n_out = (size_t)nblk * nst * (S / 8) * spdnn::kBlk;
                 spdnn::wide_slots_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, stream>>>(
-                    d.ww.pk, const_cast<uint4*>(d.ww.ps), n_out);
+                    d.ww.pk, const_cast<uint4*>(d.ww.ps), n_out, S);
                 const size_t n_sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
                 spdnn::wide_spill16_kernel<<<(unsigned)((n_sp + 255) / 256), 256, 0, stream>>>(
                     d.ww.spill_col, d.ww.spill_val, const_cast<uint16_t*>(d.ww.sp16), n_sp);
@@ -543,8 +555,11 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         if (d.mode == kPair)
             spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
                 Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
-        else if (d.mode == kWidePair && d.pair4)  // + the all-zero entries and the spill table behind the tile pair
-            spdnn::fused_wide_pair4_kernel<<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
+        else if (d.mode == kWidePair && d.pair4 && d.ww.nstage == 2)  // + the all-zero entries and the spill table
+            spdnn::fused_wide_pair4_kernel<2, 32><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
+                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+        else if (d.mode == kWidePair && d.pair4)
+            spdnn::fused_wide_pair4_kernel<4, 16><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
                 Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
         else if (d.mode == kWidePair)
             spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + 2 * spdnn::kBufSkew, s>>>(

@@ -77,7 +77,9 @@ struct WideWeights {
 };
 constexpr int kChunkPair = 4;        // row groups per chunk when a lane holds two neurons
 constexpr uint32_t kNoSlot = 0xFFFFu;
-__host__ __device__ inline int wide_steps(int nstage) { return nstage > 8 ? 8 : 16; }
+// Steps per stage of the wide format: 2 stages exist only for layers that run two neurons per
+// lane with all their steps in registers (2 x 32 = 4 x 16 = 64 steps per neuron).
+__host__ __device__ inline int wide_steps(int nstage) { return nstage > 8 ? 8 : nstage <= 2 ? 32 : 16; }
 
 // Eight connections of one output neuron applied to the four rows of an LDS
 // tile: acc[r] = fma(tile[col_k][r], w_k, acc[r]) for k = 0..7 in that order.
@@ -1240,9 +1242,10 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// a1 for wide layers of 3 or 4 stages with one weight for the whole layer: two output
+// a1 for wide layers of 2 to 4 stages with one weight for the whole layer: two output
 // neurons per lane with the slot lists of ALL stages resident in registers (two 16-bit
-// LDS addresses per register: 4 stages x 16 steps x 2 neurons = 64 registers), so that
+// LDS addresses per register: 4 stages x 16 steps, or 2 stages x 32 steps, x 2 neurons =
+// 64 registers), so that
 // nothing but tiles is read inside the loop and a stage never waits for its step list.
 // A step is (row group, stage); every row group takes 4 steps (the last one idle when
 // there are 3 stages, which keeps the tile buffers alternating).  Unused steps read the
@@ -1250,11 +1253,13 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
 // (up to kSpill per neuron) sit in a small LDS table and are read from the tile in their
 // stage's step like the others.
 // ---------------------------------------------------------------------------
+template <int NS, int S>
 __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
     int* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
-    constexpr int S = 16, NS = 4;
+    static_assert(NS * S == 64 && (NS == 2 || NS == 4), "64 steps per neuron");
+    constexpr int LNS = NS == 4 ? 2 : 1;  // log2(NS)
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -1281,7 +1286,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     const int2 win = w.win[b];
     const int c_lo = win.x;
     const int ncols = win.y;
-    const int nstage = w.nstage;  // 3 or 4
+    const int nstage = w.nstage;  // NS = 4: 3 or 4; NS = 2: 2
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
     const uint32_t zero_addr = lds_base + tile_pair_bytes(kCap);  // 16 zero bytes here and 256 bytes further
     if (tid < 2) {
@@ -1309,22 +1314,22 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
                 const uint4* qA = w.ps + ((size_t)(b * nstage + s) * (S / 8)) * kBlk + tid;
                 const uint4* qB = w.ps + ((size_t)((b + 1) * nstage + s) * (S / 8)) * kBlk + tid;
 #pragma unroll
-                for (int o = 0; o < 2; ++o) {
+                for (int o = 0; o < S / 8; ++o) {
                     const uint4 va = qA[o * kBlk], vb = qB[o * kBlk];
-                    pA[s * 8 + o * 4 + 0] = conv(va.x);
-                    pA[s * 8 + o * 4 + 1] = conv(va.y);
-                    pA[s * 8 + o * 4 + 2] = conv(va.z);
-                    pA[s * 8 + o * 4 + 3] = conv(va.w);
-                    pB[s * 8 + o * 4 + 0] = conv(vb.x);
-                    pB[s * 8 + o * 4 + 1] = conv(vb.y);
-                    pB[s * 8 + o * 4 + 2] = conv(vb.z);
-                    pB[s * 8 + o * 4 + 3] = conv(vb.w);
+                    pA[s * (S / 2) + o * 4 + 0] = conv(va.x);
+                    pA[s * (S / 2) + o * 4 + 1] = conv(va.y);
+                    pA[s * (S / 2) + o * 4 + 2] = conv(va.z);
+                    pA[s * (S / 2) + o * 4 + 3] = conv(va.w);
+                    pB[s * (S / 2) + o * 4 + 0] = conv(vb.x);
+                    pB[s * (S / 2) + o * 4 + 1] = conv(vb.y);
+                    pB[s * (S / 2) + o * 4 + 2] = conv(vb.z);
+                    pB[s * (S / 2) + o * 4 + 3] = conv(vb.w);
                 }
                 nbA[s] = __builtin_amdgcn_readfirstlane((int)w.nb8[(b * nstage + s) * 16 + wave]);
                 nbB[s] = __builtin_amdgcn_readfirstlane((int)w.nb8[((b + 1) * nstage + s) * 16 + wave]);
             } else {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) pA[s * 8 + i] = pB[s * 8 + i] = zero16 | (zero16 << 16);
+                for (int i = 0; i < S / 2; ++i) pA[s * (S / 2) + i] = pB[s * (S / 2) + i] = zero16 | (zero16 << 16);
                 nbA[s] = nbB[s] = 0;
             }
         }
@@ -1334,7 +1339,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     // stage << 14 | (LDS byte address >> 4), 0xFFFF = none.
     const uint32_t spill_tab = zero_addr + 2 * kBufSkew;
     const int nspillA = w.spill_n[b * 16 + wave], nspillB = w.spill_n[(b + 1) * 16 + wave];
-    bool anyA[NS] = {false, false, false, false}, anyB[NS] = {false, false, false, false};
+    bool anyA[NS] = {}, anyB[NS] = {};
     {
         using lds_u16 = __attribute__((address_space(3))) uint16_t;
 #pragma unroll
@@ -1365,22 +1370,22 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
         }
     };
 
-    const int T = (g1 - g0) * NS;  // steps; step t = (row group t / 4, stage t % 4)
+    const int T = (g1 - g0) * NS;  // steps; step t = (row group t / NS, stage t % NS)
     f32x4 st[kRows];
     const int wave_col = (tid & ~63) * 4;
     const uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));
     const int cat_last = cat[A - 1];
     int4 c4 = make_int4(0, 0, 0, 0);
 
-    auto fetch_rows = [&](int t) { c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + (t >> 2)) * kRows); };
+    auto fetch_rows = [&](int t) { c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + (t >> LNS)) * kRows); };
     // column (in floats) of my four staged columns: the same in every full stage, clamped in a narrower last one
     const uint32_t col_full = (uint32_t)(c_lo + 4 * tid);
     const uint32_t col_last = (uint32_t)(c_lo + (nstage - 1) * kCap + min(4 * tid, ncols - (nstage - 1) * kCap - 4));
     auto load_tile = [&](int t) {
-        const int s = t & 3;
+        const int s = t & (NS - 1);
         const int left = ncols - s * kCap;  // <= 0 for the idle fourth step of a 3-stage layer
         if (wave_col >= left) return;
-        const int row0 = (g0 + (t >> 2)) * kRows;
+        const int row0 = (g0 + (t >> LNS)) * kRows;
         const uint32_t col = s == nstage - 1 ? col_last : col_full + (uint32_t)(s * kCap);
         const float* r0 = Yin + (size_t)c4.x * N;  // row bases are the same for the whole workgroup
         const float* r1 = Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N;
@@ -1392,7 +1397,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
         st[3] = *reinterpret_cast<const f32x4*>(r3 + col);
     };
     auto store_tile = [&](int P, int t) {
-        const int left = ncols - (t & 3) * kCap;
+        const int left = ncols - (t & (NS - 1)) * kCap;
         if (wave_col >= left) return;
         using lds_f4 = __attribute__((address_space(3))) f32x4;
         asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
@@ -1445,16 +1450,20 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
         constexpr int P = decltype(Ptag)::value;
         constexpr int s = decltype(Stag)::value;
         if (t + 2 < T) fetch_rows(t + 2);
-        if (nbA[s] > 0) fma_block8ps<P>(accA, pA[s * 8 + 0], pA[s * 8 + 1], pA[s * 8 + 2], pA[s * 8 + 3], wuni, sh4);
+        constexpr int o = s * (S / 2);  // first word of this stage's steps
+        if (nbA[s] > 0) fma_block8ps<P>(accA, pA[o + 0], pA[o + 1], pA[o + 2], pA[o + 3], wuni, sh4);
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
         if (t + 2 < T) load_tile(t + 2);
-        if (nbA[s] > 1) fma_block8ps<P>(accA, pA[s * 8 + 4], pA[s * 8 + 5], pA[s * 8 + 6], pA[s * 8 + 7], wuni, sh4);
-        if (nbB[s] > 0) fma_block8ps<P>(accB, pB[s * 8 + 0], pB[s * 8 + 1], pB[s * 8 + 2], pB[s * 8 + 3], wuni, sh4);
-        if (nbB[s] > 1) fma_block8ps<P>(accB, pB[s * 8 + 4], pB[s * 8 + 5], pB[s * 8 + 6], pB[s * 8 + 7], wuni, sh4);
+#pragma unroll
+        for (int blk = 1; blk < S / 8; ++blk)
+            if (nbA[s] > blk) fma_block8ps<P>(accA, pA[o + 4 * blk], pA[o + 4 * blk + 1], pA[o + 4 * blk + 2], pA[o + 4 * blk + 3], wuni, sh4);
+#pragma unroll
+        for (int blk = 0; blk < S / 8; ++blk)
+            if (nbB[s] > blk) fma_block8ps<P>(accB, pB[o + 4 * blk], pB[o + 4 * blk + 1], pB[o + 4 * blk + 2], pB[o + 4 * blk + 3], wuni, sh4);
         if (anyA[s]) spilled(Ptag, accA, 0, nspillA, s);
         if (anyB[s]) spilled(Ptag, accB, 1, nspillB, s);
-        if (s >= 2 && s == nstage - 1) {  // s is a compile-time constant: no epilogue code in the first two steps
-            const int g = g0 + (t >> 2);
+        if (s >= NS - 2 && s == nstage - 1) {  // s is a compile-time constant: no epilogue code in the steps that cannot be last
+            const int g = g0 + (t >> LNS);
             const int nlive = min(kRows, A - g * kRows);
             const unsigned pos = finish(accA, bjA, jA, g, nlive) | finish(accB, bjB, jA + kBlk, g, nlive);
             if (lane < nlive && ((pos >> lane) & 1u)) flags[g * kRows + lane] = 1;
@@ -1473,23 +1482,26 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     for (int t = 0; t < T; t += NS) {
         step(t, P0{}, std::integral_constant<int, 0>{});
         step(t + 1, P1{}, std::integral_constant<int, 1>{});
-        step(t + 2, P0{}, std::integral_constant<int, 2>{});
-        step(t + 3, P1{}, std::integral_constant<int, 3>{});
+        if constexpr (NS == 4) {
+            step(t + 2, P0{}, std::integral_constant<int, 2>{});
+            step(t + 3, P1{}, std::integral_constant<int, 3>{});
+        }
     }
 }
 
-// Compact form of a wide layer's steps for fused_wide_pair_kernel: the 16-bit LDS slot
-// of every step, 0xFFFF where the step carries no connection (weight 0 in pk).  One
-// thread per 16-byte output (eight steps of one lane).
-__global__ void wide_slots_kernel(const uint2* __restrict__ pk, uint4* __restrict__ ps, size_t n_out) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // = ((block*nstage + stage)*2 + octet)*kBlk + lane
+// Compact form of a wide layer's steps for the two-neurons-per-lane wide kernels: the 16-bit
+// LDS slot of every step, 0xFFFF where the step carries no connection (weight 0 in pk).  One
+// thread per 16-byte output (eight steps of one lane); S = steps per stage (16 or 32).
+__global__ void wide_slots_kernel(const uint2* __restrict__ pk, uint4* __restrict__ ps, size_t n_out, int S) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // = ((block*nstage + stage)*(S/8) + octet)*kBlk + lane
     if (i >= n_out) return;
-    const size_t lane = i % kBlk, bo = i / kBlk;                      // bo = (block*nstage + stage)*2 + octet
+    const size_t lane = i % kBlk, bo = i / kBlk;
+    const size_t bs = bo / (S / 8), octet = bo % (S / 8);  // bs = block*nstage + stage
     uint32_t h[8];
     for (int k = 0; k < 8; ++k) {
-        // step 8*octet + k of this lane: pk index ((bs*8 + step/2)*kBlk + lane)*2 + step%2, bs = bo/2, step = 8*(bo%2)+k
-        const size_t step = 8 * (bo & 1) + k;
-        const uint2 e = pk[((((bo >> 1) * 8 + (step >> 1)) * kBlk + lane) << 1) | (step & 1)];
+        // step 8*octet + k of this lane: pk index ((bs*(S/2) + step/2)*kBlk + lane)*2 + step%2
+        const size_t step = 8 * octet + k;
+        const uint2 e = pk[(((bs * (S / 2) + (step >> 1)) * kBlk + lane) << 1) | (step & 1)];
         h[k] = e.y == 0u ? kNoSlot : (e.x & 0xFFFFu);
     }
     ps[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
@@ -1679,7 +1691,7 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
 // Can the layer run two output neurons per lane?  Yes if all its weights are equal, N
 // is a multiple of 2048 and either the windows of output blocks 2u and 2u+1 together
 // span at most kCap columns for every u (info[0] = 1: fused_pair_kernel) or every block
-// needs 3 or more stages anyway (info[0] = 2: fused_wide_pair_kernel, if the pattern fits
+// needs 2 or more stages anyway (info[0] = 2: the wide pair kernels, if the pattern fits
 // the wide format).  Then both blocks of a unit get their common window.  info[0] = 0
 // otherwise; info[1] = the weight's bits.  One workgroup.
 __global__ __launch_bounds__(64) void pair_merge_kernel(int2* __restrict__ win, int nblk, int N,
@@ -1699,11 +1711,11 @@ __global__ __launch_bounds__(64) void pair_merge_kernel(int2* __restrict__ win, 
         }
     }
     __syncthreads();
-    // 1: one stage suffices for every unit; 2: every block needs 3 or more stages on its own
+    // 1: one stage suffices for every unit; 2: every block needs 2 or more stages on its own
     // (the wide format, which also profits from common windows); otherwise hands off
     int s_min = 1 << 30;
     for (int bb = 0; bb < nblk; ++bb) s_min = min(s_min, win[bb].y);
-    const int mode = !candidate ? 0 : s_max <= kCap ? 1 : s_min > 2 * kCap ? 2 : 0;
+    const int mode = !candidate ? 0 : s_max <= kCap ? 1 : s_min > kCap ? 2 : 0;
     const bool ok = mode != 0;
     __syncthreads();
     if (ok) {

@@ -36,11 +36,12 @@ def test_arena_sizes():
     assert k >= 2 * 1000 * 1024 * 4 + 5 * 1000 * 4
     assert sp.spdnn_work_bytes(65536, 60000) >= 2 * 60000 * 65536 * 4
     assert sp.spdnn_work_bytes(64, 0) > 0
-    # windows of at most 2 LDS stages need no more than the compact layout; wider ones do
+    # windows of one LDS stage need no more than the compact layout; wider ones do
     n = 16384
     compact = sp.spdnn_weights_bytes_for_window(n, 10, 4096)
-    assert compact == sp.spdnn_weights_bytes_for_window(n, 10, 8192)
-    assert compact < sp.spdnn_weights_bytes_for_window(n, 10, 12288) < sp.spdnn_weights_bytes_for_window(n, 10, n)
+    assert compact == sp.spdnn_weights_bytes_for_window(n, 10, 1024)
+    assert compact < sp.spdnn_weights_bytes_for_window(n, 10, 8192) <= sp.spdnn_weights_bytes_for_window(n, 10, 12288)
+    assert sp.spdnn_weights_bytes_for_window(n, 10, 12288) <= sp.spdnn_weights_bytes_for_window(n, 10, n)
     assert sp.spdnn_weights_bytes_for_window(n, 10, n) == sp.spdnn_weights_bytes(n, 10)
     assert sp.spdnn_weights_bytes(65536, 2) < 2 * 65536 * 32 * 6 * 8
 

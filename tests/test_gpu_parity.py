@@ -275,7 +275,7 @@ def test_kernel_choice():
     cases = [
         (1024, 1024, sp.SPDNN_KERNEL_SINGLE),    # uniform weight, but N is not a multiple of 2048
         (4096, 4096, sp.SPDNN_KERNEL_PAIR),
-        (8192, 8192, sp.SPDNN_KERNEL_STAGED),    # two LDS stages
+        (8192, 8192, sp.SPDNN_KERNEL_WIDE_PAIR4),  # two LDS stages, one weight
         (16384, 16384, sp.SPDNN_KERNEL_WIDE_PAIR4),  # four stages, one weight
         (17408, 17408, sp.SPDNN_KERNEL_WIDE),       # five stages, N not a multiple of 2048
     ]
@@ -289,6 +289,8 @@ def test_kernel_choice():
 
 
 @pytest.mark.parametrize("N,L,batch", [
+    (8192, 3, 23),     # two stages of 32 steps
+    (6144, 2, 7),      # two stages, the second narrower
     (16384, 2, 19),    # four stages
     (18432, 2, 6),     # the last stage is narrower than the others
     (32768, 1, 5),     # eight stages
@@ -314,7 +316,7 @@ def test_wide_two_neurons_per_lane(N, L, batch):
         v[7, 0] = np.float32(0.0625 * (1.0 + 2.0 ** -20))
     ref2 = oracle.infer(idx, val2, bias, Y0)
     m2 = sp.Model(idx, val2, bias)
-    assert [m2.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_WIDE] * L
+    assert [m2.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_WIDE if N > 8192 else sp.SPDNN_KERNEL_STAGED] * L
     n2, rows2, Y2 = gpu_infer(idx, val2, bias, Y0, model=m2)
     m2.close()
     check_against_oracle(ref2, n2, rows2, Y2, what="wide N=%d" % N)
