@@ -345,3 +345,28 @@ def test_wide_two_neurons_per_lane_three_stages():
     m.close()
     common, _ = check_against_oracle(ref, n, rows, Y, what="wide pair, 3 stages")
     assert common > 0
+
+
+def test_layers_with_fewer_stages_than_the_widest():
+    """A model whose widest layer needs 10 stages (8 steps per stage in the wide format) and
+    whose other layer needs 8 (16 steps per stage, more steps per neuron in total): the weight
+    arena, sized for the widest window, must hold both."""
+    import paper_2007_14152_amd as sp
+    N, batch = 40960, 5
+    rng = np.random.default_rng(11)
+    i0, v0, bias = _uniform_model(rng, N, 1, N)
+    i1 = [np.sort(np.stack([rng.choice(32768, 32, replace=False) for _ in range(N)]), axis=1).astype(np.int32)]
+    v1 = [np.full((N, 32), 0.0625, dtype=np.float32)]
+    idx, val = i0 + i1, v0 + v1
+    for v in val:
+        v[3, 3] = np.float32(0.0625 * (1.0 + 2.0 ** -20))   # two weight values: one neuron per lane
+    Y0 = (rng.uniform(0, 1, size=(batch, N)) < 0.3).astype(np.float32)
+    ref = oracle.infer(idx, val, bias, Y0)
+    m = sp.Model(idx, val, bias)
+    # (with 8 steps per stage a uniform pattern of this size may not fit the wide format: staged kernel then)
+    assert m.layer_kernel(0) in (sp.SPDNN_KERNEL_WIDE, sp.SPDNN_KERNEL_STAGED)
+    assert m.layer_kernel(1) == sp.SPDNN_KERNEL_WIDE
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    m.close()
+    common, _ = check_against_oracle(ref, n, rows, Y, what="10 + 8 stages")
+    assert common > 0
