@@ -390,6 +390,47 @@ __device__ __forceinline__ void fma_block8ps(float (&acc)[4], uint32_t p0, uint3
         : "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "memory");
 }
 
+// Epilogue of one 4-row group of one neuron (Eq. 1: bias, ReLU, clip at 32): lane 4q+i
+// holds rows 0..3 of neuron 4q+i; a 4x4 transpose inside each lane quartet (two DPP
+// exchanges) leaves it with row i of neurons 4q..4q+3, which is one 16-byte store.
+// Clears the accumulators.  Returns bit r set if row r has a positive output anywhere in
+// the wave (lanes past the last neuron carry zero weights and zero bias, so their y is 0).
+__device__ __forceinline__ unsigned finish_rows(float (&a)[kRows], float bj, float* __restrict__ Yout, int N, int j,
+                                                bool jok, int row0, int nlive, int lane) {
+    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
+    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
+    const bool b0 = lane & 1, b1 = lane & 2;
+    float y0 = fminf(fmaxf(a[0] + bj, 0.0f), kClip);
+    float y1 = fminf(fmaxf(a[1] + bj, 0.0f), kClip);
+    float y2 = fminf(fmaxf(a[2] + bj, 0.0f), kClip);
+    float y3 = fminf(fmaxf(a[3] + bj, 0.0f), kClip);
+    a[0] = a[1] = a[2] = a[3] = 0.0f;
+    const unsigned pos = (__builtin_amdgcn_ballot_w64(y0 > 0.0f) != 0ull ? 1u : 0u) |
+                         (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
+                         (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
+                         (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
+    {
+        const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
+        const float r0 = xor2(s0), r1 = xor2(s1);
+        y0 = b1 ? r0 : y0;
+        y1 = b1 ? r1 : y1;
+        y2 = b1 ? y2 : r0;
+        y3 = b1 ? y3 : r1;
+    }
+    {
+        const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
+        const float r0 = xor1(s0), r1 = xor1(s1);
+        y0 = b0 ? r0 : y0;
+        y1 = b0 ? y1 : r0;
+        y2 = b0 ? r1 : y2;
+        y3 = b0 ? y3 : r1;
+    }
+    const int r = lane & 3;
+    if (jok && r < nlive)
+        *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
+    return pos;
+}
+
 // ---------------------------------------------------------------------------
 // a1: fused SpMM + bias + clipped ReLU for one layer (Eq. 1), plus the per-row
 // "has a positive output" flag that Listings 1 and 2 keep in active[].
@@ -562,45 +603,11 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
 
     const int lane = tid & 63;
     // Exchange between lanes l and l^1 / l^2 of a quartet (DPP quad permutes).
-    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
-    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
-    const bool b0 = lane & 1, b1 = lane & 2;
     auto epilogue = [&](int g) {
         const int row0 = g * kRows;
         const int nlive = min(kRows, A - row0);  // rows of this group that exist (>= 1)
-        float y0 = fminf(fmaxf(acc[0] + bj, 0.0f), kClip);
-        float y1 = fminf(fmaxf(acc[1] + bj, 0.0f), kClip);
-        float y2 = fminf(fmaxf(acc[2] + bj, 0.0f), kClip);
-        float y3 = fminf(fmaxf(acc[3] + bj, 0.0f), kClip);
-        acc[0] = acc[1] = acc[2] = acc[3] = 0.0f;
-        // row r has a positive output in this wave -> lane r raises the row's flag
-        // (lanes past the last neuron have zero weights and zero bias, so their y is 0)
-        const unsigned pos = (__builtin_amdgcn_ballot_w64(y0 > 0.0f) != 0ull ? 1u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
-        if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;
-        // 4x4 transpose inside each quartet: lane 4q+i holds rows 0..3 of neuron 4q+i and
-        // ends up with row i of neurons 4q..4q+3, which is one 16-byte store.
-        {
-            const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
-            const float r0 = xor2(s0), r1 = xor2(s1);
-            y0 = b1 ? r0 : y0;
-            y1 = b1 ? r1 : y1;
-            y2 = b1 ? y2 : r0;
-            y3 = b1 ? y3 : r1;
-        }
-        {
-            const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
-            const float r0 = xor1(s0), r1 = xor1(s1);
-            y0 = b0 ? r0 : y0;
-            y1 = b0 ? y1 : r0;
-            y2 = b0 ? r1 : y2;
-            y3 = b0 ? y3 : r1;
-        }
-        const int r = lane & 3;
-        if (jok && r < nlive)
-            *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
+        const unsigned pos = finish_rows(acc, bj, Yout, N, j, jok, row0, nlive, lane);
+        if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;  // lane r raises row r's flag
     };
 
     // One pipeline step with compile-time buffer index P.  On entry tile t is in
@@ -743,40 +750,8 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     };
 
     const int lane = tid & 63;
-    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
-    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
-    const bool b0 = lane & 1, b1 = lane & 2;
-    // bias, clip, 4x4 transpose inside the lane quartet, one 16-byte store; returns the rows with a positive output
     auto finish = [&](float (&acc)[kRows], float bj, int j, int row0, int nlive) -> unsigned {
-        float y0 = fminf(fmaxf(acc[0] + bj, 0.0f), kClip);
-        float y1 = fminf(fmaxf(acc[1] + bj, 0.0f), kClip);
-        float y2 = fminf(fmaxf(acc[2] + bj, 0.0f), kClip);
-        float y3 = fminf(fmaxf(acc[3] + bj, 0.0f), kClip);
-        acc[0] = acc[1] = acc[2] = acc[3] = 0.0f;
-        const unsigned pos = (__builtin_amdgcn_ballot_w64(y0 > 0.0f) != 0ull ? 1u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
-        {
-            const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
-            const float r0 = xor2(s0), r1 = xor2(s1);
-            y0 = b1 ? r0 : y0;
-            y1 = b1 ? r1 : y1;
-            y2 = b1 ? y2 : r0;
-            y3 = b1 ? y3 : r1;
-        }
-        {
-            const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
-            const float r0 = xor1(s0), r1 = xor1(s1);
-            y0 = b0 ? r0 : y0;
-            y1 = b0 ? y1 : r0;
-            y2 = b0 ? r1 : y2;
-            y3 = b0 ? y3 : r1;
-        }
-        const int r = lane & 3;
-        if (r < nlive)
-            *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
-        return pos;
+        return finish_rows(acc, bj, Yout, N, j, true, row0, nlive, lane);
     };
 
     // One step: neuron A's 32 connections, tile t+1 into the other buffer and the loads of
@@ -1408,41 +1383,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     };
 
     float accA[kRows] = {0.f, 0.f, 0.f, 0.f}, accB[kRows] = {0.f, 0.f, 0.f, 0.f};
-    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
-    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
-    const bool b0 = lane & 1, b1 = lane & 2;
-    // bias, clip, 4x4 transpose inside the lane quartet, one 16-byte store
     auto finish = [&](float (&a)[kRows], float bj, int j, int g, int nlive) -> unsigned {
-        const int row0 = g * kRows;
-        float y0 = fminf(fmaxf(a[0] + bj, 0.0f), kClip);
-        float y1 = fminf(fmaxf(a[1] + bj, 0.0f), kClip);
-        float y2 = fminf(fmaxf(a[2] + bj, 0.0f), kClip);
-        float y3 = fminf(fmaxf(a[3] + bj, 0.0f), kClip);
-        a[0] = a[1] = a[2] = a[3] = 0.0f;
-        const unsigned pos = (__builtin_amdgcn_ballot_w64(y0 > 0.0f) != 0ull ? 1u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
-                             (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
-        {
-            const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
-            const float r0 = xor2(s0), r1 = xor2(s1);
-            y0 = b1 ? r0 : y0;
-            y1 = b1 ? r1 : y1;
-            y2 = b1 ? y2 : r0;
-            y3 = b1 ? y3 : r1;
-        }
-        {
-            const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
-            const float r0 = xor1(s0), r1 = xor1(s1);
-            y0 = b0 ? r0 : y0;
-            y1 = b0 ? y1 : r0;
-            y2 = b0 ? r1 : y2;
-            y3 = b0 ? y3 : r1;
-        }
-        const int r = lane & 3;
-        if (r < nlive)
-            *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
-        return pos;
+        return finish_rows(a, bj, Yout, N, j, true, g * kRows, nlive, lane);
     };
 
     // One step with compile-time tile buffer P and stage s.
