@@ -42,6 +42,13 @@ def _load():
                            ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p]
+        for name in ("spdnn_oracle_infer_csr", "spdnn_oracle_infer_csr_f64"):
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_int32, ctypes.c_int32, pp_i, pp_i, pp_i, ctypes.c_void_p,
+                           ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -61,16 +68,19 @@ class OracleResult:
         self.layers_evaluated = layers_evaluated
 
 
-def infer(idx, val, bias, Y0, no_skip=False, f64=False, want_Y=True, fragile_eps=FRAGILE_EPS):
+def infer(idx, val, bias, Y0, no_skip=False, f64=False, want_Y=True, fragile_eps=FRAGILE_EPS, ptr=None):
     """Run the oracle.
 
     idx: list of L int32 arrays [N, 32] (an entry may be None for a layer no
     active row reaches); val: list of L float32 arrays [N, 32]; bias: float32
-    [N]; Y0: [batch, N] float32 (float64 if f64).  Returns OracleResult.
+    [N]; Y0: [batch, N] float32 (float64 if f64).  With ptr (list of L int32
+    arrays [N+1]) the layers are general: neuron j of layer l owns entries
+    ptr[l][j] .. ptr[l][j+1]-1 of the flat arrays idx[l] / val[l].  Returns
+    OracleResult.
     """
     lib = _load()
     L = len(idx)
-    assert len(val) == L
+    assert len(val) == L and (ptr is None or len(ptr) == L)
     bias = np.ascontiguousarray(bias, dtype=np.float32)
     N = int(bias.shape[0])
     ft = np.float64 if f64 else np.float32
@@ -80,14 +90,23 @@ def infer(idx, val, bias, Y0, no_skip=False, f64=False, want_Y=True, fragile_eps
     keep = []
     ip = (ctypes.c_void_p * max(L, 1))()
     vp = (ctypes.c_void_p * max(L, 1))()
+    pp = (ctypes.c_void_p * max(L, 1))()
     for l in range(L):
         if idx[l] is None:
             ip[l] = None
             vp[l] = None
+            pp[l] = None
             continue
         a = np.ascontiguousarray(idx[l], dtype=np.int32)
         v = np.ascontiguousarray(val[l], dtype=np.float32)
-        assert a.shape == (N, 32) and v.shape == (N, 32), "layer %d: expected [N,32]" % l
+        if ptr is None:
+            assert a.shape == (N, 32) and v.shape == (N, 32), "layer %d: expected [N,32]" % l
+        else:
+            q = np.ascontiguousarray(ptr[l], dtype=np.int32)
+            assert q.shape == (N + 1,) and q[0] == 0 and (np.diff(q) >= 0).all(), "layer %d: bad ptr" % l
+            assert a.shape == (int(q[N]),) and v.shape == a.shape, "layer %d: expected ptr[N] entries" % l
+            keep.append(q)
+            pp[l] = q.ctypes.data
         if a.size and (a.min() < 0 or a.max() >= N):
             raise ValueError("layer %d: column index outside [0, N)" % l)
         keep.append((a, v))
@@ -99,8 +118,13 @@ def infer(idx, val, bias, Y0, no_skip=False, f64=False, want_Y=True, fragile_eps
     apl = np.zeros(L + 1, dtype=np.int32)
     frag = np.zeros(max(batch, 1), dtype=np.int32)
     nev = np.zeros(1, dtype=np.int32)
-    fn = lib.spdnn_oracle_infer_f64 if f64 else lib.spdnn_oracle_infer
-    rc = fn(N, L, ip, vp, bias.ctypes.data, Y0.ctypes.data, batch, 1 if no_skip else 0,
+    if ptr is None:
+        fn = lib.spdnn_oracle_infer_f64 if f64 else lib.spdnn_oracle_infer
+        head = (N, L, ip, vp)
+    else:
+        fn = lib.spdnn_oracle_infer_csr_f64 if f64 else lib.spdnn_oracle_infer_csr
+        head = (N, L, pp, ip, vp)
+    rc = fn(*head, bias.ctypes.data, Y0.ctypes.data, batch, 1 if no_skip else 0,
             n_active.ctypes.data, rows.ctypes.data, Y.ctypes.data if want_Y else None,
             apl.ctypes.data, frag.ctypes.data, float(fragile_eps), nev.ctypes.data)
     if rc == -2:

@@ -24,13 +24,22 @@
 //  * accumulation: slot order k = 0..31, one fused multiply-add per connection
 //    in the working precision, bias added last.
 //
+// General sparse layers (Section II-A-1: W_l may be any sparse matrix; Listing 1
+// stores it in CSR): the *_csr entry points take, per layer, ptr[0..N] with the
+// connections of output neuron j at positions ptr[j] .. ptr[j+1]-1 of idx / val, any
+// number per neuron (none: the output is the clipped bias).  Same definition, same
+// accumulation rule (stored order, one fused multiply-add each, bias last).
+//
 // Precision: float (the paper's FEATPREC) in spdnn_oracle_infer; double in
 // spdnn_oracle_infer_f64 (used to bound the float rounding error in tests).
 //
 // Pins (tests/test_oracle_*.py): dense brute force on tiny N, layer-0 integer
 // closed form, uniform-row closed form incl. the clip at 32, identity pattern,
 // zero input, row independence, permutation equivariance, monotonicity,
-// skip == no-skip, float vs double within the rounding bound.
+// skip == no-skip, float vs double within the rounding bound; for the general
+// (CSR) form: dense brute force with uneven neuron lengths, the constant-row closed
+// form with per-neuron weight sums, neurons without connections, and invariance
+// under appended zero-weight connections.
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -45,16 +54,19 @@ template <> inline double fma_t<double>(double a, double b, double c) { return s
 constexpr int kNnz = 32;
 
 // One feature row through one layer.  Returns the largest pre-clip value z.
+// ptr == NULL: neuron j owns entries j*32 .. j*32+31; else entries ptr[j] .. ptr[j+1]-1.
 template <typename T>
-T layer_row(int32_t N, const int32_t* idx, const float* val, const float* bias,
+T layer_row(int32_t N, const int32_t* ptr, const int32_t* idx, const float* val, const float* bias,
             const T* in, T* out, bool* any_positive) {
     bool pos = false;
     T zmax = -INFINITY;
     for (int32_t j = 0; j < N; ++j) {
         T acc = 0;
-        const int32_t* ij = idx + (size_t)j * kNnz;
-        const float* vj = val + (size_t)j * kNnz;
-        for (int k = 0; k < kNnz; ++k) acc = fma_t<T>(in[ij[k]], (T)vj[k], acc);
+        const size_t first = ptr ? (size_t)ptr[j] : (size_t)j * kNnz;
+        const int cnt = ptr ? ptr[j + 1] - ptr[j] : kNnz;
+        const int32_t* ij = idx + first;
+        const float* vj = val + first;
+        for (int k = 0; k < cnt; ++k) acc = fma_t<T>(in[ij[k]], (T)vj[k], acc);
         T z = acc + (T)bias[j];
         if (z > zmax) zmax = z;
         T y = (z < (T)0) ? (T)0 : (z > (T)32) ? (T)32 : z;
@@ -66,7 +78,7 @@ T layer_row(int32_t N, const int32_t* idx, const float* val, const float* bias,
 }
 
 template <typename T>
-int infer(int32_t N, int32_t L, const int32_t* const* idx, const float* const* val,
+int infer(int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx, const float* const* val,
           const float* bias, const T* Y0, int32_t batch, int32_t no_skip,
           int32_t* n_active, int32_t* active_rows, T* Y_final,
           int32_t* active_per_layer, int32_t* fragile_layer, double fragile_eps,
@@ -90,14 +102,14 @@ int infer(int32_t N, int32_t L, const int32_t* const* idx, const float* const* v
             if (active_per_layer) active_per_layer[l + 1] = 0;
             continue;
         }
-        if (!idx[l] || !val[l]) return -2;       // layer needed but not provided
+        if (!idx[l] || !val[l] || (ptr && !ptr[l])) return -2;  // layer needed but not provided
         ++evaluated;
         std::vector<int32_t> keep;
         const int32_t nrows = no_skip ? batch : (int32_t)act.size();
         for (int32_t i = 0; i < nrows; ++i) {
             const int32_t r = no_skip ? i : act[i];
             bool pos = false;
-            T zmax = layer_row<T>(N, idx[l], val[l], bias, &cur[(size_t)r * n], &nxt[(size_t)r * n], &pos);
+            T zmax = layer_row<T>(N, ptr ? ptr[l] : nullptr, idx[l], val[l], bias, &cur[(size_t)r * n], &nxt[(size_t)r * n], &pos);
             if (no_skip) {
                 if (!alive[r]) continue;         // already dropped from the list
                 if (!pos) alive[r] = 0;
@@ -137,7 +149,7 @@ int spdnn_oracle_infer(int32_t N, int32_t L, const int32_t* const* idx, const fl
                        int32_t* n_active, int32_t* active_rows, float* Y_final,
                        int32_t* active_per_layer, int32_t* fragile_layer, double fragile_eps,
                        int32_t* layers_evaluated) {
-    return infer<float>(N, L, idx, val, bias, Y0, batch, no_skip, n_active, active_rows, Y_final,
+    return infer<float>(N, L, nullptr, idx, val, bias, Y0, batch, no_skip, n_active, active_rows, Y_final,
                         active_per_layer, fragile_layer, fragile_eps, layers_evaluated);
 }
 
@@ -147,7 +159,29 @@ int spdnn_oracle_infer_f64(int32_t N, int32_t L, const int32_t* const* idx, cons
                            int32_t* n_active, int32_t* active_rows, double* Y_final,
                            int32_t* active_per_layer, int32_t* fragile_layer, double fragile_eps,
                            int32_t* layers_evaluated) {
-    return infer<double>(N, L, idx, val, bias, Y0, batch, no_skip, n_active, active_rows, Y_final,
+    return infer<double>(N, L, nullptr, idx, val, bias, Y0, batch, no_skip, n_active, active_rows, Y_final,
+                         active_per_layer, fragile_layer, fragile_eps, layers_evaluated);
+}
+
+// General sparse layers: ptr[l] has N+1 non-decreasing entries starting at 0; idx[l] /
+// val[l] have ptr[l][N] entries.  Everything else as above.
+int spdnn_oracle_infer_csr(int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx,
+                           const float* const* val, const float* bias, const float* Y0, int32_t batch,
+                           int32_t no_skip, int32_t* n_active, int32_t* active_rows, float* Y_final,
+                           int32_t* active_per_layer, int32_t* fragile_layer, double fragile_eps,
+                           int32_t* layers_evaluated) {
+    if (L > 0 && !ptr) return -1;
+    return infer<float>(N, L, ptr, idx, val, bias, Y0, batch, no_skip, n_active, active_rows, Y_final,
+                        active_per_layer, fragile_layer, fragile_eps, layers_evaluated);
+}
+
+int spdnn_oracle_infer_csr_f64(int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx,
+                               const float* const* val, const float* bias, const double* Y0, int32_t batch,
+                               int32_t no_skip, int32_t* n_active, int32_t* active_rows, double* Y_final,
+                               int32_t* active_per_layer, int32_t* fragile_layer, double fragile_eps,
+                               int32_t* layers_evaluated) {
+    if (L > 0 && !ptr) return -1;
+    return infer<double>(N, L, ptr, idx, val, bias, Y0, batch, no_skip, n_active, active_rows, Y_final,
                          active_per_layer, fragile_layer, fragile_eps, layers_evaluated);
 }
 

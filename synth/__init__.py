@@ -291,6 +291,49 @@ def gen_values(N, device=None):
     return torch.full((N, NNZ), WEIGHT, dtype=torch.float32, device=device)
 
 
+_STREAM_G = 0x5350444E4E5F4731    # general layers: neuron lengths and weights
+
+
+def gen_layer_general(N, l, seed, kmin, kmax, window=None, uniform_weight=False):
+    """A general sparse layer (Section II-A-1: W_l may be any sparse matrix), as
+    numpy arrays (ptr int32 [N+1], idx int32 [nnz], val float32 [nnz]): output
+    neuron j owns entries ptr[j] .. ptr[j+1]-1.
+
+    Recipe: neuron j has d_j = kmin + (hash mod (kmax-kmin+1)) connections.  Its
+    columns are the first d_j of the concatenation of ceil(kmax/32) independent
+    32-column draws of gen_layer (each ascending; a column may repeat across
+    draws -- repeated connections add up).  Weights: m / (d_j * 2**23) with m a
+    hashed integer in [2**23, 3 * 2**23), so a neuron's weights sum to about 2, as
+    the 32 weights of 1/16 of the challenge networks do; uniform_weight=True gives
+    every connection 1/16 instead.
+    """
+    if not (0 <= kmin <= kmax):
+        raise ValueError("need 0 <= kmin <= kmax")
+    bk = _NP()
+    draws = max(1, -(-kmax // NNZ))
+    cols = np.concatenate([gen_layer(N, l + 100003 * t, seed, window) for t in range(draws)], axis=1)  # [N, 32*draws]
+    kg = _mix_py(_mix_py(seed ^ _STREAM_G) ^ l)
+    j = bk.arange(N)
+    nkey = _mix(bk, j ^ bk.const(kg))
+    deg = (np.uint64(kmin) + bk.lsr(nkey, 11) % np.uint64(kmax - kmin + 1)).astype(np.int64)   # [N]
+    ptr = np.zeros(N + 1, dtype=np.int64)
+    np.cumsum(deg, out=ptr[1:])
+    if ptr[N] >= (1 << 31):
+        raise ValueError("layer too large for 32-bit offsets")
+    k = np.arange(NNZ * draws, dtype=np.int64)[None, :]
+    take = k < deg[:, None]
+    idx = cols[take].astype(np.int32)
+    if uniform_weight:
+        val = np.full(idx.shape, WEIGHT, dtype=np.float32)
+    else:
+        t = bk.arange(NNZ * draws, start=1)
+        h = _stream(bk, nkey[:, None], t[None, :])
+        m = (np.uint64(1 << 23) + (bk.lsr(h, 20) & np.uint64((1 << 24) - 1))).astype(np.float64)
+        w = m / (np.maximum(deg, 1)[:, None].astype(np.float64) * float(1 << 23))
+        val = w[take].astype(np.float32)
+    return ptr.astype(np.int32), idx, val
+
+
 def gen_bias(N, value, device=None):
     """Bias vector: float32 [N], one constant (Alg. 1 step 2)."""
     if device is None or device == "numpy":
