@@ -7,7 +7,8 @@
  * (Section II-A-1, Eq. 1, with the clipped ReLU defined next to it; the steps
  * are those of Alg. 1, step 3), where Y_l is a dense batch x N feature map,
  * one feature row per input, and output neuron j of layer l has exactly 32
- * stored connections (input column idx_l[j][k], weight val_l[j][k]).  After
+ * stored connections (input column idx_l[j][k], weight val_l[j][k]) -- or any
+ * number of them for models built with spdnn_create_csr.  After
  * every layer the rows with no strictly positive output are dropped and the
  * list of surviving rows is compacted, as the host loop of Listing 1 does; a
  * dropped row is never evaluated again, which is exact because every bias is
@@ -91,6 +92,37 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx,
                  const float* const* val, const float* bias, int32_t where,
                  void* weights_arena, size_t weights_arena_bytes, void* hip_stream);
 
+/* General sparse layers (Section II-A-1: W_l may be any sparse matrix; Listing 1 holds it in
+ * CSR): output neuron j of layer l owns entries ptr[l][j] .. ptr[l][j+1]-1 of idx[l] / val[l],
+ * any number of them, none included (its output is then the clipped bias, 0).  The library
+ * evaluates
+ *
+ *     Y_{l+1}[r][j] = min(max( sum_k Y_l[r][idx_l[k]] * val_l[k] + bias[j], 0), 32)
+ *
+ * over the neuron's entries k.  A layer whose longest neuron has K connections runs as
+ * max(1, ceil(K/32)) passes of the fused kernel over 32 connections per neuron, shorter
+ * neurons padded with zero weights (the padding of Section III-A-3); the passes of a layer
+ * accumulate in the output buffer and the last one applies bias and ReLU.
+ *
+ * spdnn_csr_passes: passes[l] (host, may be NULL) = passes of layer l, *total = their sum,
+ * which is the "L" to size the weights arena with (spdnn_weights_bytes(N, *total, ...)).
+ *   ptr        : host array of L pointers to device arrays of N+1 int32, ptr[l][0] >= 0,
+ *                non-decreasing.
+ *   scratch_dev: device memory, 8-byte aligned, >= 8*L bytes, contents scratch.
+ * Blocks until done.  SPDNN_EINVAL if a ptr array decreases or is negative. */
+int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev,
+                     size_t scratch_bytes, void* hip_stream, int32_t* passes, int32_t* total);
+
+/* Build a model of L general layers.  ptr, idx, val: host arrays of L pointers to DEVICE
+ * arrays (ptr[l]: N+1 int32 as above; idx[l], val[l]: at least ptr[l][N] entries, columns in
+ * [0, N), repeated columns add up); bias: N floats in DEVICE memory, all <= 0.  All read
+ * during the call only.  weights_arena: device, 256-byte aligned, >= spdnn_weights_bytes(N,
+ * total passes) (or the _for_window variant).  Everything else as spdnn_create; the handle is
+ * used with the same spdnn_infer. */
+int spdnn_create_csr(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* ptr,
+                     const int32_t* const* idx, const float* const* val, const float* bias,
+                     void* weights_arena, size_t weights_arena_bytes, void* hip_stream);
+
 /* Run all L layers on `batch` feature rows.
  *   Y0_dev : device, batch x N floats, row-major (row r = input r), 16-byte aligned, finite
  *            values; not modified.
@@ -137,6 +169,7 @@ int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows
  * SPDNN_KERNEL_WIDE_PAIR4 the same for two to four stages (the step lists of all stages stay in
  *                      registers).
  * Returns SPDNN_EINVAL for a NULL handle or pointer or l outside [0, L). */
+/* (A layer of several passes reports the kernel of its first pass.) */
 #define SPDNN_KERNEL_SINGLE 0
 #define SPDNN_KERNEL_STAGED 1
 #define SPDNN_KERNEL_WIDE 2
@@ -144,6 +177,10 @@ int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows
 #define SPDNN_KERNEL_WIDE_PAIR 4
 #define SPDNN_KERNEL_WIDE_PAIR4 5
 int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind);
+
+/* Number of fused-kernel passes layer l takes: 1, or ceil(K/32) for a general layer whose
+ * longest neuron has K > 32 connections. */
+int spdnn_layer_passes(spdnn_t h, int32_t l, int32_t* passes);
 
 /* Measurement aid: enqueue a plain device-to-device copy kernel of `bytes` bytes (a multiple
  * of 16; both pointers 16-byte aligned, device memory) on the given stream.  It reads and

@@ -30,7 +30,8 @@ SPDNN_KERNEL_WIDE_PAIR4 = 5
 
 EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
            "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_copy_probe",
-           "spdnn_weights_bytes_for_window", "spdnn_scan_windows", "spdnn_layer_kernel")
+           "spdnn_weights_bytes_for_window", "spdnn_scan_windows", "spdnn_layer_kernel",
+           "spdnn_csr_passes", "spdnn_create_csr", "spdnn_layer_passes")
 KERNEL_NAMES = {0: "fused_layer_kernel<false>", 1: "fused_layer_kernel<true>", 2: "fused_wide_kernel",
                 3: "fused_pair_kernel", 4: "fused_wide_pair_kernel", 5: "fused_wide_pair4_kernel"}
 
@@ -64,6 +65,10 @@ def lib():
         L.spdnn_weights_bytes_for_window.argtypes = [i32, i32, i32, ctypes.POINTER(sz)]
         L.spdnn_scan_windows.argtypes = [i32, i32, ctypes.POINTER(vp), i32, vp, sz, vp, ctypes.POINTER(i32)]
         L.spdnn_layer_kernel.argtypes = [vp, i32, ctypes.POINTER(i32)]
+        L.spdnn_layer_passes.argtypes = [vp, i32, ctypes.POINTER(i32)]
+        L.spdnn_csr_passes.argtypes = [i32, i32, ctypes.POINTER(vp), vp, sz, vp, vp, ctypes.POINTER(i32)]
+        L.spdnn_create_csr.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                       ctypes.POINTER(vp), vp, vp, sz, vp]
         for n in EXPORTS:
             if n != "spdnn_last_error":
                 getattr(L, n).restype = ctypes.c_int
@@ -117,6 +122,28 @@ def spdnn_create(N, L, idx_ptrs, val_ptrs, bias_ptr, where, arena_ptr, arena_byt
     return h.value
 
 
+def spdnn_csr_passes(N, L, ptr_ptrs, scratch_ptr, scratch_bytes, stream=0):
+    """ptr_ptrs: L device addresses of int32[N+1].  Returns (passes per layer, their sum)."""
+    import numpy as np
+    pp = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in ptr_ptrs])
+    passes = np.zeros(max(L, 1), dtype=np.int32)
+    total = ctypes.c_int32(0)
+    _check(lib().spdnn_csr_passes(N, L, pp, ctypes.c_void_p(int(scratch_ptr)), scratch_bytes,
+                                  ctypes.c_void_p(int(stream)), passes.ctypes.data, ctypes.byref(total)))
+    return passes[:L], total.value
+
+
+def spdnn_create_csr(N, L, ptr_ptrs, idx_ptrs, val_ptrs, bias_ptr, arena_ptr, arena_bytes, stream=0):
+    """General layers; every address is device memory.  Returns the opaque handle."""
+    pp = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in ptr_ptrs])
+    ip = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in idx_ptrs])
+    vp = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in val_ptrs])
+    h = ctypes.c_void_p(0)
+    _check(lib().spdnn_create_csr(ctypes.byref(h), N, L, pp, ip, vp, ctypes.c_void_p(int(bias_ptr)),
+                                  ctypes.c_void_p(int(arena_ptr)), arena_bytes, ctypes.c_void_p(int(stream))))
+    return h.value
+
+
 def spdnn_infer(h, y0_ptr, batch, work_ptr, work_bytes, active_rows_ptr, y_final_ptr) -> int:
     """Returns n_active."""
     n = ctypes.c_int32(-1)
@@ -153,6 +180,13 @@ def spdnn_layer_kernel(h, l: int) -> int:
     return k.value
 
 
+def spdnn_layer_passes(h, l: int) -> int:
+    """Fused-kernel passes of layer l (1 unless some neuron has more than 32 connections)."""
+    k = ctypes.c_int32(-1)
+    _check(lib().spdnn_layer_passes(ctypes.c_void_p(h), l, ctypes.byref(k)))
+    return k.value
+
+
 def spdnn_copy_probe(dst_ptr, src_ptr, nbytes, stream=0) -> None:
     _check(lib().spdnn_copy_probe(ctypes.c_void_p(int(dst_ptr)), ctypes.c_void_p(int(src_ptr)), nbytes,
                                   ctypes.c_void_p(int(stream))))
@@ -165,7 +199,7 @@ class Model:
     (copied through the host path) or CUDA torch tensors (device path); bias: [N].
     """
 
-    def __init__(self, idx, val, bias, device="cuda:0", stream=None, window_hint=None):
+    def __init__(self, idx, val, bias, device="cuda:0", stream=None, window_hint=None, ptr=None):
         import numpy as np
         import torch
         self.torch = torch
@@ -173,6 +207,9 @@ class Model:
         L = len(idx)
         N = int(bias.shape[0])
         self.N, self.L = N, L
+        if ptr is not None:
+            self._init_general(ptr, idx, val, bias, stream)
+            return
         on_dev = hasattr(idx[0], "is_cuda") and idx[0].is_cuda
         keep = []
         if on_dev:
@@ -208,6 +245,42 @@ class Model:
         self.work = None
         del keep
 
+    @classmethod
+    def from_csr(cls, ptr, idx, val, bias, device="cuda:0", stream=None):
+        """General layers: ptr[l] int32 [N+1], idx[l] / val[l] flat arrays of ptr[l][N] entries
+        (numpy arrays or torch tensors; copied to the device with torch)."""
+        return cls(idx, val, bias, device=device, stream=stream, ptr=ptr)
+
+    def _init_general(self, ptr, idx, val, bias, stream):
+        torch = self.torch
+        N, L = self.N, self.L
+        dev = self.device
+
+        def to(a, dt):   # a layer without connections still needs a non-null address
+            t = torch.as_tensor(a).to(dev, dt).contiguous()
+            return t if t.numel() else torch.zeros(1, dtype=dt, device=dev)
+
+        ptr = [to(a, torch.int32) for a in ptr]
+        idx = [to(a, torch.int32) for a in idx]
+        val = [to(a, torch.float32) for a in val]
+        b = to(bias, torch.float32)
+        for q, a, v in zip(ptr, idx, val):
+            assert q.numel() == N + 1 and a.numel() == v.numel()
+        with torch.cuda.device(dev):
+            s = stream if stream is not None else torch.cuda.current_stream(dev)
+            self.stream = s
+            scratch = torch.empty(8 * L + 256, dtype=torch.uint8, device=dev)
+            self.passes, total = spdnn_csr_passes(N, L, [q.data_ptr() for q in ptr], scratch.data_ptr(),
+                                                  scratch.numel(), s.cuda_stream)
+            del scratch
+            self.widest_window = None
+            nbytes = spdnn_weights_bytes(N, total)
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            self.h = spdnn_create_csr(N, L, [q.data_ptr() for q in ptr], [a.data_ptr() for a in idx],
+                                      [v.data_ptr() for v in val], b.data_ptr(), self.arena.data_ptr(), nbytes,
+                                      s.cuda_stream)
+        self.work = None
+
     def infer(self, Y0, want_Y=True):
         """Y0: CUDA float32 [batch, N].  Returns (n_active, active_rows[int32 n], Y[n, N] or None)."""
         torch = self.torch
@@ -233,6 +306,9 @@ class Model:
 
     def layer_kernel(self, l):
         return spdnn_layer_kernel(self.h, l)
+
+    def layer_passes(self, l):
+        return spdnn_layer_passes(self.h, l)
 
     def close(self):
         if getattr(self, "h", None):

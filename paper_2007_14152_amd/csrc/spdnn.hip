@@ -5,8 +5,10 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
+#include <cstdint>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -52,6 +54,8 @@ struct LayerDesc {
     int lds_cols;  // columns the LDS tile must hold for this layer
     float wuni;    // kPair, kWidePair: the layer's weight
     bool pair4;    // kWidePair: 3 or 4 stages -> slot lists resident in registers
+    int pass;      // what this pass's epilogue does (spdnn::kPassAdd | spdnn::kPassFinal)
+    bool multi;    // one of several passes over a layer with more than 32 connections per neuron
 };
 
 }  // namespace
@@ -61,7 +65,8 @@ struct spdnn_model {
     hipStream_t stream = nullptr;
     int num_cu = 256;
     const float* bias_dev = nullptr;
-    std::vector<LayerDesc> layers;
+    std::vector<LayerDesc> layers;     // one per pass; a layer is one pass unless some neuron has more than 32 connections
+    std::vector<int32_t> first_pass;   // L+1 entries: layer l is passes first_pass[l] .. first_pass[l+1]-1
     int* host_counts = nullptr;  // pinned, L+1 entries: rows active on entry to layer l
     hipEvent_t lag_ev[kLag] = {nullptr, nullptr};
     // profiling
@@ -104,6 +109,7 @@ size_t staging_bytes(int32_t N, int32_t L) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
     return up((size_t)N * spdnn::kNnz * sizeof(int32_t)) + up((size_t)N * spdnn::kNnz * sizeof(float)) +
            up((size_t)nblk * spdnn::kCap * sizeof(uint16_t)) +  // column -> LDS slot table of the layer being set up
+           up(sizeof(int) * (size_t)nblk) +                     // general layers: smallest column of every block
            up(sizeof(int) * (size_t)(5 * L + 1));  // error flag; per layer: wide failure, widest window, weights differ, pair info[2]
 }
 size_t arena_bytes_for(int32_t N, int32_t L, int nstage_cap) {
@@ -142,10 +148,274 @@ size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
     return o;
 }
 
-template <bool MULTI>
+template <bool MULTI, bool PASSES>
 hipError_t allow_big_lds() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_layer_kernel<MULTI>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_layer_kernel<MULTI, PASSES>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)spdnn::tile_pair_bytes(spdnn::kCap));
+}
+
+
+// Longest neuron of every layer of a general model -> passes of 32 connections.  scratch: device, 8*L bytes.
+int scan_csr(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev, size_t scratch_bytes,
+             hipStream_t stream, std::vector<int32_t>* passes_of) {
+    if (scratch_bytes < sizeof(int) * 2 * (size_t)L)
+        return fail(SPDNN_ESIZE, "scratch has %zu bytes, %zu needed", scratch_bytes, sizeof(int) * 2 * (size_t)L);
+    if (reinterpret_cast<uintptr_t>(scratch_dev) % 8) return fail(SPDNN_EINVAL, "scratch must be 8-byte aligned");
+    int* out = static_cast<int*>(scratch_dev);
+    HIP_TRY(hipMemsetAsync(out, 0, sizeof(int) * 2 * (size_t)L, stream));
+    for (int32_t l = 0; l < L; ++l) {
+        if (!ptr[l]) return fail(SPDNN_EINVAL, "ptr[%d] is NULL", l);
+        spdnn::csr_scan_kernel<<<(N + 255) / 256, 256, 0, stream>>>(ptr[l], N, out + 2 * l);
+    }
+    HIP_TRY(hipGetLastError());
+    std::vector<int> h(2 * (size_t)L);
+    HIP_TRY(hipMemcpyAsync(h.data(), out, sizeof(int) * h.size(), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    passes_of->assign((size_t)L, 1);
+    for (int32_t l = 0; l < L; ++l) {
+        if (h[2 * l + 1]) return fail(SPDNN_EINVAL, "ptr[%d] is negative somewhere or decreases", l);
+        (*passes_of)[l] = std::max(1, (h[2 * l] + spdnn::kNnz - 1) / spdnn::kNnz);
+    }
+    return SPDNN_OK;
+}
+
+// Set-up shared by spdnn_create (ptr == NULL: every layer is [N][32]) and spdnn_create_csr
+// (device arrays; layer l is cut into passes_of[l] passes of 32 connections per neuron).
+int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& passes_of, const int32_t* const* ptr,
+                const int32_t* const* idx, const float* const* val, const float* bias, int32_t where,
+                void* weights_arena, size_t weights_arena_bytes, hipStream_t stream) {
+    int32_t P = 0;  // passes = layers as the kernels see them
+    std::vector<int32_t> layer_of, round_of, first_pass((size_t)L + 1, 0);
+    for (int32_t l = 0; l < L; ++l) {
+        first_pass[l] = P;
+        for (int32_t r = 0; r < passes_of[l]; ++r) {
+            layer_of.push_back(l);
+            round_of.push_back(r);
+        }
+        P += passes_of[l];
+    }
+    first_pass[L] = P;
+    // The arena decides how many stages the wide format may use (0 = none: layers with
+    // wide windows then run the staged kernel, which is slower but needs no extra room).
+    int nstage_cap = stages_of(N);
+    while (nstage_cap > 1 && arena_bytes_for(N, P, nstage_cap) > weights_arena_bytes) --nstage_cap;
+    if (nstage_cap < 2) nstage_cap = 0;
+    {
+        const size_t need = arena_bytes_for(N, P, nstage_cap);
+        if (weights_arena_bytes < need)
+            return fail(SPDNN_ESIZE, "weights arena has %zu bytes, at least %zu needed", weights_arena_bytes, need);
+    }
+
+    const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
+
+    // bias: must be <= 0 everywhere, otherwise a dropped (all-zero) row would not stay zero
+    std::vector<float> hb(N);
+    if (where == SPDNN_HOST) {
+        std::memcpy(hb.data(), bias, sizeof(float) * N);
+    } else {
+        HIP_TRY(hipMemcpy(hb.data(), bias, sizeof(float) * N, hipMemcpyDeviceToHost));
+    }
+    for (int32_t j = 0; j < N; ++j)
+        if (!(hb[j] <= 0.0f) || !std::isfinite(hb[j]))
+            return fail(SPDNN_EBIAS, "bias[%d] = %g: every bias must be finite and <= 0", j, (double)hb[j]);
+
+    spdnn_model* m = new (std::nothrow) spdnn_model;
+    if (!m) return fail(SPDNN_EHIP, "out of host memory");
+    struct Guard {
+        spdnn_model* m;
+        ~Guard() {
+            if (m) spdnn_destroy(m);
+        }
+    } guard{m};
+
+    m->N = N;
+    m->L = L;
+    m->first_pass = first_pass;
+    m->nblk = nblk;
+    m->G = (nblk % 4 == 0) ? 4 : (nblk % 3 == 0) ? 3 : (nblk % 2 == 0) ? 2 : 1;
+    m->stream = stream;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    m->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    HIP_TRY((allow_big_lds<false, false>()));
+    HIP_TRY((allow_big_lds<true, false>()));
+    HIP_TRY((allow_big_lds<false, true>()));
+    HIP_TRY((allow_big_lds<true, true>()));
+    constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
+    constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
+    const int tile_lds = (int)spdnn::tile_pair_bytes(spdnn::kCap);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::order_pack_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::wide_pack_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<1>)));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<2>)));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + 2 * spdnn::kBufSkew));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<4, 16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<2, 32>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
+                          hipHostMallocDefault));
+    for (int i = 0; i < kLag; ++i) HIP_TRY(hipEventCreateWithFlags(&m->lag_ev[i], hipEventDisableTiming));
+
+    // carve the arena: bias | P x (win, rel, val) | staging (raw idx, raw val, error flag)
+    char* base = static_cast<char*>(weights_arena);
+    size_t o = 0;
+    float* bias_dev = reinterpret_cast<float*>(base + o);
+    o += up((size_t)N * sizeof(float));
+    HIP_TRY(hipMemcpyAsync(bias_dev, hb.data(), sizeof(float) * N, hipMemcpyHostToDevice, stream));
+    m->bias_dev = bias_dev;
+    const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
+    std::vector<int2*> win_dev(P);
+    m->layers.resize(P);
+    for (int32_t l = 0; l < P; ++l) {
+        int2* win = reinterpret_cast<int2*>(base + o);
+        o += up((size_t)nblk * sizeof(int2));
+        uint16_t* rel = reinterpret_cast<uint16_t*>(base + o);
+        o += up(e * sizeof(uint16_t));
+        float* wv = reinterpret_cast<float*>(base + o);
+        o += up(e * sizeof(float));
+        uint32_t* qsel = reinterpret_cast<uint32_t*>(base + o);
+        o += up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t));
+        m->layers[l].w = spdnn::LayerWeights{rel, wv, win, qsel};
+        win_dev[l] = win;
+        spdnn::WideWeights ww{};
+        ww.win = win;
+        if (nstage_cap >= 2) {  // room for the wide format; the layer's own stage count strides the arrays
+            const size_t we = (size_t)nblk * wide_steps_max(nstage_cap) * spdnn::kBlk;
+            const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
+            ww.pk = reinterpret_cast<uint2*>(base + o);
+            o += up(we * sizeof(uint2));
+            ww.nb8 = reinterpret_cast<uint8_t*>(base + o);
+            o += up((size_t)nblk * nstage_cap * 16);
+            ww.spill_col = reinterpret_cast<uint16_t*>(base + o);
+            o += up(sp * sizeof(uint16_t));
+            ww.spill_val = reinterpret_cast<float*>(base + o);
+            o += up(sp * sizeof(float));
+            ww.spill_n = reinterpret_cast<uint8_t*>(base + o);
+            o += up((size_t)nblk * 16);
+            if (wide_has_slots(nstage_cap)) {
+                ww.ps = reinterpret_cast<uint4*>(base + o);
+                o += up(we * sizeof(uint16_t));
+                ww.sp16 = reinterpret_cast<uint16_t*>(base + o);
+                o += up(sp * sizeof(uint16_t));
+            }
+        }
+        m->layers[l].ww = ww;
+    }
+    int32_t* st_idx = reinterpret_cast<int32_t*>(base + o);
+    o += up((size_t)N * spdnn::kNnz * sizeof(int32_t));
+    float* st_val = reinterpret_cast<float*>(base + o);
+    o += up((size_t)N * spdnn::kNnz * sizeof(float));
+    uint16_t* slot_tab = reinterpret_cast<uint16_t*>(base + o);
+    o += up((size_t)nblk * spdnn::kCap * sizeof(uint16_t));
+    int* blockmin = reinterpret_cast<int*>(base + o);
+    o += up(sizeof(int) * (size_t)nblk);
+    // [0] bad column seen; [1 + p] pass p could not use the wide format; [1 + P + p] pass p's widest window;
+    // [1 + 2P + p] pass p has more than one weight value; [1 + 3P + 2p] {two neurons per lane possible, weight bits}
+    int* err_dev = reinterpret_cast<int*>(base + o);
+    HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int) * (size_t)(5 * P + 1), stream));
+
+    const size_t raw = (size_t)N * spdnn::kNnz;
+    std::vector<int2> hw((size_t)P * nblk);
+    for (int32_t l = 0; l < P; ++l) {  // l = pass; it belongs to layer ll
+        const int32_t ll = layer_of[l];
+        const int32_t* di = idx[ll];
+        const float* dv = val[ll];
+        LayerDesc& d = m->layers[l];
+        d.multi = passes_of[ll] > 1;
+        d.pass = (round_of[l] > 0 ? spdnn::kPassAdd : 0) | (round_of[l] == passes_of[ll] - 1 ? spdnn::kPassFinal : 0);
+        if (ptr) {  // general layer: connections 32r .. 32r+31 of every neuron, padded with zero weights
+            const int r = round_of[l];
+            spdnn::csr_block_min_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(ptr[ll], idx[ll], N, r, blockmin);
+            spdnn::csr_round_kernel<<<(unsigned)((raw + 255) / 256), 256, 0, stream>>>(ptr[ll], idx[ll], val[ll], N, r,
+                                                                                     blockmin, st_idx, st_val);
+            HIP_TRY(hipGetLastError());
+            di = st_idx;
+            dv = st_val;
+        } else if (where == SPDNN_HOST) {
+            HIP_TRY(hipMemcpyAsync(st_idx, idx[ll], raw * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+            HIP_TRY(hipMemcpyAsync(st_val, val[ll], raw * sizeof(float), hipMemcpyHostToDevice, stream));
+            di = st_idx;
+            dv = st_val;
+        }
+        int* widest_dev = err_dev + 1 + P + l;
+        int* pair_dev = err_dev + 1 + 3 * P + 2 * l;
+        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev, widest_dev, dv,
+                                                                       err_dev + 1 + 2 * P + l);
+        // a layer of several passes runs the one-neuron-per-lane kernels, whose epilogue knows about passes
+        if (!d.multi)
+            spdnn::pair_merge_kernel<<<1, 64, 0, stream>>>(win_dev[l], nblk, N, dv, err_dev + 1 + 2 * P + l, widest_dev,
+                                                           pair_dev);
+        HIP_TRY(hipGetLastError());
+        // the windows decide the layer's kernel and its set-up; they are small, so read them back now
+        int pair_info[2] = {0, 0};
+        HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipMemcpyAsync(pair_info, pair_dev, sizeof(pair_info), hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        const int pair = pair_info[0] == 1;        // two neurons per lane, single stage
+        const bool wide_pair = pair_info[0] == 2;  // ... if the layer also fits the wide format
+        if (pair)
+            spdnn::balance_kernel<2><<<nblk / 2, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<2>), stream>>>(
+                di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
+        else
+            spdnn::balance_kernel<1><<<nblk, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<1>), stream>>>(
+                di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
+        spdnn::order_pack_kernel<<<nblk, spdnn::kOrderThreads, order_lds, stream>>>(
+            di, dv, N, win_dev[l], widest_dev, slot_tab, pair, const_cast<uint16_t*>(d.w.rel),
+            const_cast<float*>(d.w.val));
+        HIP_TRY(hipGetLastError());
+        int widest = 4;
+        for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[(size_t)l * nblk + b].y);
+        const int nst = stages_of(widest);
+        d.lds_cols = std::min(widest, spdnn::kCap);
+        d.mode = pair ? kPair : nst <= 1 ? kSingle : kStaged;
+        std::memcpy(&d.wuni, &pair_info[1], sizeof(float));
+        // the wide format: 3 and more stages, or 2 stages when the layer can run two neurons per lane
+        if (!d.multi && (nst >= 3 || (nst == 2 && wide_pair && d.ww.ps)) && nst <= nstage_cap) {
+            d.ww.nstage = nst;
+            spdnn::wide_pack_kernel<<<nblk, spdnn::kOrderThreads, wide_lds, stream>>>(
+                di, dv, N, win_dev[l], nst, const_cast<uint2*>(d.ww.pk), const_cast<uint8_t*>(d.ww.nb8), const_cast<uint16_t*>(d.ww.spill_col),
+                const_cast<float*>(d.ww.spill_val), const_cast<uint8_t*>(d.ww.spill_n), err_dev + 1 + l);
+            HIP_TRY(hipGetLastError());
+            d.mode = kWide;
+            if (wide_pair && spdnn::wide_steps(nst) >= 16 && d.ww.ps) {
+                const int S = spdnn::wide_steps(nst);
+                const size_t n_out = (size_t)nblk * nst * (S / 8) * spdnn::kBlk;
+                spdnn::wide_slots_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, stream>>>(
+                    d.ww.pk, const_cast<uint4*>(d.ww.ps), n_out, S);
+                const size_t n_sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
+                spdnn::wide_spill16_kernel<<<(unsigned)((n_sp + 255) / 256), 256, 0, stream>>>(
+                    d.ww.spill_col, d.ww.spill_val, const_cast<uint16_t*>(d.ww.sp16), n_sp);
+                HIP_TRY(hipGetLastError());
+                d.mode = kWidePair;
+                d.pair4 = nst <= 4;
+            }
+        }
+        if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
+    }
+    // error flag and the layers whose patterns did not fit the wide format
+    std::vector<int> herr((size_t)P + 1, 0);
+    HIP_TRY(hipMemcpyAsync(herr.data(), err_dev, sizeof(int) * (size_t)(P + 1), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (herr[0]) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
+    for (int32_t l = 0; l < P; ++l)
+        if ((m->layers[l].mode == kWide || m->layers[l].mode == kWidePair) && herr[1 + l]) m->layers[l].mode = kStaged;
+    guard.m = nullptr;
+    *out = m;
+    return SPDNN_OK;
 }
 
 }  // namespace
@@ -250,210 +520,43 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
     if (reinterpret_cast<uintptr_t>(weights_arena) % kAlign) return fail(SPDNN_EINVAL, "weights_arena must be 256-byte aligned");
     for (int32_t l = 0; l < L; ++l)
         if (!idx[l] || !val[l]) return fail(SPDNN_EINVAL, "idx[%d] or val[%d] is NULL", l, l);
-    // The arena decides how many stages the wide format may use (0 = none: layers with
-    // wide windows then run the staged kernel, which is slower but needs no extra room).
-    int nstage_cap = stages_of(N);
-    while (nstage_cap > 1 && arena_bytes_for(N, L, nstage_cap) > weights_arena_bytes) --nstage_cap;
-    if (nstage_cap < 2) nstage_cap = 0;
-    {
-        const size_t need = arena_bytes_for(N, L, nstage_cap);
-        if (weights_arena_bytes < need)
-            return fail(SPDNN_ESIZE, "weights arena has %zu bytes, at least %zu needed", weights_arena_bytes, need);
-    }
+    return create_impl(out, N, L, std::vector<int32_t>((size_t)L, 1), nullptr, idx, val, bias, where, weights_arena,
+                       weights_arena_bytes, reinterpret_cast<hipStream_t>(hip_stream));
+}
 
-    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-    const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
-
-    // bias: must be <= 0 everywhere, otherwise a dropped (all-zero) row would not stay zero
-    std::vector<float> hb(N);
-    if (where == SPDNN_HOST) {
-        std::memcpy(hb.data(), bias, sizeof(float) * N);
-    } else {
-        HIP_TRY(hipMemcpy(hb.data(), bias, sizeof(float) * N, hipMemcpyDeviceToHost));
-    }
-    for (int32_t j = 0; j < N; ++j)
-        if (!(hb[j] <= 0.0f) || !std::isfinite(hb[j]))
-            return fail(SPDNN_EBIAS, "bias[%d] = %g: every bias must be finite and <= 0", j, (double)hb[j]);
-
-    spdnn_model* m = new (std::nothrow) spdnn_model;
-    if (!m) return fail(SPDNN_EHIP, "out of host memory");
-    struct Guard {
-        spdnn_model* m;
-        ~Guard() {
-            if (m) spdnn_destroy(m);
-        }
-    } guard{m};
-
-    m->N = N;
-    m->L = L;
-    m->nblk = nblk;
-    m->G = (nblk % 4 == 0) ? 4 : (nblk % 3 == 0) ? 3 : (nblk % 2 == 0) ? 2 : 1;
-    m->stream = stream;
-    int dev = 0;
-    HIP_TRY(hipGetDevice(&dev));
-    hipDeviceProp_t prop;
-    HIP_TRY(hipGetDeviceProperties(&prop, dev));
-    m->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    HIP_TRY(allow_big_lds<false>());
-    HIP_TRY(allow_big_lds<true>());
-    constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
-    constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
-    const int tile_lds = (int)spdnn::tile_pair_bytes(spdnn::kCap);
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::order_pack_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::wide_pack_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<1>)));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<2>)));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + 2 * spdnn::kBufSkew));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<4, 16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<2, 32>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
-    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
-                          hipHostMallocDefault));
-    for (int i = 0; i < kLag; ++i) HIP_TRY(hipEventCreateWithFlags(&m->lag_ev[i], hipEventDisableTiming));
-
-    // carve the arena: bias | L x (win, rel, val) | staging (raw idx, raw val, error flag)
-    char* base = static_cast<char*>(weights_arena);
-    size_t o = 0;
-    float* bias_dev = reinterpret_cast<float*>(base + o);
-    o += up((size_t)N * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(bias_dev, hb.data(), sizeof(float) * N, hipMemcpyHostToDevice, stream));
-    m->bias_dev = bias_dev;
-    const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
-    std::vector<int2*> win_dev(L);
-    m->layers.resize(L);
+int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev, size_t scratch_bytes,
+                     void* hip_stream, int32_t* passes, int32_t* total) {
+    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+    if (!ptr || !scratch_dev || !total) return fail(SPDNN_EINVAL, "null argument");
+    std::vector<int32_t> po;
+    const int rc = scan_csr(N, L, ptr, scratch_dev, scratch_bytes, reinterpret_cast<hipStream_t>(hip_stream), &po);
+    if (rc != SPDNN_OK) return rc;
+    int64_t sum = 0;
     for (int32_t l = 0; l < L; ++l) {
-        int2* win = reinterpret_cast<int2*>(base + o);
-        o += up((size_t)nblk * sizeof(int2));
-        uint16_t* rel = reinterpret_cast<uint16_t*>(base + o);
-        o += up(e * sizeof(uint16_t));
-        float* wv = reinterpret_cast<float*>(base + o);
-        o += up(e * sizeof(float));
-        uint32_t* qsel = reinterpret_cast<uint32_t*>(base + o);
-        o += up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t));
-        m->layers[l].w = spdnn::LayerWeights{rel, wv, win, qsel};
-        win_dev[l] = win;
-        spdnn::WideWeights ww{};
-        ww.win = win;
-        if (nstage_cap >= 2) {  // room for the wide format; the layer's own stage count strides the arrays
-            const size_t we = (size_t)nblk * wide_steps_max(nstage_cap) * spdnn::kBlk;
-            const size_t sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
-            ww.pk = reinterpret_cast<uint2*>(base + o);
-            o += up(we * sizeof(uint2));
-            ww.nb8 = reinterpret_cast<uint8_t*>(base + o);
-            o += up((size_t)nblk * nstage_cap * 16);
-            ww.spill_col = reinterpret_cast<uint16_t*>(base + o);
-            o += up(sp * sizeof(uint16_t));
-            ww.spill_val = reinterpret_cast<float*>(base + o);
-            o += up(sp * sizeof(float));
-            ww.spill_n = reinterpret_cast<uint8_t*>(base + o);
-            o += up((size_t)nblk * 16);
-            if (wide_has_slots(nstage_cap)) {
-                ww.ps = reinterpret_cast<uint4*>(base + o);
-                o += up(we * sizeof(uint16_t));
-                ww.sp16 = reinterpret_cast<uint16_t*>(base + o);
-                o += up(sp * sizeof(uint16_t));
-            }
-        }
-        m->layers[l].ww = ww;
+        if (passes) passes[l] = po[l];
+        sum += po[l];
     }
-    int32_t* st_idx = reinterpret_cast<int32_t*>(base + o);
-    o += up((size_t)N * spdnn::kNnz * sizeof(int32_t));
-    float* st_val = reinterpret_cast<float*>(base + o);
-    o += up((size_t)N * spdnn::kNnz * sizeof(float));
-    uint16_t* slot_tab = reinterpret_cast<uint16_t*>(base + o);
-    o += up((size_t)nblk * spdnn::kCap * sizeof(uint16_t));
-    // [0] bad column seen; [1 + l] layer l could not use the wide format; [1 + L + l] layer l's widest window;
-    // [1 + 2L + l] layer l has more than one weight value; [1 + 3L + 2l] {two neurons per lane possible, weight bits}
-    int* err_dev = reinterpret_cast<int*>(base + o);
-    HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int) * (size_t)(5 * L + 1), stream));
-
-    const size_t raw = (size_t)N * spdnn::kNnz;
-    std::vector<int2> hw((size_t)L * nblk);
-    for (int32_t l = 0; l < L; ++l) {
-        const int32_t* di = idx[l];
-        const float* dv = val[l];
-        if (where == SPDNN_HOST) {
-            HIP_TRY(hipMemcpyAsync(st_idx, idx[l], raw * sizeof(int32_t), hipMemcpyHostToDevice, stream));
-            HIP_TRY(hipMemcpyAsync(st_val, val[l], raw * sizeof(float), hipMemcpyHostToDevice, stream));
-            di = st_idx;
-            dv = st_val;
-        }
-        LayerDesc& d = m->layers[l];
-        int* widest_dev = err_dev + 1 + L + l;
-        int* pair_dev = err_dev + 1 + 3 * L + 2 * l;
-        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev, widest_dev, dv,
-                                                                       err_dev + 1 + 2 * L + l);
-        spdnn::pair_merge_kernel<<<1, 64, 0, stream>>>(win_dev[l], nblk, N, dv, err_dev + 1 + 2 * L + l, widest_dev,
-                                                       pair_dev);
-        HIP_TRY(hipGetLastError());
-        // the windows decide the layer's kernel and its set-up; they are small, so read them back now
-        int pair_info[2] = {0, 0};
-        HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
-        HIP_TRY(hipMemcpyAsync(pair_info, pair_dev, sizeof(pair_info), hipMemcpyDeviceToHost, stream));
-        HIP_TRY(hipStreamSynchronize(stream));
-        const int pair = pair_info[0] == 1;        // two neurons per lane, single stage
-        const bool wide_pair = pair_info[0] == 2;  // ... if the layer also fits the wide format
-        if (pair)
-            spdnn::balance_kernel<2><<<nblk / 2, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<2>), stream>>>(
-                di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
-        else
-            spdnn::balance_kernel<1><<<nblk, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<1>), stream>>>(
-                di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
-        spdnn::order_pack_kernel<<<nblk, spdnn::kOrderThreads, order_lds, stream>>>(
-            di, dv, N, win_dev[l], widest_dev, slot_tab, pair, const_cast<uint16_t*>(d.w.rel),
-            const_cast<float*>(d.w.val));
-        HIP_TRY(hipGetLastError());
-        int widest = 4;
-        for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[(size_t)l * nblk + b].y);
-        const int nst = stages_of(widest);
-        d.lds_cols = std::min(widest, spdnn::kCap);
-        d.mode = pair ? kPair : nst <= 1 ? kSingle : kStaged;
-        std::memcpy(&d.wuni, &pair_info[1], sizeof(float));
-        // the wide format: 3 and more stages, or 2 stages when the layer can run two neurons per lane
-        if ((nst >= 3 || (nst == 2 && wide_pair && d.ww.ps)) && nst <= nstage_cap) {
-            d.ww.nstage = nst;
-            spdnn::wide_pack_kernel<<<nblk, spdnn::kOrderThreads, wide_lds, stream>>>(
-                di, dv, N, win_dev[l], nst, const_cast<uint2*>(d.ww.pk), const_cast<uint8_t*>(d.ww.nb8), const_cast<uint16_t*>(d.ww.spill_col),
-                const_cast<float*>(d.ww.spill_val), const_cast<uint8_t*>(d.ww.spill_n), err_dev + 1 + l);
-            HIP_TRY(hipGetLastError());
-            d.mode = kWide;
-            if (wide_pair && spdnn::wide_steps(nst) >= 16 && d.ww.ps) {
-                const int S = spdnn::wide_steps(nst);
-                const size_t n_out = (size_t)nblk * nst * (S / 8) * spdnn::kBlk;
-                spdnn::wide_slots_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, stream>>>(
-                    d.ww.pk, const_cast<uint4*>(d.ww.ps), n_out, S);
-                const size_t n_sp = (size_t)nblk * spdnn::kSpill * spdnn::kBlk;
-                spdnn::wide_spill16_kernel<<<(unsigned)((n_sp + 255) / 256), 256, 0, stream>>>(
-                    d.ww.spill_col, d.ww.spill_val, const_cast<uint16_t*>(d.ww.sp16), n_sp);
-                HIP_TRY(hipGetLastError());
-                d.mode = kWidePair;
-                d.pair4 = nst <= 4;
-            }
-        }
-        if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
-    }
-    // error flag and the layers whose patterns did not fit the wide format
-    std::vector<int> herr((size_t)L + 1, 0);
-    HIP_TRY(hipMemcpyAsync(herr.data(), err_dev, sizeof(int) * (size_t)(L + 1), hipMemcpyDeviceToHost, stream));
-    HIP_TRY(hipStreamSynchronize(stream));
-    if (herr[0]) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
-    for (int32_t l = 0; l < L; ++l)
-        if ((m->layers[l].mode == kWide || m->layers[l].mode == kWidePair) && herr[1 + l]) m->layers[l].mode = kStaged;
-    guard.m = nullptr;
-    *out = m;
+    if (sum > INT32_MAX) return fail(SPDNN_EINVAL, "too many passes");
+    *total = (int32_t)sum;
     return SPDNN_OK;
+}
+
+int spdnn_create_csr(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx,
+                     const float* const* val, const float* bias, void* weights_arena, size_t weights_arena_bytes,
+                     void* hip_stream) {
+    if (!out) return fail(SPDNN_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+    if (!ptr || !idx || !val || !bias || !weights_arena) return fail(SPDNN_EINVAL, "null argument");
+    if (reinterpret_cast<uintptr_t>(weights_arena) % kAlign) return fail(SPDNN_EINVAL, "weights_arena must be 256-byte aligned");
+    for (int32_t l = 0; l < L; ++l)
+        if (!ptr[l] || !idx[l] || !val[l]) return fail(SPDNN_EINVAL, "ptr[%d], idx[%d] or val[%d] is NULL", l, l, l);
+    // the arena's head serves as scratch for the scan; nothing else is in it yet
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    std::vector<int32_t> passes_of;
+    const int rc = scan_csr(N, L, ptr, weights_arena, weights_arena_bytes, stream, &passes_of);
+    if (rc != SPDNN_OK) return rc;
+    return create_impl(out, N, L, passes_of, ptr, idx, val, bias, SPDNN_DEVICE, weights_arena, weights_arena_bytes, stream);
 }
 
 int spdnn_destroy(spdnn_t h) {
@@ -487,7 +590,15 @@ int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind) {
     static_assert(kSingle == SPDNN_KERNEL_SINGLE && kStaged == SPDNN_KERNEL_STAGED && kWide == SPDNN_KERNEL_WIDE &&
                       kPair == SPDNN_KERNEL_PAIR && kWidePair == SPDNN_KERNEL_WIDE_PAIR,
                   "layer modes are the header's kernel kinds");
-    *kind = (h->layers[l].mode == kWidePair && h->layers[l].pair4) ? SPDNN_KERNEL_WIDE_PAIR4 : h->layers[l].mode;
+    const LayerDesc& d = h->layers[h->first_pass[l]];
+    *kind = (d.mode == kWidePair && d.pair4) ? SPDNN_KERNEL_WIDE_PAIR4 : d.mode;
+    return SPDNN_OK;
+}
+
+int spdnn_layer_passes(spdnn_t h, int32_t l, int32_t* passes) {
+    if (!h || !passes) return fail(SPDNN_EINVAL, "null argument");
+    if (l < 0 || l >= h->L) return fail(SPDNN_EINVAL, "layer %d outside [0, %d)", l, h->L);
+    *passes = h->first_pass[l + 1] - h->first_pass[l];
     return SPDNN_OK;
 }
 
@@ -528,54 +639,63 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
     int32_t bound = batch;  // upper bound of the rows active at the layer being launched
     int32_t run = 0;        // layers launched
     for (int32_t l = 0; l < L; ++l) {
-        const LayerDesc& d = h->layers[l];
         const float* Yin = (l == 0) ? Y0_dev : wv.Y[(l - 1) & 1];
         float* Yout = wv.Y[l & 1];
-        // launch shape: one workgroup per CU; the rows are cut into Q chunks per output block
-        const int32_t ngroups = (bound + spdnn::kRows - 1) / spdnn::kRows;
-        // kPair: the workgroups' column blocks are pairs of output blocks
-        const bool two = d.mode == kPair || d.mode == kWidePair;
-        const int32_t ncb = two ? h->nblk / 2 : h->nblk;
-        // Workgroups that read the same rows go to one XCD (32 CUs, one L2).  In a wide layer every
-        // column block reads whole rows: as many of them as possible share an XCD, so that a row is
-        // fetched from memory once, not once per XCD.
-        int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1) : h->G;
-        if (d.mode == kWide || d.mode == kWidePair)
-            for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
-                if (ncb % g == 0) {
-                    G = g;
-                    break;
-                }
-        int32_t Q = std::max(1, h->num_cu / ncb);
-        Q = std::max(1, std::min(Q, ngroups));
-        const int32_t units = (ncb / G) * Q;
-        const int32_t grid = (units + 7) / 8 * 8 * G;
-        const size_t lds = spdnn::tile_pair_bytes((d.lds_cols + 255) / 256 * 256);  // whole waves of 256 columns
         if (h->profiling) HIP_TRY(hipEventRecord(h->t0[l], s));
-        if (d.mode == kPair)
-            spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
-                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
-        else if (d.mode == kWidePair && d.pair4 && d.ww.nstage == 2)  // + the all-zero entries and the spill table
-            spdnn::fused_wide_pair4_kernel<2, 32><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
-                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
-        else if (d.mode == kWidePair && d.pair4)
-            spdnn::fused_wide_pair4_kernel<4, 16><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
-                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
-        else if (d.mode == kWidePair)
-            spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + 2 * spdnn::kBufSkew, s>>>(
-                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
-        else if (d.mode == kWide && d.ww.nstage > 8)
-            spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(
-                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
-        else if (d.mode == kWide)
-            spdnn::fused_wide_kernel<16><<<grid, spdnn::kBlk, lds, s>>>(
-                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
-        else if (d.mode == kStaged)
-            spdnn::fused_layer_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(
-                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
-        else
-            spdnn::fused_layer_kernel<false><<<grid, spdnn::kBlk, lds, s>>>(
-                Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
+        // one launch per pass: a layer is a single pass unless some neuron has more than 32 connections
+        for (int32_t p = h->first_pass[l]; p < h->first_pass[l + 1]; ++p) {
+            const LayerDesc& d = h->layers[p];
+            // launch shape: one workgroup per CU; the rows are cut into Q chunks per output block
+            const int32_t ngroups = (bound + spdnn::kRows - 1) / spdnn::kRows;
+            // kPair: the workgroups' column blocks are pairs of output blocks
+            const bool two = d.mode == kPair || d.mode == kWidePair;
+            const int32_t ncb = two ? h->nblk / 2 : h->nblk;
+            // Workgroups that read the same rows go to one XCD (32 CUs, one L2).  In a wide layer every
+            // column block reads whole rows: as many of them as possible share an XCD, so that a row is
+            // fetched from memory once, not once per XCD.
+            int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1) : h->G;
+            if (d.mode == kWide || d.mode == kWidePair)
+                for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
+                    if (ncb % g == 0) {
+                        G = g;
+                        break;
+                    }
+            int32_t Q = std::max(1, h->num_cu / ncb);
+            Q = std::max(1, std::min(Q, ngroups));
+            const int32_t units = (ncb / G) * Q;
+            const int32_t grid = (units + 7) / 8 * 8 * G;
+            const size_t lds = spdnn::tile_pair_bytes((d.lds_cols + 255) / 256 * 256);  // whole waves of 256 columns
+            if (d.multi && d.mode == kStaged)
+                spdnn::fused_layer_kernel<true, true><<<grid, spdnn::kBlk, lds, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q, d.pass);
+            else if (d.multi)
+                spdnn::fused_layer_kernel<false, true><<<grid, spdnn::kBlk, lds, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q, d.pass);
+            else if (d.mode == kPair)
+                spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
+            else if (d.mode == kWidePair && d.pair4 && d.ww.nstage == 2)  // + the all-zero entries and the spill table
+                spdnn::fused_wide_pair4_kernel<2, 32><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+            else if (d.mode == kWidePair && d.pair4)
+                spdnn::fused_wide_pair4_kernel<4, 16><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+            else if (d.mode == kWidePair)
+                spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + 2 * spdnn::kBufSkew, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+            else if (d.mode == kWide && d.ww.nstage > 8)
+                spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
+            else if (d.mode == kWide)
+                spdnn::fused_wide_kernel<16><<<grid, spdnn::kBlk, lds, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
+            else if (d.mode == kStaged)
+                spdnn::fused_layer_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
+            else
+                spdnn::fused_layer_kernel<false><<<grid, spdnn::kBlk, lds, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
+        }
         if (h->profiling) HIP_TRY(hipEventRecord(h->t1[l], s));
         spdnn::compact_kernel<<<1, 1024, 0, s>>>(wv.flags, wv.count, wv.gid[l & 1], wv.gid[(l + 1) & 1],
                                                   wv.cat[(l + 1) & 1], h->host_counts + l + 1);

@@ -431,6 +431,65 @@ __device__ __forceinline__ unsigned finish_rows(float (&a)[kRows], float bj, flo
     return pos;
 }
 
+// The same epilogue for a layer that is evaluated in several passes of 32 connections
+// per neuron (neurons with more than 32 connections): every pass but the first adds
+// the partial sums that the pass before left in Yout, every pass but the last stores
+// the raw sums, and the last one adds the bias, clips and reports the rows with a
+// positive output.  Transposes first, so that partial sums, bias and result all move
+// as 16-byte accesses of 4 neighbouring neurons.
+constexpr int kPassAdd = 1;    // add the partial sums found in Yout
+constexpr int kPassFinal = 2;  // bias, clip, row flags
+__device__ __forceinline__ unsigned finish_rows_pass(float (&a)[kRows], const float* __restrict__ bias,
+                                                     float* __restrict__ Yout, int N, int j, bool jok, int row0,
+                                                     int nlive, int lane, int pass) {
+    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
+    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
+    const bool b0 = lane & 1, b1 = lane & 2;
+    float y0 = a[0], y1 = a[1], y2 = a[2], y3 = a[3];
+    a[0] = a[1] = a[2] = a[3] = 0.0f;
+    {
+        const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
+        const float r0 = xor2(s0), r1 = xor2(s1);
+        y0 = b1 ? r0 : y0;
+        y1 = b1 ? r1 : y1;
+        y2 = b1 ? y2 : r0;
+        y3 = b1 ? y3 : r1;
+    }
+    {
+        const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
+        const float r0 = xor1(s0), r1 = xor1(s1);
+        y0 = b0 ? r0 : y0;
+        y1 = b0 ? y1 : r0;
+        y2 = b0 ? r1 : y2;
+        y3 = b0 ? y3 : r1;
+    }
+    // now: row (lane & 3) of neurons (j & ~3) .. (j & ~3) + 3
+    const int r = lane & 3;
+    const bool ok = jok && r < nlive;  // N is a multiple of 4: a quartet of neurons exists as a whole or not at all
+    float4* dst = reinterpret_cast<float4*>(Yout + (size_t)(row0 + (ok ? r : 0)) * N + (jok ? (j & ~3) : 0));
+    if ((pass & kPassAdd) && ok) {
+        const float4 p = *dst;
+        y0 += p.x;
+        y1 += p.y;
+        y2 += p.z;
+        y3 += p.w;
+    }
+    unsigned pos = 0;
+    if (pass & kPassFinal) {
+        const float4 bq = jok ? *reinterpret_cast<const float4*>(bias + (j & ~3)) : make_float4(0.f, 0.f, 0.f, 0.f);
+        y0 = fminf(fmaxf(y0 + bq.x, 0.0f), kClip);
+        y1 = fminf(fmaxf(y1 + bq.y, 0.0f), kClip);
+        y2 = fminf(fmaxf(y2 + bq.z, 0.0f), kClip);
+        y3 = fminf(fmaxf(y3 + bq.w, 0.0f), kClip);
+        const bool any = ok && (y0 > 0.0f || y1 > 0.0f || y2 > 0.0f || y3 > 0.0f);
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(any);  // lane 4q+r speaks for row r
+        pos = ((m & 0x1111111111111111ull) ? 1u : 0u) | ((m & 0x2222222222222222ull) ? 2u : 0u) |
+              ((m & 0x4444444444444444ull) ? 4u : 0u) | ((m & 0x8888888888888888ull) ? 8u : 0u);
+    }
+    if (ok) *dst = make_float4(y0, y1, y2, y3);
+    return pos;
+}
+
 // ---------------------------------------------------------------------------
 // a1: fused SpMM + bias + clipped ReLU for one layer (Eq. 1), plus the per-row
 // "has a positive output" flag that Listings 1 and 2 keep in active[].
@@ -440,12 +499,15 @@ __device__ __forceinline__ unsigned finish_rows(float (&a)[kRows], float bj, flo
 // *count_ptr = number of active rows A.  The grid is nblk * G-aligned units
 // (see unit mapping below); a workgroup handles row groups
 // [q*per, (q+1)*per) of ceil(A/4).
+//
+// PASSES: the launch is one of several passes over a layer whose neurons have more
+// than 32 connections; `pass` says what the epilogue does (finish_rows_pass).
 // ---------------------------------------------------------------------------
-template <bool MULTI>
+template <bool MULTI, bool PASSES = false>
 __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
     int* __restrict__ flags, const int* __restrict__ count_ptr, LayerWeights w,
-    const float* __restrict__ bias, int N, int nblk, int G, int Q) {
+    const float* __restrict__ bias, int N, int nblk, int G, int Q, int pass = kPassFinal) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
 
@@ -606,7 +668,8 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     auto epilogue = [&](int g) {
         const int row0 = g * kRows;
         const int nlive = min(kRows, A - row0);  // rows of this group that exist (>= 1)
-        const unsigned pos = finish_rows(acc, bj, Yout, N, j, jok, row0, nlive, lane);
+        const unsigned pos = PASSES ? finish_rows_pass(acc, bias, Yout, N, j, jok, row0, nlive, lane, pass)
+                                    : finish_rows(acc, bj, Yout, N, j, jok, row0, nlive, lane);
         if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;  // lane r raises row r's flag
     };
 
@@ -1627,6 +1690,69 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
         }
         win[blockIdx.x] = make_int2(c_lo, ncols);
         atomicMax(widest, ncols);  // the layer's widest window (zero before the launch)
+    }
+}
+
+// ---------------------------------------------------------------------------
+// a0 for general sparse layers (Section II-A-1: W_l may be any sparse matrix; Listing 1
+// holds it in CSR; Section III-A-3 pads the neurons of a warp to a common length with
+// zeros): neuron j owns entries ptr[j] .. ptr[j+1]-1.  A layer whose longest neuron
+// has K connections is cut into ceil(K/32) passes of 32 connections per neuron, short
+// neurons padded with zero weights, and every pass then goes through the set-up of a
+// fixed-32 layer.
+// ---------------------------------------------------------------------------
+// out[0] = longest neuron (atomic max; zero before the launch), out[1] = 1 if ptr is
+// negative somewhere or decreases.
+__global__ void csr_scan_kernel(const int32_t* __restrict__ ptr, int N, int* __restrict__ out) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= N) return;
+    const int a = ptr[j], e = ptr[j + 1];
+    if (a < 0 || e < a)
+        out[1] = 1;
+    else
+        atomicMax(out, e - a);
+}
+
+// Pass r of a layer: smallest valid column among entries 32r .. 32r+31 of the neurons of
+// every 1024-neuron block (blockmin[b] = N before the launch).  The padding points there,
+// so that it does not widen the block's column window.
+__global__ __launch_bounds__(kBlk) void csr_block_min_kernel(const int32_t* __restrict__ ptr,
+                                                             const int32_t* __restrict__ idx, int N, int r,
+                                                             int* __restrict__ blockmin) {
+    __shared__ int s_lo;
+    if (threadIdx.x == 0) s_lo = N;
+    __syncthreads();
+    const int j = blockIdx.x * kBlk + threadIdx.x;
+    int lo = N;
+    if (j < N) {
+        const int a = ptr[j] + r * kNnz;
+        const int e = min(ptr[j + 1], a + kNnz);
+        for (int k = a; k < e; ++k) {
+            const int c = idx[k];
+            if (c >= 0) lo = min(lo, c);
+        }
+    }
+    atomicMin(&s_lo, lo);
+    __syncthreads();
+    if (threadIdx.x == 0) blockmin[blockIdx.x] = s_lo;
+}
+
+// Pass r of a layer as a fixed-32 layer: out_idx / out_val [N][32].  One thread per entry.
+__global__ void csr_round_kernel(const int32_t* __restrict__ ptr, const int32_t* __restrict__ idx,
+                                 const float* __restrict__ val, int N, int r, const int* __restrict__ blockmin,
+                                 int32_t* __restrict__ out_idx, float* __restrict__ out_val) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)N * kNnz) return;
+    const int j = (int)(i / kNnz);
+    const int k = (int)(i % kNnz);
+    const int a = ptr[j] + r * kNnz + k;
+    if (a < ptr[j + 1]) {
+        out_idx[i] = idx[a];
+        out_val[i] = val[a];
+    } else {
+        const int lo = blockmin[j / kBlk];
+        out_idx[i] = lo < N ? lo : 0;
+        out_val[i] = 0.0f;
     }
 }
 
