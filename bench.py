@@ -28,6 +28,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch (debug)")
     ap.add_argument("--density", default=None, help="'mixed' = sustained-activity variant (ours)")
+    ap.add_argument("--general", default=None, metavar="KMIN,KMAX",
+                    help="general-layer variant (ours): neurons with KMIN..KMAX connections and varying weights, "
+                         "through spdnn_create_csr; needs --layers (default 6)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
@@ -46,13 +49,13 @@ def measured_traffic(workload_key):
         return None
 
 
-def algorithmic_bytes(rows, N):
+def algorithmic_bytes(rows, N, nnz=None):
     """Bytes one fused-layer launch must move: read and write every (active row,
     neuron) once in float32, plus the layer's weights once (u16 index + f32 value)."""
-    return float(rows) * N * 8.0 + N * 32 * 6.0
+    return float(rows) * N * 8.0 + (N * 32 if nnz is None else nnz) * 6.0
 
 
-def cpu_baseline(c, L, didx, dval, dbias, density, layers_run, target_s):
+def cpu_baseline(c, L, didx, dval, dbias, density, layers_run, target_s, ptr=None, edges_per_row=None):
     """The oracle as it stands, single thread, on a seeded sample of rows of the same
     workload.  Only the layers some row can reach are copied to the host."""
     import numpy as np
@@ -60,22 +63,23 @@ def cpu_baseline(c, L, didx, dval, dbias, density, layers_run, target_s):
     import synth
     N, batch = c["N"], c["batch"]
     have = min(L, layers_run + 4)
-    idx = [didx[l].cpu().numpy() if l < have else None for l in range(L)]
-    val = [dval[l].cpu().numpy() if l < have else None for l in range(L)]
-    bias = dbias.cpu().numpy()
+    tonp = lambda a: a if isinstance(a, np.ndarray) else a.cpu().numpy()
+    idx = [tonp(didx[l]) if l < have else None for l in range(L)]
+    val = [tonp(dval[l]) if l < have else None for l in range(L)]
+    bias = tonp(dbias)
     rng = np.random.default_rng(12345)
 
     def run(nrows):
         ids = np.sort(rng.choice(batch, min(nrows, batch), replace=False))
         y = synth.gen_y0(batch, N, c["seed"], density=density, rows=ids)
         t0 = time.perf_counter()
-        r = oracle.infer(idx, val, bias, y, want_Y=False)
+        r = oracle.infer(idx, val, bias, y, want_Y=False, ptr=ptr)
         return time.perf_counter() - t0, len(ids), r
 
     t, n, _ = run(16)
     rows = int(max(16, min(batch, n * target_s / max(t, 1e-6))))
     t, n, r = run(rows)
-    edges = float(n) * N * 32 * L
+    edges = float(n) * (N * 32 * L if edges_per_row is None else edges_per_row)
     return {"value": edges / t / 1e12, "unit": "TeraEdges/s", "cores": 1, "kind": "oracle",
             "sample": "%d seeded rows of the same workload, all %d layers (%d evaluated before every "
                       "sampled row was inactive), %.2f s single-threaded" % (n, L, r.layers_evaluated, t)}
@@ -99,12 +103,22 @@ def main():
     N, batch = c["N"], c["batch"]
     density = a.density if a.density else synth.DENSITY
     t_setup = time.perf_counter()
-    didx = torch.empty((L, N, 32), dtype=torch.int32, device=dev)
-    for l in range(L):
-        didx[l] = synth.gen_layer(N, l, c["seed"], c["window"], device=dev)
-    dval = torch.full((L, N, 32), synth.WEIGHT, dtype=torch.float32, device=dev)
-    dbias = synth.gen_bias(N, c["bias"], device=dev)
-    model = sp.Model([didx[l] for l in range(L)], [dval[l] for l in range(L)], dbias, device=dev)
+    ptr = nnz = None
+    if a.general:
+        kmin, kmax = (int(x) for x in a.general.split(","))
+        L = a.layers or 6
+        gen = [synth.gen_layer_general(N, l, c["seed"], kmin, kmax, c["window"]) for l in range(L)]
+        ptr, didx, dval = [g[0] for g in gen], [g[1] for g in gen], [g[2] for g in gen]
+        nnz = [int(p[N]) for p in ptr]
+        dbias = synth.gen_bias(N, c["bias"])
+        model = sp.Model.from_csr(ptr, didx, dval, dbias, device=dev)
+    else:
+        didx = torch.empty((L, N, 32), dtype=torch.int32, device=dev)
+        for l in range(L):
+            didx[l] = synth.gen_layer(N, l, c["seed"], c["window"], device=dev)
+        dval = torch.full((L, N, 32), synth.WEIGHT, dtype=torch.float32, device=dev)
+        dbias = synth.gen_bias(N, c["bias"], device=dev)
+        model = sp.Model([didx[l] for l in range(L)], [dval[l] for l in range(L)], dbias, device=dev)
     y0 = synth.gen_y0(batch, N, c["seed"], density=density, device=dev)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
@@ -131,15 +145,19 @@ def main():
         n_active, _, _ = model.infer(y0, want_Y=False)
         run, rows_in, ms = model.profile()
         sum_ms += float(ms.sum())
-        sum_bytes += sum(algorithmic_bytes(r, N) for r in rows_in)
+        sum_bytes += sum(algorithmic_bytes(r, N, nnz[l] if nnz else None) for l, r in enumerate(rows_in))
         launches += run
         rows_trace = rows_in
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     model.set_profiling(False)
 
-    edges = synth.nominal_edges(N, L, batch)
-    executed = float(sum(int(r) for r in rows_trace)) * N * 32
+    if nnz:   # general layers: an edge is a stored connection
+        edges = float(batch) * sum(nnz)
+        executed = float(sum(int(r) * nnz[l] for l, r in enumerate(rows_trace)))
+    else:
+        edges = synth.nominal_edges(N, L, batch)
+        executed = float(sum(int(r) for r in rows_trace)) * N * 32
     ms_per_step = dt / a.steps * 1e3
     achieved = sum_bytes / (sum_ms * 1e-3) / 1e9 if sum_ms > 0 else 0.0
     out = {
@@ -150,7 +168,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "cfg%d: N=%d L=%d batch=%d bias=%g window=%s density=%s" % (
-            a.config, N, L, batch, c["bias"], c["window"], density),
+            a.config, N, L, batch, c["bias"], c["window"], density) + (
+                " general layers %s connections per neuron, passes %s" % (
+                    a.general, [model.layer_passes(l) for l in range(L)]) if a.general else ""),
             "layers_launched": int(launches // a.steps), "rows_in_per_layer": [int(r) for r in rows_trace[:8]],
             "n_active_final": int(n_active), "executed_TeraEdges_per_s": executed * a.steps / dt / 1e12,
             "setup_s": t_setup},
@@ -162,7 +182,8 @@ def main():
                      "algorithmic_bytes_per_launch": sum_bytes / max(launches, 1)},
     }
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(c, L, didx, dval, dbias, density, int(launches // a.steps), a.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(c, L, didx, dval, dbias, density, int(launches // a.steps), a.cpu_seconds,
+                                           ptr=ptr, edges_per_row=float(sum(nnz)) if nnz else None)
     print(json.dumps(out))
 
 
