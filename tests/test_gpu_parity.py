@@ -222,6 +222,33 @@ def test_deterministic_and_device_weights():
     m.close()
 
 
+def test_two_models_and_a_stream_of_the_callers():
+    """Two handles alive at once, one of them on a stream the caller made (default priority),
+    called in turns and with changing batch sizes: each gives what it gives alone."""
+    import torch
+    import paper_2007_14152_amd as sp
+    c, idx, val, bias = config_model(0, 5)
+    c2, idx2, val2, bias2 = config_model(2, 3)
+    Ya = synth.gen_y0(500, c["N"], c["seed"], density="mixed")
+    Yb = synth.gen_y0(90, c2["N"], c2["seed"], density="mixed")
+    alone_a = gpu_infer(idx, val, bias, Ya)
+    alone_a_small = gpu_infer(idx, val, bias, Ya[:33])
+    alone_b = gpu_infer(idx2, val2, bias2, Yb)
+    side = torch.cuda.Stream()
+    ma = sp.Model(idx, val, bias, stream=side)
+    mb = sp.Model(idx2, val2, bias2)
+    ya = torch.from_numpy(Ya).to("cuda:0")
+    yb = torch.from_numpy(Yb).to("cuda:0")
+    torch.cuda.synchronize()   # the inputs were produced on torch's stream, ma runs on its own
+    for _ in range(2):
+        for y, m, ref in ((ya, ma, alone_a), (yb, mb, alone_b), (ya[:33].contiguous(), ma, alone_a_small)):
+            torch.cuda.synchronize()
+            n, rows, Y = m.infer(y)
+            assert n == ref[0] and np.array_equal(rows.cpu().numpy(), ref[1]) and np.array_equal(Y.cpu().numpy(), ref[2])
+    ma.close()
+    mb.close()
+
+
 def _uniform_model(rng, N, L, window, w=0.0625):
     """Every neuron: 32 distinct columns inside the 'window'-wide span its 'window'-aligned group of
     neurons shares; one weight for all connections."""
