@@ -51,3 +51,42 @@ def test_full_batch_sampled_rows(cfg, layers, sample):
     if layers == 1:
         assert n == batch and common == sample
     m.close()
+
+
+@pytest.mark.parametrize("cfg,layers,kmin,kmax,density,sample", [(4, 1, 16, 64, None, 10), (2, 4, 8, 72, "mixed", 40)])
+def test_full_batch_general_layers_sampled_rows(cfg, layers, kmin, kmax, density, sample):
+    """The general-layer variant the benchmark can time (bench.py --general): 60 000 rows, neurons of
+    kmin..kmax connections, several passes per layer; sampled rows against the oracle's general form."""
+    import torch
+    import paper_2007_14152_amd as sp
+    dev = "cuda:0"
+    c = synth.config(cfg)
+    N, batch = c["N"], c["batch"]
+    dens = density or synth.DENSITY
+    print("general cfg", cfg, "layers", layers, "N", N, "batch", batch, flush=True)
+    gen = [synth.gen_layer_general(N, l, c["seed"], kmin, kmax, c["window"]) for l in range(layers)]
+    ptr, idx, val = [g[0] for g in gen], [g[1] for g in gen], [g[2] for g in gen]
+    bias = synth.gen_bias(N, c["bias"])
+    m = sp.Model.from_csr(ptr, idx, val, bias, device=dev)
+    assert max(m.layer_passes(l) for l in range(layers)) > 1
+    y0 = synth.gen_y0(batch, N, c["seed"], density=dens, device=dev)
+    n, rows, Y = m.infer(y0)
+    del y0
+    rows_h = rows.cpu().numpy()
+    assert n == rows_h.shape[0] and np.all(np.diff(rows_h) > 0)
+    if n:
+        assert float(Y.min()) >= 0.0 and float(Y.max()) <= 32.0
+    rng = np.random.default_rng(300 + cfg)
+    ids = np.sort(rng.choice(batch, sample, replace=False))
+    ids[0], ids[-1] = 0, batch - 1
+    ref = oracle.infer(idx, val, bias, synth.gen_y0(batch, N, c["seed"], density=dens, rows=ids), ptr=ptr)
+    pos = np.searchsorted(rows_h, ids)
+    pos_c = np.minimum(pos, max(n - 1, 0))
+    present = (rows_h[pos_c] == ids) if n else np.zeros(len(ids), bool)
+    sub_rows = ids[present]
+    sub_Y = Y[torch.from_numpy(pos_c[present]).to(dev)].cpu().numpy() if present.any() else np.zeros((0, N), np.float32)
+    common, _ = check_against_oracle(ref, len(sub_rows), sub_rows, sub_Y, row_ids=ids,
+                                     what="general cfg%d L=%d sampled" % (cfg, layers))
+    if density == "mixed":
+        assert 0 < common < sample
+    m.close()
