@@ -123,6 +123,27 @@ int spdnn_create_csr(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* p
                      const int32_t* const* idx, const float* const* val, const float* bias,
                      void* weights_arena, size_t weights_arena_bytes, void* hip_stream);
 
+/* Out-of-core weights (Section III-B-1): the re-laid weights of all layers live in host memory;
+ * the device keeps the bias, two layer-sized buffers and the set-up staging area.  While layer l
+ * runs from one buffer, a second HIP stream (made by the library, default priority) copies layer
+ * l+1 into the other; a buffer is refilled as soon as the kernels that read it are done.
+ *
+ * spdnn_ooc_bytes: sizes of the two arenas for a model whose widest column window is
+ * widest_window (as spdnn_scan_windows reports; N is always enough).
+ * spdnn_create_ooc: as spdnn_create, with
+ *   device_arena : device memory, 256-byte aligned, >= *device_bytes;
+ *   host_arena   : host memory, 16-byte aligned, >= *host_bytes, written during the call and read
+ *                  by every spdnn_infer; pinned memory (hipHostMalloc) lets the copies overlap the
+ *                  kernels, pageable memory works but serialises them.
+ * Both stay the caller's and must outlive the handle.  spdnn_infer is called as usual and gives
+ * bit-identical results; it returns with the copy stream idle. */
+int spdnn_ooc_bytes(int32_t N, int32_t L, int32_t widest_window, size_t* device_bytes,
+                    size_t* host_bytes);
+int spdnn_create_ooc(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx,
+                     const float* const* val, const float* bias, int32_t where,
+                     void* device_arena, size_t device_arena_bytes, void* host_arena,
+                     size_t host_arena_bytes, void* hip_stream);
+
 /* Run all L layers on `batch` feature rows.
  *   Y0_dev : device, batch x N floats, row-major (row r = input r), 16-byte aligned, finite
  *            values; not modified.

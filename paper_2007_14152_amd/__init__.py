@@ -31,7 +31,7 @@ SPDNN_KERNEL_WIDE_PAIR4 = 5
 EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
            "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_copy_probe",
            "spdnn_weights_bytes_for_window", "spdnn_scan_windows", "spdnn_layer_kernel",
-           "spdnn_csr_passes", "spdnn_create_csr", "spdnn_layer_passes")
+           "spdnn_csr_passes", "spdnn_create_csr", "spdnn_layer_passes", "spdnn_ooc_bytes", "spdnn_create_ooc")
 KERNEL_NAMES = {0: "fused_layer_kernel<false>", 1: "fused_layer_kernel<true>", 2: "fused_wide_kernel",
                 3: "fused_pair_kernel", 4: "fused_wide_pair_kernel", 5: "fused_wide_pair4_kernel"}
 
@@ -66,6 +66,9 @@ def lib():
         L.spdnn_scan_windows.argtypes = [i32, i32, ctypes.POINTER(vp), i32, vp, sz, vp, ctypes.POINTER(i32)]
         L.spdnn_layer_kernel.argtypes = [vp, i32, ctypes.POINTER(i32)]
         L.spdnn_layer_passes.argtypes = [vp, i32, ctypes.POINTER(i32)]
+        L.spdnn_ooc_bytes.argtypes = [i32, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.spdnn_create_ooc.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+                                       i32, vp, sz, vp, sz, vp]
         L.spdnn_csr_passes.argtypes = [i32, i32, ctypes.POINTER(vp), vp, sz, vp, vp, ctypes.POINTER(i32)]
         L.spdnn_create_csr.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                        ctypes.POINTER(vp), vp, vp, sz, vp]
@@ -119,6 +122,24 @@ def spdnn_create(N, L, idx_ptrs, val_ptrs, bias_ptr, where, arena_ptr, arena_byt
     h = ctypes.c_void_p(0)
     _check(lib().spdnn_create(ctypes.byref(h), N, L, ip, vp, ctypes.c_void_p(int(bias_ptr)), where,
                               ctypes.c_void_p(int(arena_ptr)), arena_bytes, ctypes.c_void_p(int(stream))))
+    return h.value
+
+
+def spdnn_ooc_bytes(N: int, L: int, widest_window: int):
+    """Returns (device_bytes, host_bytes) of the out-of-core arenas."""
+    d, h = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().spdnn_ooc_bytes(N, L, widest_window, ctypes.byref(d), ctypes.byref(h)))
+    return d.value, h.value
+
+
+def spdnn_create_ooc(N, L, idx_ptrs, val_ptrs, bias_ptr, where, dev_ptr, dev_bytes, host_ptr, host_bytes, stream=0):
+    """Out-of-core weights: as spdnn_create, with a small device arena and a host arena."""
+    ip = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in idx_ptrs])
+    vp = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in val_ptrs])
+    h = ctypes.c_void_p(0)
+    _check(lib().spdnn_create_ooc(ctypes.byref(h), N, L, ip, vp, ctypes.c_void_p(int(bias_ptr)), where,
+                                  ctypes.c_void_p(int(dev_ptr)), dev_bytes, ctypes.c_void_p(int(host_ptr)), host_bytes,
+                                  ctypes.c_void_p(int(stream))))
     return h.value
 
 
@@ -199,7 +220,7 @@ class Model:
     (copied through the host path) or CUDA torch tensors (device path); bias: [N].
     """
 
-    def __init__(self, idx, val, bias, device="cuda:0", stream=None, window_hint=None, ptr=None):
+    def __init__(self, idx, val, bias, device="cuda:0", stream=None, window_hint=None, ptr=None, out_of_core=False):
         import numpy as np
         import torch
         self.torch = torch
@@ -239,9 +260,16 @@ class Model:
             self.widest_window = spdnn_scan_windows(N, L, ip, where, scratch.data_ptr(), scratch.numel(),
                                                     s.cuda_stream)
             del scratch
-            nbytes = spdnn_weights_bytes_for_window(N, L, window_hint or self.widest_window)
-            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-            self.h = spdnn_create(N, L, ip, vp, bp, where, self.arena.data_ptr(), nbytes, s.cuda_stream)
+            if out_of_core:   # weights in pinned host memory, two layer buffers on the device
+                dbytes, hbytes = spdnn_ooc_bytes(N, L, window_hint or self.widest_window)
+                self.arena = torch.empty(dbytes, dtype=torch.uint8, device=self.device)
+                self.host_arena = torch.empty(hbytes, dtype=torch.uint8, pin_memory=True)
+                self.h = spdnn_create_ooc(N, L, ip, vp, bp, where, self.arena.data_ptr(), dbytes,
+                                          self.host_arena.data_ptr(), hbytes, s.cuda_stream)
+            else:
+                nbytes = spdnn_weights_bytes_for_window(N, L, window_hint or self.widest_window)
+                self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+                self.h = spdnn_create(N, L, ip, vp, bp, where, self.arena.data_ptr(), nbytes, s.cuda_stream)
         self.work = None
         del keep
 

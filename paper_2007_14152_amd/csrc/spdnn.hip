@@ -69,6 +69,13 @@ struct spdnn_model {
     std::vector<int32_t> first_pass;   // L+1 entries: layer l is passes first_pass[l] .. first_pass[l+1]-1
     int* host_counts = nullptr;  // pinned, L+1 entries: rows active on entry to layer l
     hipEvent_t lag_ev[kLag] = {nullptr, nullptr};
+    // out-of-core weights: pass p's block lives in host memory and is copied into device slot p & 1
+    const char* ooc_host = nullptr;
+    char* ooc_slot[2] = {nullptr, nullptr};
+    size_t ooc_block = 0;
+    hipStream_t ooc_stream = nullptr;
+    hipEvent_t ooc_ready[2] = {nullptr, nullptr};  // the copy into the slot has landed
+    hipEvent_t ooc_freed[2] = {nullptr, nullptr};  // the kernels that read the slot are done
     // profiling
     int profiling = 0;
     std::vector<hipEvent_t> t0, t1;
@@ -112,10 +119,16 @@ size_t staging_bytes(int32_t N, int32_t L) {
            up(sizeof(int) * (size_t)nblk) +                     // general layers: smallest column of every block
            up(sizeof(int) * (size_t)(5 * L + 1));  // error flag; per layer: wide failure, widest window, weights differ, pair info[2]
 }
-size_t arena_bytes_for(int32_t N, int32_t L, int nstage_cap) {
+size_t block_bytes(int32_t N, int nstage_cap) {  // one pass's re-laid weights
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
-    return up((size_t)N * sizeof(float)) + (size_t)L * (layer_bytes(nblk) + wide_bytes(nblk, nstage_cap)) +
-           staging_bytes(N, L);
+    return layer_bytes(nblk) + wide_bytes(nblk, nstage_cap);
+}
+size_t arena_bytes_for(int32_t N, int32_t L, int nstage_cap) {
+    return up((size_t)N * sizeof(float)) + (size_t)L * block_bytes(N, nstage_cap) + staging_bytes(N, L);
+}
+// out-of-core: the device holds the bias, two blocks and the staging area; the host holds all blocks
+size_t ooc_device_bytes_for(int32_t N, int32_t L, int nstage_cap) {
+    return up((size_t)N * sizeof(float)) + 2 * block_bytes(N, nstage_cap) + staging_bytes(N, L);
 }
 
 struct WorkView {
@@ -183,7 +196,9 @@ int scan_csr(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev,
 // (device arrays; layer l is cut into passes_of[l] passes of 32 connections per neuron).
 int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& passes_of, const int32_t* const* ptr,
                 const int32_t* const* idx, const float* const* val, const float* bias, int32_t where,
-                void* weights_arena, size_t weights_arena_bytes, hipStream_t stream) {
+                void* weights_arena, size_t weights_arena_bytes, hipStream_t stream, void* host_arena = nullptr,
+                size_t host_arena_bytes = 0) {
+    const bool ooc = host_arena != nullptr;
     int32_t P = 0;  // passes = layers as the kernels see them
     std::vector<int32_t> layer_of, round_of, first_pass((size_t)L + 1, 0);
     for (int32_t l = 0; l < L; ++l) {
@@ -197,13 +212,21 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     first_pass[L] = P;
     // The arena decides how many stages the wide format may use (0 = none: layers with
     // wide windows then run the staged kernel, which is slower but needs no extra room).
+    auto fits = [&](int cap) {
+        return ooc ? ooc_device_bytes_for(N, P, cap) <= weights_arena_bytes &&
+                         (size_t)P * block_bytes(N, cap) <= host_arena_bytes
+                   : arena_bytes_for(N, P, cap) <= weights_arena_bytes;
+    };
     int nstage_cap = stages_of(N);
-    while (nstage_cap > 1 && arena_bytes_for(N, P, nstage_cap) > weights_arena_bytes) --nstage_cap;
+    while (nstage_cap > 1 && !fits(nstage_cap)) --nstage_cap;
     if (nstage_cap < 2) nstage_cap = 0;
-    {
-        const size_t need = arena_bytes_for(N, P, nstage_cap);
-        if (weights_arena_bytes < need)
-            return fail(SPDNN_ESIZE, "weights arena has %zu bytes, at least %zu needed", weights_arena_bytes, need);
+    if (!fits(nstage_cap)) {
+        if (ooc)
+            return fail(SPDNN_ESIZE, "out-of-core arenas have %zu (device) and %zu (host) bytes, at least %zu and %zu needed",
+                        weights_arena_bytes, host_arena_bytes, ooc_device_bytes_for(N, P, 0),
+                        (size_t)P * block_bytes(N, 0));
+        return fail(SPDNN_ESIZE, "weights arena has %zu bytes, at least %zu needed", weights_arena_bytes,
+                    arena_bytes_for(N, P, 0));
     }
 
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
@@ -280,7 +303,21 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
     std::vector<int2*> win_dev(P);
     m->layers.resize(P);
+    const size_t blk_bytes = block_bytes(N, nstage_cap);
+    if (ooc) {  // two device slots; pass p is built in slot p & 1 and runs from there
+        m->ooc_host = static_cast<const char*>(host_arena);
+        m->ooc_block = blk_bytes;
+        m->ooc_slot[0] = base + o;
+        m->ooc_slot[1] = base + o + blk_bytes;
+        HIP_TRY(hipStreamCreateWithFlags(&m->ooc_stream, hipStreamNonBlocking));
+        for (int i = 0; i < 2; ++i) {
+            HIP_TRY(hipEventCreateWithFlags(&m->ooc_ready[i], hipEventDisableTiming));
+            HIP_TRY(hipEventCreateWithFlags(&m->ooc_freed[i], hipEventDisableTiming));
+        }
+    }
+    const size_t blocks_at = o;
     for (int32_t l = 0; l < P; ++l) {
+        o = blocks_at + (size_t)(ooc ? (l & 1) : l) * blk_bytes;
         int2* win = reinterpret_cast<int2*>(base + o);
         o += up((size_t)nblk * sizeof(int2));
         uint16_t* rel = reinterpret_cast<uint16_t*>(base + o);
@@ -315,6 +352,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         }
         m->layers[l].ww = ww;
     }
+    o = blocks_at + (size_t)(ooc ? 2 : P) * blk_bytes;
     int32_t* st_idx = reinterpret_cast<int32_t*>(base + o);
     o += up((size_t)N * spdnn::kNnz * sizeof(int32_t));
     float* st_val = reinterpret_cast<float*>(base + o);
@@ -404,6 +442,9 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
                 d.pair4 = nst <= 4;
             }
         }
+        if (ooc)  // the finished block goes to the host; its slot is rebuilt two passes later, after this copy
+            HIP_TRY(hipMemcpyAsync(static_cast<char*>(host_arena) + (size_t)l * blk_bytes, m->ooc_slot[l & 1], blk_bytes,
+                                   hipMemcpyDeviceToHost, stream));
         if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
     }
     // error flag and the layers whose patterns did not fit the wide format
@@ -524,6 +565,32 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, 
                        weights_arena_bytes, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
+int spdnn_ooc_bytes(int32_t N, int32_t L, int32_t widest_window, size_t* device_bytes, size_t* host_bytes) {
+    if (!device_bytes || !host_bytes) return fail(SPDNN_EINVAL, "null argument");
+    if (!valid_n(N) || L < 1 || widest_window < 1)
+        return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1, widest_window >= 1");
+    const int cap = stages_of(std::min(widest_window, N));
+    *device_bytes = ooc_device_bytes_for(N, L, cap);
+    *host_bytes = (size_t)L * block_bytes(N, cap);
+    return SPDNN_OK;
+}
+
+int spdnn_create_ooc(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, const float* const* val,
+                     const float* bias, int32_t where, void* device_arena, size_t device_arena_bytes,
+                     void* host_arena, size_t host_arena_bytes, void* hip_stream) {
+    if (!out) return fail(SPDNN_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+    if (!idx || !val || !bias || !device_arena || !host_arena) return fail(SPDNN_EINVAL, "null argument");
+    if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
+    if (reinterpret_cast<uintptr_t>(device_arena) % kAlign || reinterpret_cast<uintptr_t>(host_arena) % 16)
+        return fail(SPDNN_EINVAL, "device_arena must be 256-byte aligned, host_arena 16-byte aligned");
+    for (int32_t l = 0; l < L; ++l)
+        if (!idx[l] || !val[l]) return fail(SPDNN_EINVAL, "idx[%d] or val[%d] is NULL", l, l);
+    return create_impl(out, N, L, std::vector<int32_t>((size_t)L, 1), nullptr, idx, val, bias, where, device_arena,
+                       device_arena_bytes, reinterpret_cast<hipStream_t>(hip_stream), host_arena, host_arena_bytes);
+}
+
 int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev, size_t scratch_bytes,
                      void* hip_stream, int32_t* passes, int32_t* total) {
     if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
@@ -564,6 +631,11 @@ int spdnn_destroy(spdnn_t h) {
     if (h->host_counts) (void)hipHostFree(h->host_counts);
     for (int i = 0; i < kLag; ++i)
         if (h->lag_ev[i]) (void)hipEventDestroy(h->lag_ev[i]);
+    for (int i = 0; i < 2; ++i) {
+        if (h->ooc_ready[i]) (void)hipEventDestroy(h->ooc_ready[i]);
+        if (h->ooc_freed[i]) (void)hipEventDestroy(h->ooc_freed[i]);
+    }
+    if (h->ooc_stream) (void)hipStreamDestroy(h->ooc_stream);
     for (hipEvent_t e : h->t0) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->t1) (void)hipEventDestroy(e);
     delete h;
@@ -638,6 +710,24 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
     h->host_counts[0] = batch;
     int32_t bound = batch;  // upper bound of the rows active at the layer being launched
     int32_t run = 0;        // layers launched
+    // Out-of-core weights (Section III-B-1): pass p runs from device slot p & 1.  The copy stream fills
+    // the two slots, and refills a slot with pass p + 2 as soon as the kernels of pass p are done with
+    // it, so the transfer of the next layer runs under the current layer's kernel.
+    const int32_t P = (int32_t)h->layers.size();
+    auto ooc_fetch = [&](int32_t p) -> hipError_t {
+        hipError_t e = hipMemcpyAsync(h->ooc_slot[p & 1], h->ooc_host + (size_t)p * h->ooc_block, h->ooc_block,
+                                      hipMemcpyHostToDevice, h->ooc_stream);
+        return e != hipSuccess ? e : hipEventRecord(h->ooc_ready[p & 1], h->ooc_stream);
+    };
+    // whatever happens below, the copy stream is idle again when the call returns
+    struct Drain {
+        hipStream_t cs;
+        ~Drain() {
+            if (cs) (void)hipStreamSynchronize(cs);
+        }
+    } drain{h->ooc_stream};
+    if (h->ooc_host)
+        for (int32_t p = 0; p < std::min(P, 2); ++p) HIP_TRY(ooc_fetch(p));
     for (int32_t l = 0; l < L; ++l) {
         const float* Yin = (l == 0) ? Y0_dev : wv.Y[(l - 1) & 1];
         float* Yout = wv.Y[l & 1];
@@ -645,6 +735,7 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         // one launch per pass: a layer is a single pass unless some neuron has more than 32 connections
         for (int32_t p = h->first_pass[l]; p < h->first_pass[l + 1]; ++p) {
             const LayerDesc& d = h->layers[p];
+            if (h->ooc_host) HIP_TRY(hipStreamWaitEvent(s, h->ooc_ready[p & 1], 0));
             // launch shape: one workgroup per CU; the rows are cut into Q chunks per output block
             const int32_t ngroups = (bound + spdnn::kRows - 1) / spdnn::kRows;
             // kPair: the workgroups' column blocks are pairs of output blocks
@@ -695,6 +786,13 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
             else
                 spdnn::fused_layer_kernel<false><<<grid, spdnn::kBlk, lds, s>>>(
                     Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
+            if (h->ooc_host) {  // the slot is free once this kernel is done: refill it with pass p + 2
+                HIP_TRY(hipEventRecord(h->ooc_freed[p & 1], s));
+                if (p + 2 < P) {
+                    HIP_TRY(hipStreamWaitEvent(h->ooc_stream, h->ooc_freed[p & 1], 0));
+                    HIP_TRY(ooc_fetch(p + 2));
+                }
+            }
         }
         if (h->profiling) HIP_TRY(hipEventRecord(h->t1[l], s));
         spdnn::compact_kernel<<<1, 1024, 0, s>>>(wv.flags, wv.count, wv.gid[l & 1], wv.gid[(l + 1) & 1],

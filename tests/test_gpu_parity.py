@@ -397,3 +397,57 @@ def test_layers_with_fewer_stages_than_the_widest():
     m.close()
     common, _ = check_against_oracle(ref, n, rows, Y, what="10 + 8 stages")
     assert common > 0
+
+
+@pytest.mark.parametrize("cfg,layers,batch,density", [
+    (0, 1, 200, "mixed"),      # a single layer: one buffer in use
+    (0, 2, 200, "mixed"),
+    (0, 12, 900, "mixed"),     # every layer runs; buffers are refilled five times each
+    (0, 12, 300, None),        # the rows die after a few layers: copies still in flight when the loop stops
+    (2, 5, 120, "mixed"),      # two neurons per lane
+    (3, 3, 40, "mixed"),       # wide format (more arrays per layer block)
+])
+def test_out_of_core_weights_match_resident_weights(cfg, layers, batch, density):
+    """Weights streamed from pinned host memory through two device buffers (Section III-B-1):
+    same bits as with all weights resident, on repeated calls and against the oracle."""
+    import torch
+    import paper_2007_14152_amd as sp
+    c, idx, val, bias = config_model(cfg, layers)
+    Y0 = synth.gen_y0(batch, c["N"], c["seed"], density=density or synth.DENSITY)
+    res = sp.Model(idx, val, bias)
+    ooc = sp.Model(idx, val, bias, out_of_core=True)
+    assert ooc.arena.numel() < res.arena.numel() or layers <= 2
+    assert [ooc.layer_kernel(l) for l in range(layers)] == [res.layer_kernel(l) for l in range(layers)]
+    y0 = torch.from_numpy(Y0).to("cuda:0")
+    want = res.infer(y0)
+    for rep in range(3):
+        y = y0 if rep != 1 else y0[:batch // 2].contiguous()
+        w = want if rep != 1 else res.infer(y)
+        n, rows, Y = ooc.infer(y)
+        assert n == w[0] and torch.equal(rows, w[1]) and torch.equal(Y, w[2]), "call %d" % rep
+    ref = oracle.infer(idx, val, bias, Y0)
+    check_against_oracle(ref, want[0], want[1].cpu().numpy(), want[2].cpu().numpy(), what="out of core cfg%d" % cfg)
+    res.close()
+    ooc.close()
+
+
+def test_out_of_core_sizes_and_errors():
+    import torch
+    import paper_2007_14152_amd as sp
+    c, idx, val, bias = config_model(0, 4)
+    N = c["N"]
+    dbytes, hbytes = sp.spdnn_ooc_bytes(N, 4, N)
+    assert hbytes == 4 * (hbytes // 4) and dbytes < sp.spdnn_weights_bytes_for_window(N, 400, N)
+    d400, h400 = sp.spdnn_ooc_bytes(N, 400, N)
+    assert h400 == 100 * hbytes and d400 - dbytes < 400 * 64   # the device side grows by a few counters per layer only
+    dev = torch.empty(dbytes, dtype=torch.uint8, device="cuda:0")
+    host = torch.empty(hbytes, dtype=torch.uint8, pin_memory=True)
+    ip = [a.ctypes.data for a in idx]
+    vp = [a.ctypes.data for a in val]
+    for db, hb in ((dbytes - 1, hbytes), (dbytes, hbytes - 1)):
+        with pytest.raises(sp.SpdnnError) as e:
+            sp.spdnn_create_ooc(N, 4, ip, vp, bias.ctypes.data, sp.SPDNN_HOST, dev.data_ptr(), db, host.data_ptr(), hb)
+        assert e.value.code == sp.SPDNN_ESIZE
+    with pytest.raises(sp.SpdnnError) as e:
+        sp.spdnn_create_ooc(N, 4, ip, vp, bias.ctypes.data, sp.SPDNN_HOST, dev.data_ptr(), dbytes, 0, hbytes)
+    assert e.value.code == sp.SPDNN_EINVAL
