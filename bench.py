@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--general", default=None, metavar="KMIN,KMAX",
                     help="general-layer variant (ours): neurons with KMIN..KMAX connections and varying weights, "
                          "through spdnn_create_csr; needs --layers (default 6)")
+    ap.add_argument("--out-of-core", action="store_true",
+                    help="weights in pinned host memory, streamed through two device buffers (ours: the target keeps them resident)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
@@ -118,7 +120,8 @@ def main():
             didx[l] = synth.gen_layer(N, l, c["seed"], c["window"], device=dev)
         dval = torch.full((L, N, 32), synth.WEIGHT, dtype=torch.float32, device=dev)
         dbias = synth.gen_bias(N, c["bias"], device=dev)
-        model = sp.Model([didx[l] for l in range(L)], [dval[l] for l in range(L)], dbias, device=dev)
+        model = sp.Model([didx[l] for l in range(L)], [dval[l] for l in range(L)], dbias, device=dev,
+                         out_of_core=a.out_of_core)
     y0 = synth.gen_y0(batch, N, c["seed"], density=density, device=dev)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
@@ -170,7 +173,9 @@ def main():
         "config": {"workload": "cfg%d: N=%d L=%d batch=%d bias=%g window=%s density=%s" % (
             a.config, N, L, batch, c["bias"], c["window"], density) + (
                 " general layers %s connections per neuron, passes %s" % (
-                    a.general, [model.layer_passes(l) for l in range(L)]) if a.general else ""),
+                    a.general, [model.layer_passes(l) for l in range(L)]) if a.general else "") + (
+                " weights out of core (%.1f MB on the device, %.1f MB in pinned host memory)" % (
+                    model.arena.numel() / 1e6, model.host_arena.numel() / 1e6) if a.out_of_core else ""),
             "layers_launched": int(launches // a.steps), "rows_in_per_layer": [int(r) for r in rows_trace[:8]],
             "n_active_final": int(n_active), "executed_TeraEdges_per_s": executed * a.steps / dt / 1e12,
             "setup_s": t_setup},
