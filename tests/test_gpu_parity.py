@@ -451,3 +451,18 @@ def test_out_of_core_sizes_and_errors():
     with pytest.raises(sp.SpdnnError) as e:
         sp.spdnn_create_ooc(N, 4, ip, vp, bias.ctypes.data, sp.SPDNN_HOST, dev.data_ptr(), dbytes, 0, hbytes)
     assert e.value.code == sp.SPDNN_EINVAL
+
+
+def test_batch_larger_than_one_compaction_chunk():
+    """The compaction handles 65536 rows per chunk: batches beyond one and two chunks, with
+    survivors and dropped rows in every chunk."""
+    rng = np.random.default_rng(77)
+    N, L, batch = 64, 4, 140001
+    idx, val, bias = rand_model(rng, N, L, True, True, lo=0.0, hi=0.12)
+    Y0 = (rng.uniform(size=(batch, N)) < rng.uniform(0.0, 0.5, size=(batch, 1))).astype(np.float32)
+    ref = oracle.infer(idx, val, bias, Y0)
+    assert 1000 < ref.n_active < batch - 1000
+    assert (ref.active_rows < 65536).any() and (ref.active_rows >= 131072).any()
+    n, rows, Y = gpu_infer(idx, val, bias, Y0)
+    common, _ = check_against_oracle(ref, n, rows, Y, what="three compaction chunks")
+    assert common > 1000
