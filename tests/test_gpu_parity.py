@@ -466,3 +466,27 @@ def test_batch_larger_than_one_compaction_chunk():
     n, rows, Y = gpu_infer(idx, val, bias, Y0)
     common, _ = check_against_oracle(ref, n, rows, Y, what="three compaction chunks")
     assert common > 1000
+
+
+@pytest.mark.parametrize("uniform", [True, False])
+def test_largest_n_with_columns_anywhere(uniform):
+    """N = 65536 (the largest the 16-bit column offsets allow) with columns drawn from the whole
+    row: 16 LDS stages per output block."""
+    import paper_2007_14152_amd as sp
+    N, L, batch = 65536, 2, 9
+    rng = np.random.default_rng(65536 + uniform)
+    idx = [synth.gen_layer(N, l, 4242) for l in range(L)]
+    val = [np.full((N, 32), 0.0625, np.float32) if uniform else rng.uniform(0.0, 0.12, size=(N, 32)).astype(np.float32)
+           for _ in range(L)]
+    bias = np.full(N, -0.3, dtype=np.float32)
+    Y0 = (rng.uniform(size=(batch, N)) < np.linspace(0.1, 0.6, batch)[:, None]).astype(np.float32)
+    ref = oracle.infer(idx, val, bias, Y0)
+    assert 0 < ref.n_active
+    m = sp.Model(idx, val, bias)
+    assert m.widest_window == N
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    kinds = [m.layer_kernel(l) for l in range(L)]
+    m.close()
+    assert kinds == [sp.SPDNN_KERNEL_WIDE] * L
+    common, _ = check_against_oracle(ref, n, rows, Y, what="N=65536 anywhere uniform=%s" % uniform)
+    assert common > 0
