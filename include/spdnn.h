@@ -105,13 +105,17 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx,
  * accumulate in the output buffer and the last one applies bias and ReLU.
  *
  * spdnn_csr_passes: passes[l] (host, may be NULL) = passes of layer l, *total = their sum,
- * which is the "L" to size the weights arena with (spdnn_weights_bytes(N, *total, ...)).
+ * which is the "L" to size the weights arena with (spdnn_weights_bytes(N, *total, ...)); if
+ * widest_window is not NULL, also the widest column window of any 1024-neuron block (as
+ * spdnn_scan_windows reports it) for spdnn_weights_bytes_for_window(N, *total, *widest_window).
  *   ptr        : host array of L pointers to device arrays of N+1 int32, ptr[l][0] >= 0,
  *                non-decreasing.
- *   scratch_dev: device memory, 8-byte aligned, >= 8*L bytes, contents scratch.
+ *   idx        : as for spdnn_create_csr; may be NULL if widest_window is NULL.
+ *   scratch_dev: device memory, 8-byte aligned, >= 8*L + 8*ceil(N/1024) bytes, contents scratch.
  * Blocks until done.  SPDNN_EINVAL if a ptr array decreases or is negative. */
-int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev,
-                     size_t scratch_bytes, void* hip_stream, int32_t* passes, int32_t* total);
+int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx,
+                     void* scratch_dev, size_t scratch_bytes, void* hip_stream, int32_t* passes,
+                     int32_t* total, int32_t* widest_window);
 
 /* Build a model of L general layers.  ptr, idx, val: host arrays of L pointers to DEVICE
  * arrays (ptr[l]: N+1 int32 as above; idx[l], val[l]: at least ptr[l][N] entries, columns in

@@ -69,7 +69,8 @@ def lib():
         L.spdnn_ooc_bytes.argtypes = [i32, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.spdnn_create_ooc.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
                                        i32, vp, sz, vp, sz, vp]
-        L.spdnn_csr_passes.argtypes = [i32, i32, ctypes.POINTER(vp), vp, sz, vp, vp, ctypes.POINTER(i32)]
+        L.spdnn_csr_passes.argtypes = [i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, sz, vp, vp,
+                                       ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.spdnn_create_csr.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                        ctypes.POINTER(vp), vp, vp, sz, vp]
         for n in EXPORTS:
@@ -143,14 +144,20 @@ def spdnn_create_ooc(N, L, idx_ptrs, val_ptrs, bias_ptr, where, dev_ptr, dev_byt
     return h.value
 
 
-def spdnn_csr_passes(N, L, ptr_ptrs, scratch_ptr, scratch_bytes, stream=0):
-    """ptr_ptrs: L device addresses of int32[N+1].  Returns (passes per layer, their sum)."""
+def spdnn_csr_passes(N, L, ptr_ptrs, scratch_ptr, scratch_bytes, stream=0, idx_ptrs=None):
+    """ptr_ptrs (idx_ptrs): L device addresses of int32[N+1] (of the column arrays).  Returns
+    (passes per layer, their sum), and with idx_ptrs also the widest column window."""
     import numpy as np
     pp = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in ptr_ptrs])
+    ip = (ctypes.c_void_p * max(L, 1))(*[int(p) for p in idx_ptrs]) if idx_ptrs is not None else None
     passes = np.zeros(max(L, 1), dtype=np.int32)
     total = ctypes.c_int32(0)
-    _check(lib().spdnn_csr_passes(N, L, pp, ctypes.c_void_p(int(scratch_ptr)), scratch_bytes,
-                                  ctypes.c_void_p(int(stream)), passes.ctypes.data, ctypes.byref(total)))
+    widest = ctypes.c_int32(0)
+    _check(lib().spdnn_csr_passes(N, L, pp, ip, ctypes.c_void_p(int(scratch_ptr)), scratch_bytes,
+                                  ctypes.c_void_p(int(stream)), passes.ctypes.data, ctypes.byref(total),
+                                  ctypes.byref(widest) if idx_ptrs is not None else None))
+    if idx_ptrs is not None:
+        return passes[:L], total.value, widest.value
     return passes[:L], total.value
 
 
@@ -297,12 +304,13 @@ class Model:
         with torch.cuda.device(dev):
             s = stream if stream is not None else torch.cuda.current_stream(dev)
             self.stream = s
-            scratch = torch.empty(8 * L + 256, dtype=torch.uint8, device=dev)
-            self.passes, total = spdnn_csr_passes(N, L, [q.data_ptr() for q in ptr], scratch.data_ptr(),
-                                                  scratch.numel(), s.cuda_stream)
+            scratch = torch.empty(8 * L + 8 * ((N + 1023) // 1024) + 256, dtype=torch.uint8, device=dev)
+            self.passes, total, self.widest_window = spdnn_csr_passes(
+                N, L, [q.data_ptr() for q in ptr], scratch.data_ptr(), scratch.numel(), s.cuda_stream,
+                idx_ptrs=[a.data_ptr() for a in idx])
             del scratch
-            self.widest_window = None
-            nbytes = spdnn_weights_bytes(N, total)
+            # size the arena for the patterns' widest column window instead of the worst case
+            nbytes = spdnn_weights_bytes_for_window(N, total, self.widest_window)
             self.arena = torch.empty(nbytes, dtype=torch.uint8, device=dev)
             self.h = spdnn_create_csr(N, L, [q.data_ptr() for q in ptr], [a.data_ptr() for a in idx],
                                       [v.data_ptr() for v in val], b.data_ptr(), self.arena.data_ptr(), nbytes,

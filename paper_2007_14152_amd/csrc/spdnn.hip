@@ -168,13 +168,18 @@ hipError_t allow_big_lds() {
 }
 
 
-// Longest neuron of every layer of a general model -> passes of 32 connections.  scratch: device, 8*L bytes.
+// Longest neuron of every layer of a general model -> passes of 32 connections; with idx also the
+// widest column window of any 1024-neuron block (of any aligned pair of blocks when N is a multiple
+// of 2048, as spdnn_scan_windows counts).  scratch: device, 8*L + 8*ceil(N/1024) bytes.
 int scan_csr(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev, size_t scratch_bytes,
-             hipStream_t stream, std::vector<int32_t>* passes_of) {
-    if (scratch_bytes < sizeof(int) * 2 * (size_t)L)
-        return fail(SPDNN_ESIZE, "scratch has %zu bytes, %zu needed", scratch_bytes, sizeof(int) * 2 * (size_t)L);
+             hipStream_t stream, std::vector<int32_t>* passes_of, const int32_t* const* idx = nullptr,
+             int32_t* widest_window = nullptr) {
+    const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
+    const size_t need = sizeof(int) * 2 * (size_t)L + sizeof(int2) * (size_t)nblk;
+    if (scratch_bytes < need) return fail(SPDNN_ESIZE, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
     if (reinterpret_cast<uintptr_t>(scratch_dev) % 8) return fail(SPDNN_EINVAL, "scratch must be 8-byte aligned");
     int* out = static_cast<int*>(scratch_dev);
+    int2* win = reinterpret_cast<int2*>(out + 2 * (size_t)L);
     HIP_TRY(hipMemsetAsync(out, 0, sizeof(int) * 2 * (size_t)L, stream));
     for (int32_t l = 0; l < L; ++l) {
         if (!ptr[l]) return fail(SPDNN_EINVAL, "ptr[%d] is NULL", l);
@@ -188,6 +193,29 @@ int scan_csr(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev,
     for (int32_t l = 0; l < L; ++l) {
         if (h[2 * l + 1]) return fail(SPDNN_EINVAL, "ptr[%d] is negative somewhere or decreases", l);
         (*passes_of)[l] = std::max(1, (h[2 * l] + spdnn::kNnz - 1) / spdnn::kNnz);
+    }
+    if (idx && widest_window) {  // after the ptr arrays are known to be sound
+        std::vector<int2> hw(nblk);
+        int widest = 4;
+        for (int32_t l = 0; l < L; ++l) {
+            if (!idx[l]) return fail(SPDNN_EINVAL, "idx[%d] is NULL", l);
+            spdnn::csr_block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(ptr[l], idx[l], N, win);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(hipMemcpyAsync(hw.data(), win, sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
+            HIP_TRY(hipStreamSynchronize(stream));
+            for (int32_t b = 0; b < nblk; ++b) {
+                const int lo = hw[b].x & ~3;  // windows start at a multiple of 4 columns
+                widest = std::max(widest, (hw[b].x + hw[b].y - lo + 3) & ~3);
+            }
+            if (N % (2 * spdnn::kBlk) == 0)
+                for (int32_t b = 0; b + 1 < nblk; b += 2) {
+                    if (!hw[b].y || !hw[b + 1].y) continue;
+                    const int lo = std::min(hw[b].x, hw[b + 1].x) & ~3;
+                    const int hi = std::max(hw[b].x + hw[b].y, hw[b + 1].x + hw[b + 1].y);
+                    widest = std::max(widest, (hi - lo + 3) & ~3);
+                }
+        }
+        *widest_window = widest;
     }
     return SPDNN_OK;
 }
@@ -591,12 +619,14 @@ int spdnn_create_ooc(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* i
                        device_arena_bytes, reinterpret_cast<hipStream_t>(hip_stream), host_arena, host_arena_bytes);
 }
 
-int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev, size_t scratch_bytes,
-                     void* hip_stream, int32_t* passes, int32_t* total) {
+int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx, void* scratch_dev,
+                     size_t scratch_bytes, void* hip_stream, int32_t* passes, int32_t* total, int32_t* widest_window) {
     if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
     if (!ptr || !scratch_dev || !total) return fail(SPDNN_EINVAL, "null argument");
+    if (widest_window && !idx) return fail(SPDNN_EINVAL, "widest_window needs idx");
     std::vector<int32_t> po;
-    const int rc = scan_csr(N, L, ptr, scratch_dev, scratch_bytes, reinterpret_cast<hipStream_t>(hip_stream), &po);
+    const int rc = scan_csr(N, L, ptr, scratch_dev, scratch_bytes, reinterpret_cast<hipStream_t>(hip_stream), &po, idx,
+                            widest_window);
     if (rc != SPDNN_OK) return rc;
     int64_t sum = 0;
     for (int32_t l = 0; l < L; ++l) {

@@ -1713,6 +1713,35 @@ __global__ void csr_scan_kernel(const int32_t* __restrict__ ptr, int N, int* __r
         atomicMax(out, e - a);
 }
 
+// Column window of every 1024-neuron block of a general layer, over all of its neurons'
+// connections (valid columns only): win[b] = {first column, columns}, {0, 0} if it has none.
+__global__ __launch_bounds__(kBlk) void csr_block_window_kernel(const int32_t* __restrict__ ptr,
+                                                                const int32_t* __restrict__ idx, int N,
+                                                                int2* __restrict__ win) {
+    __shared__ int s_lo, s_hi;
+    if (threadIdx.x == 0) {
+        s_lo = N;
+        s_hi = -1;
+    }
+    __syncthreads();
+    const int j = blockIdx.x * kBlk + threadIdx.x;
+    int lo = N, hi = -1;
+    if (j < N) {
+        const int a = ptr[j], e = ptr[j + 1];
+        for (int k = a; k < e; ++k) {
+            const int c = idx[k];
+            if (c >= 0 && c < N) {
+                lo = min(lo, c);
+                hi = max(hi, c);
+            }
+        }
+    }
+    atomicMin(&s_lo, lo);
+    atomicMax(&s_hi, hi);
+    __syncthreads();
+    if (threadIdx.x == 0) win[blockIdx.x] = s_hi >= s_lo ? make_int2(s_lo, s_hi + 1 - s_lo) : make_int2(0, 0);
+}
+
 // Pass r of a layer: smallest valid column among entries 32r .. 32r+31 of the neurons of
 // every 1024-neuron block (blockmin[b] = N before the launch).  The padding points there,
 // so that it does not widen the block's column window.

@@ -90,6 +90,11 @@ def test_long_neurons_several_passes(N, L, batch, kmax, width):
     want = [max(1, -(-int(np.diff(p).max()) // 32)) for p in ptr]
     assert [m.layer_passes(l) for l in range(L)] == want and max(want) > 1
     assert m.layer_kernel(0) in (sp.SPDNN_KERNEL_SINGLE, sp.SPDNN_KERNEL_STAGED)
+    if width:   # the arena was sized for the patterns' window, not for the worst case
+        assert m.widest_window <= 1024 + width + 8
+        assert m.arena.numel() < sp.spdnn_weights_bytes(N, sum(want))
+    else:
+        assert m.widest_window >= N - 64
     n, rows, Y = gpu_infer_general(ptr, idx, val, bias, Y0, model=m)
     m.close()
     common, _ = check_against_oracle(ref, n, rows, Y, what="general long N=%d" % N)
@@ -211,8 +216,10 @@ def test_general_errors_and_edges():
     tv = [torch.from_numpy(v).to(dev) for v in val]
     tb = torch.from_numpy(bias).to(dev)
     scratch = torch.empty(4096, dtype=torch.uint8, device=dev)
-    passes, total = sp.spdnn_csr_passes(N, 2, [p.data_ptr() for p in tp], scratch.data_ptr(), scratch.numel(),
-                                        torch.cuda.current_stream().cuda_stream)
+    passes, total, widest = sp.spdnn_csr_passes(N, 2, [p.data_ptr() for p in tp], scratch.data_ptr(), scratch.numel(),
+                                                torch.cuda.current_stream().cuda_stream,
+                                                idx_ptrs=[a.data_ptr() for a in ti])
+    assert widest == N   # columns anywhere: every block spans the whole row
     assert passes.tolist() == [max(1, -(-int(np.diff(p).max()) // 32)) for p in ptr] and total == int(passes.sum())
     need = sp.spdnn_weights_bytes_for_window(N, total, 4)
     arena = torch.empty(need, dtype=torch.uint8, device=dev)
