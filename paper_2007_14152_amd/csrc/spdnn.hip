@@ -135,8 +135,8 @@ struct WorkView {
     float* Y[2];
     int* cat[2];
     int* gid[2];
-    int* flags;
-    int* count;
+    uint8_t* flags[2];  // one byte per row; layer l raises flags[l & 1]
+    int* count[2];      // layer l reads count[l & 1]
 };
 size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
     size_t o = 0;
@@ -154,10 +154,15 @@ size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
         if (v) v->gid[i] = reinterpret_cast<int*>(base + o);
         o += lb;
     }
-    if (v) v->flags = reinterpret_cast<int*>(base + o);
-    o += lb;
-    if (v) v->count = reinterpret_cast<int*>(base + o);
-    o += kAlign;
+    const size_t fb = up((size_t)batch + 16);  // flags are read 16 bytes at a time
+    for (int i = 0; i < 2; ++i) {
+        if (v) v->flags[i] = reinterpret_cast<uint8_t*>(base + o);
+        o += fb;
+    }
+    for (int i = 0; i < 2; ++i) {
+        if (v) v->count[i] = reinterpret_cast<int*>(base + o);
+        o += kAlign;
+    }
     return o;
 }
 
@@ -736,7 +741,8 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
     carve_work(N, batch, static_cast<char*>(work_arena), &wv);
     hipStream_t s = h->stream;
 
-    spdnn::init_lists_kernel<<<(batch + 255) / 256, 256, 0, s>>>(wv.cat[0], wv.gid[0], wv.flags, wv.count, batch);
+    spdnn::init_lists_kernel<<<(batch + 255) / 256, 256, 0, s>>>(wv.cat[0], wv.gid[0], wv.flags[0], wv.flags[1], wv.count[0],
+                                                                 batch);
     h->host_counts[0] = batch;
     int32_t bound = batch;  // upper bound of the rows active at the layer being launched
     int32_t run = 0;        // layers launched
@@ -788,34 +794,34 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
             const size_t lds = spdnn::tile_pair_bytes((d.lds_cols + 255) / 256 * 256);  // whole waves of 256 columns
             if (d.multi && d.mode == kStaged)
                 spdnn::fused_layer_kernel<true, true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q, d.pass);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, h->G, Q, d.pass);
             else if (d.multi)
                 spdnn::fused_layer_kernel<false, true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q, d.pass);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, h->G, Q, d.pass);
             else if (d.mode == kPair)
                 spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWidePair && d.pair4 && d.ww.nstage == 2)  // + the all-zero entries and the spill table
                 spdnn::fused_wide_pair4_kernel<2, 32><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWidePair && d.pair4)
                 spdnn::fused_wide_pair4_kernel<4, 16><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWidePair)
                 spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + 2 * spdnn::kBufSkew, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWide && d.ww.nstage > 8)
                 spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, h->nblk, h->G, Q);
             else if (d.mode == kWide)
                 spdnn::fused_wide_kernel<16><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.ww, h->bias_dev, N, h->nblk, h->G, Q);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, h->nblk, h->G, Q);
             else if (d.mode == kStaged)
                 spdnn::fused_layer_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, h->G, Q);
             else
                 spdnn::fused_layer_kernel<false><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags, wv.count, d.w, h->bias_dev, N, h->nblk, h->G, Q);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, h->G, Q);
             if (h->ooc_host) {  // the slot is free once this kernel is done: refill it with pass p + 2
                 HIP_TRY(hipEventRecord(h->ooc_freed[p & 1], s));
                 if (p + 2 < P) {
@@ -825,7 +831,8 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
             }
         }
         if (h->profiling) HIP_TRY(hipEventRecord(h->t1[l], s));
-        spdnn::compact_kernel<<<1, 1024, 0, s>>>(wv.flags, wv.count, wv.gid[l & 1], wv.gid[(l + 1) & 1],
+        spdnn::compact_kernel<<<spdnn::kCompactWGs, 1024, 0, s>>>(wv.flags[l & 1], wv.flags[(l + 1) & 1], wv.count[l & 1],
+                                                  wv.count[(l + 1) & 1], wv.gid[l & 1], wv.gid[(l + 1) & 1],
                                                   wv.cat[(l + 1) & 1], h->host_counts + l + 1);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(h->lag_ev[l % kLag], s));

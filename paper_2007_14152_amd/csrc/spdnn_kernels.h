@@ -506,7 +506,7 @@ __device__ __forceinline__ unsigned finish_rows_pass(float (&a)[kRows], const fl
 template <bool MULTI, bool PASSES = false>
 __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    int* __restrict__ flags, const int* __restrict__ count_ptr, LayerWeights w,
+    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, LayerWeights w,
     const float* __restrict__ bias, int N, int nblk, int G, int Q, int pass = kPassFinal) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
@@ -726,7 +726,7 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    int* __restrict__ flags, const int* __restrict__ count_ptr, LayerWeights w,
+    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, LayerWeights w,
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
@@ -865,7 +865,7 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
 template <int S>
 __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
     const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    int* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
+    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
     const float* __restrict__ bias, int N, int nblk, int G, int Q) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
@@ -1077,7 +1077,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    int* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
+    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
     constexpr int S = 16;
     extern __shared__ float4 lds4[];
@@ -1294,7 +1294,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
 template <int NS, int S>
 __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    int* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
+    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
     static_assert(NS * S == 64 && (NS == 2 || NS == 4), "64 steps per neuron");
     constexpr int LNS = NS == 4 ? 2 : 1;  // log2(NS)
@@ -1531,78 +1531,115 @@ __global__ void wide_spill16_kernel(const uint16_t* __restrict__ spill_col, cons
 // a2: active-row compaction (the host loop of Listing 1 between two layers,
 // moved onto the GPU).  Stable filter of the A rows whose flag is set:
 // cat_out[p] = slot in the buffer just written, gid_out[p] = original row id,
-// *count = new A; flags are cleared for the next layer.  The new count is also
-// stored to pinned host memory so the host can size later launches without a
-// stream sync.
+// *count_out = new A.  The new count is also stored to pinned host memory so the
+// host can size later launches without a stream sync.
 //
-// One workgroup, three phases per 65536 rows, so that no phase is a chain of
-// dependent round trips: (1) every thread reads its flag and its row number in each
-// of up to 64 rounds of 1024 rows (16 loads in flight at a time), remembers the
-// flags as bits and a wave64 ballot gives each wave's count per round; (2) the
-// 64 x 16 counts are scanned once by the whole workgroup; (3) every thread
-// re-derives its rank from a ballot of its remembered bit and writes its rows out
-// (no loads left in this phase).
+// Flags are bytes (0 or 1).  kCompactWGs workgroups, no communication between them:
+// workgroup w owns the rows [w*S, (w+1)*S) (S a multiple of 1024) and counts for
+// itself the flags set before its slice -- at most A bytes, read 16 at a time, which is
+// less than what its own slice costs -- so no workgroup ever waits for another.  Its
+// own slice goes in chunks of kCompactRounds rounds of 1024 rows, three phases each so
+// that no phase is a chain of dependent round trips: (1) every thread reads its flag
+// and its row number of every round, remembers the flags as bits, and a wave64 ballot
+// gives each wave's count per round; (2) the rounds x 16 counts are scanned once by
+// the whole workgroup; (3) every thread re-derives its rank from a ballot of its
+// remembered bit and writes its rows out (no loads left in this phase).
+//
+// Flags and count are double-buffered over the layers: this launch reads flags_in and
+// count_in, which the other workgroups may still be reading, writes count_out, and
+// clears the same rows of flags_clear, the buffer the next layer's kernel raises its
+// flags in.  (A never grows, so rows past A in either buffer are never read again.)
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void compact_kernel(int* __restrict__ flags, int* __restrict__ count,
-                                                       const int* __restrict__ gid_in,
-                                                       int* __restrict__ gid_out, int* __restrict__ cat_out,
-                                                       int* host_count) {
-    __shared__ int tot[64 * 16];  // [round][wave]: kept rows, then exclusive offsets
+constexpr int kCompactWGs = 16;
+constexpr int kCompactRounds = 4;
+static_assert(kCompactRounds * 16 == 64, "one wave scans the (round, wave) counts");
+
+// Number of set bytes among flags[0 .. n), counted by the whole workgroup.  red: 17 ints of LDS.
+__device__ __forceinline__ int count_flags(const uint8_t* __restrict__ flags, int n, int* red) {
+    const int tid = threadIdx.x;
+    int c = 0;
+    for (int i = tid * 16; i < n; i += kBlk * 16) {
+        if (i + 16 <= n) {  // bytes are 0 or 1: the population count of a word is its number of flags
+            const uint4 v = *reinterpret_cast<const uint4*>(flags + i);
+            c += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+        } else {
+            for (int k = i; k < n; ++k) c += flags[k];
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
+    __syncthreads();  // red may still be read from a call before
+    if ((tid & 63) == 0) red[tid >> 6] = c;
+    __syncthreads();
+    if (tid == 0) {
+        int t = 0;
+        for (int w = 0; w < 16; ++w) t += red[w];
+        red[16] = t;
+    }
+    __syncthreads();
+    return red[16];
+}
+
+__global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict__ flags_in,
+                                                       uint8_t* __restrict__ flags_clear,
+                                                       const int* __restrict__ count_in, int* __restrict__ count_out,
+                                                       const int* __restrict__ gid_in, int* __restrict__ gid_out,
+                                                       int* __restrict__ cat_out, int* host_count) {
+    __shared__ int tot[kCompactRounds * 16];  // [round][wave]: kept rows, then exclusive offsets
     __shared__ int wave_tot[16];
+    __shared__ int red[17];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int A = *count;
-    int base = 0;
-    for (int chunk0 = 0; chunk0 < A; chunk0 += 65536) {
-        const int nr = min(64, (A - chunk0 + 1023) >> 10);
-        unsigned long long mine = 0ull;
-        int g[64];  // original row number of my row of round r (all loop indices below are compile-time)
+    const int A = *count_in;
+    const int S = ((A + (int)gridDim.x - 1) / (int)gridDim.x + 1023) & ~1023;
+    const int lo = min(A, (int)blockIdx.x * S);
+    const int hi = min(A, lo + S);
+    if (blockIdx.x == 0) {  // the first workgroup also reports the new count
+        const int total = count_flags(flags_in, A, red);
+        if (tid == 0) {
+            *count_out = total;
+            __hip_atomic_store(host_count, total, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+    if (lo >= hi) return;
+    int base = count_flags(flags_in, lo, red);  // rows kept before my slice (lo is a multiple of 1024)
+    for (int chunk0 = lo; chunk0 < hi; chunk0 += kCompactRounds * 1024) {
+        const int nr = min(kCompactRounds, (hi - chunk0 + 1023) >> 10);
+        unsigned mine = 0u;
+        int f[kCompactRounds], g[kCompactRounds];  // my flag and original row number of round r
 #pragma unroll
-        for (int r0 = 0; r0 < 64; r0 += 8) {  // 8 rounds per batch: 16 loads in flight
-            if (r0 >= nr) continue;
-            int f[8];
+        for (int r = 0; r < kCompactRounds; ++r) {
+            const int i = chunk0 + (r << 10) + tid;
+            const bool ok = r < nr && i < hi;
+            f[r] = ok ? flags_in[i] : 0;
+            g[r] = ok ? gid_in[i] : 0;
+        }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = chunk0 + ((r0 + u) << 10) + tid;
-                const bool ok = r0 + u < nr && i < A;
-                f[u] = ok ? flags[i] : 0;
-                g[r0 + u] = ok ? gid_in[i] : 0;
+        for (int r = 0; r < kCompactRounds; ++r) {
+            const int i = chunk0 + (r << 10) + tid;
+            if (r < nr && i < hi) flags_clear[i] = 0;
+            const unsigned long long m = __ballot(f[r] != 0);
+            if (f[r] != 0) mine |= 1u << r;
+            if (lane == 0) tot[r * 16 + wave] = __popcll(m);
+        }
+        __syncthreads();
+        // exclusive scan over the (round, wave) counts: entry tid = round tid/16, wave tid%16 (one wave's worth)
+        if (wave == 0) {
+            const int v = tot[lane];
+            int incl = v;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int up = __shfl_up(incl, d, 64);
+                if (lane >= d) incl += up;
             }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int r = r0 + u;
-                const int i = chunk0 + (r << 10) + tid;
-                if (r < nr && i < A) flags[i] = 0;
-                const unsigned long long m = __ballot(f[u] != 0);
-                if (f[u] != 0) mine |= 1ull << r;
-                if (lane == 0 && r < nr) tot[r * 16 + wave] = __popcll(m);
-            }
+            tot[lane] = incl - v;
+            if (lane == 63) wave_tot[0] = incl;
         }
         __syncthreads();
-        // exclusive scan over the (round, wave) counts: entry tid = round tid/16, wave tid%16
-        const int v = (tid < nr * 16) ? tot[tid] : 0;
-        int incl = v;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int up = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += up;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        int wbase = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            const int c = wave_tot[w];
-            wbase += (w < wave) ? c : 0;
-            total += c;
-        }
-        tot[tid] = wbase + incl - v;
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < 64; ++r) {
-            if (r >= nr) continue;
-            const bool keep = (mine >> r) & 1ull;
+        for (int r = 0; r < kCompactRounds; ++r) {
+            const bool keep = (mine >> r) & 1u;
             const unsigned long long m = __ballot(keep);
             if (keep) {
                 const int p = base + tot[r * 16 + wave] + __popcll(m & ((1ull << lane) - 1ull));
@@ -1610,23 +1647,20 @@ __global__ __launch_bounds__(1024) void compact_kernel(int* __restrict__ flags, 
                 gid_out[p] = g[r];
             }
         }
-        base += total;
+        base += wave_tot[0];
         __syncthreads();
-    }
-    if (tid == 0) {
-        *count = base;
-        __hip_atomic_store(host_count, base, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
-// Start of an inference: identity lists, cleared flags, A = batch.
-__global__ void init_lists_kernel(int* __restrict__ cat, int* __restrict__ gid, int* __restrict__ flags,
-                                  int* __restrict__ count, int batch) {
+// Start of an inference: identity lists, both flag buffers cleared, A = batch.
+__global__ void init_lists_kernel(int* __restrict__ cat, int* __restrict__ gid, uint8_t* __restrict__ flags0,
+                                  uint8_t* __restrict__ flags1, int* __restrict__ count, int batch) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < batch) {
         cat[i] = i;
         gid[i] = i;
-        flags[i] = 0;
+        flags0[i] = 0;
+        flags1[i] = 0;
     }
     if (i == 0) *count = batch;
 }
