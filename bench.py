@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--general", default=None, metavar="KMIN,KMAX",
                     help="general-layer variant (ours): neurons with KMIN..KMAX connections and varying weights, "
                          "through spdnn_create_csr; needs --layers (default 6)")
+    ap.add_argument("--scatter", action="store_true",
+                    help="scattered-window variant (ours): the members of every window are spread over the row by a "
+                         "seeded permutation per layer")
     ap.add_argument("--out-of-core", action="store_true",
                     help="weights in pinned host memory, streamed through two device buffers (ours: the target keeps them resident)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -118,6 +121,8 @@ def main():
         didx = torch.empty((L, N, 32), dtype=torch.int32, device=dev)
         for l in range(L):
             didx[l] = synth.gen_layer(N, l, c["seed"], c["window"], device=dev)
+            if a.scatter:
+                didx[l] = synth.scatter_columns(didx[l], N, l, c["seed"], device=dev)
         dval = torch.full((L, N, 32), synth.WEIGHT, dtype=torch.float32, device=dev)
         dbias = synth.gen_bias(N, c["bias"], device=dev)
         model = sp.Model([didx[l] for l in range(L)], [dval[l] for l in range(L)], dbias, device=dev,
@@ -174,6 +179,7 @@ def main():
             a.config, N, L, batch, c["bias"], c["window"], density) + (
                 " general layers %s connections per neuron, passes %s" % (
                     a.general, [model.layer_passes(l) for l in range(L)]) if a.general else "") + (
+                " windows scattered" if a.scatter else "") + (
                 " weights out of core (%.1f MB on the device, %.1f MB in pinned host memory)" % (
                     model.arena.numel() / 1e6, model.host_arena.numel() / 1e6) if a.out_of_core else ""),
             "layers_launched": int(launches // a.steps), "rows_in_per_layer": [int(r) for r in rows_trace[:8]],

@@ -284,6 +284,25 @@ def gen_layer(N, l, seed, window=None, device=None):
     return bk.to_i32(cols)
 
 
+_STREAM_S = 0x5350444E4E5F5331    # column scatter
+
+
+def scatter_columns(cols, N, l, seed, device=None):
+    """The "scattered window" variant of a windowed layer: every column c of the
+    pattern is replaced by pi_l(c), pi_l a seeded permutation of all N columns (ranks
+    of one hash per column), and each neuron's columns are sorted again.  The set of
+    columns an output block reads keeps its size but is spread over the whole row."""
+    bk = _backend(device)
+    k = _mix_py(_mix_py(seed ^ _STREAM_S) ^ l)
+    h = bk.lsr(_mix(bk, bk.arange(N) ^ bk.const(k)), 1)
+    pi = bk.argsort(bk.argsort(h))                          # rank of column c
+    if bk.name == "numpy":
+        out = np.sort(pi[np.asarray(cols, dtype=np.int64)], axis=1)
+    else:
+        out = torch.sort(pi[cols.to(torch.int64)], dim=1).values
+    return bk.to_i32(out)
+
+
 def gen_values(N, device=None):
     """Weight values of one layer: float32 [N, 32], all 1/16."""
     if device is None or device == "numpy":

@@ -490,3 +490,23 @@ def test_largest_n_with_columns_anywhere(uniform):
     assert kinds == [sp.SPDNN_KERNEL_WIDE] * L
     common, _ = check_against_oracle(ref, n, rows, Y, what="N=65536 anywhere uniform=%s" % uniform)
     assert common > 0
+
+
+def test_scattered_windows():
+    """cfg-4-like windows whose members are scattered over the row by a permutation per layer:
+    each block still reads 1024 different columns, but from everywhere, so the layers run as wide
+    layers; results against the oracle."""
+    import paper_2007_14152_amd as sp
+    N, L, batch, w = 16384, 3, 40, 1024
+    idx = [synth.scatter_columns(synth.gen_layer(N, l, 31, w), N, l, 31) for l in range(L)]
+    val = [synth.gen_values(N) for _ in range(L)]
+    bias = synth.gen_bias(N, -0.3)
+    Y0 = synth.gen_y0(batch, N, 31, density="mixed")
+    ref = oracle.infer(idx, val, bias, Y0)
+    assert 0 < ref.n_active < batch
+    m = sp.Model(idx, val, bias)
+    assert m.widest_window > N - 64
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    m.close()
+    common, _ = check_against_oracle(ref, n, rows, Y, what="scattered windows")
+    assert common > 0

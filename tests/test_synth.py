@@ -55,3 +55,21 @@ def test_golden_digests():
     spec.loader.exec_module(mk)
     want = open(os.path.join(GOLD, "synth_golden.txt")).read().strip().splitlines()
     assert list(mk.lines()) == want
+
+
+def test_scattered_window_variant():
+    """scatter_columns renames the columns by one permutation per layer: each block's set of
+    columns keeps its size but spreads over the row; rows stay sorted and distinct; both
+    backends agree."""
+    import torch
+    N, w = 8192, 1024
+    a = synth.gen_layer(N, 3, 11, w)
+    b = synth.scatter_columns(a, N, 3, 11)
+    assert b.dtype == np.int32 and b.shape == a.shape and (np.diff(b, axis=1) > 0).all()
+    for blk in range(N // w):
+        ua, ub = np.unique(a[blk * w:(blk + 1) * w]), np.unique(b[blk * w:(blk + 1) * w])
+        assert len(ua) == len(ub) <= w and ua.max() - ua.min() < w and ub.max() - ub.min() > N // 2
+    # a permutation: two columns are equal after renaming iff they were equal before
+    assert len(np.unique(b)) == len(np.unique(a))
+    assert not np.array_equal(b, synth.scatter_columns(a, N, 4, 11))
+    assert np.array_equal(b, synth.scatter_columns(torch.from_numpy(a), N, 3, 11, device="cpu").numpy())
