@@ -313,7 +313,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + 2 * spdnn::kBufSkew));
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPadLds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<4, 16>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<2, 32>),
@@ -808,7 +808,7 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
                 spdnn::fused_wide_pair4_kernel<4, 16><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
                     Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWidePair)
-                spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + 2 * spdnn::kBufSkew, s>>>(
+                spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + spdnn::kPadLds, s>>>(
                     Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWide && d.ww.nstage > 8)
                 spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(

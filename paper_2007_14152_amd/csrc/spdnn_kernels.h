@@ -76,7 +76,13 @@ struct WideWeights {
                                 // (0xFFFF = none), for fused_wide_pair4_kernel
 };
 constexpr int kChunkPair = 4;        // row groups per chunk when a lane holds two neurons
-constexpr uint32_t kNoSlot = 0xFFFFu;
+// Compact step lists (layers with one weight value): a 16-bit code is the LDS slot of the step's
+// column, or -- for a step that pads a short list -- kPadSlot | q: "read zeros from bank quad q".
+// The set-up (wide_pack_kernel) gives every padded step a quad that the other lanes served in the
+// same clock do not read, so padding never collides with a real read.  The kernels keep 16 all-zero
+// entries, one per quad, right behind the tile pair, where slots kCap .. kCap+15 fall (512 bytes,
+// so that the second buffer's +256 lands on zeros too): padding needs no special case in them.
+constexpr uint32_t kPadSlot = kCap;
 // Steps per stage of the wide format: 2 stages exist only for layers that run two neurons per
 // lane with all their steps in registers (2 x 32 = 4 x 16 = 64 steps per neuron).
 __host__ __device__ inline int wide_steps(int nstage) { return nstage > 8 ? 8 : nstage <= 2 ? 32 : 16; }
@@ -1108,10 +1114,11 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     const int ncols = win.y;
     const int nstage = w.nstage;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
-    const uint32_t zero_addr = lds_base + tile_pair_bytes(kCap);  // 16 zero bytes here and 256 bytes further
-    if (tid < 2) {
+    // 512 zero bytes behind the tile pair: slots kCap .. kCap+15, an entry per bank quad, for either buffer
+    const uint32_t zero_addr = lds_base + tile_pair_bytes(kCap);
+    if (tid < 2 * kBufSkew / 16) {
         using lds_f4 = __attribute__((address_space(3))) f32x4;
-        *reinterpret_cast<lds_f4*>(zero_addr + tid * kBufSkew) = f32x4{0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<lds_f4*>(zero_addr + tid * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const float bjA = bias[jA], bjB = bias[jB];
 
@@ -1174,8 +1181,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t lo = x[i] & 0xFFFFu, hi = x[i] >> 16;
-            o[2 * i] = lo == kNoSlot ? zero_addr : lds_base + tile_offset(lo);
-            o[2 * i + 1] = hi == kNoSlot ? zero_addr : lds_base + tile_offset(hi);
+            o[2 * i] = lds_base + tile_offset(lo);  // padding codes are slots of the zero entries
+            o[2 * i + 1] = lds_base + tile_offset(hi);
         }
     };
     auto load_weights = [&](int s) {
@@ -1326,10 +1333,11 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     const int ncols = win.y;
     const int nstage = w.nstage;  // NS = 4: 3 or 4; NS = 2: 2
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
-    const uint32_t zero_addr = lds_base + tile_pair_bytes(kCap);  // 16 zero bytes here and 256 bytes further
-    if (tid < 2) {
+    // 512 zero bytes behind the tile pair: slots kCap .. kCap+15, an entry per bank quad, for either buffer
+    const uint32_t zero_addr = lds_base + tile_pair_bytes(kCap);
+    if (tid < 2 * kBufSkew / 16) {
         using lds_f4 = __attribute__((address_space(3))) f32x4;
-        *reinterpret_cast<lds_f4*>(zero_addr + tid * kBufSkew) = f32x4{0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<lds_f4*>(zero_addr + tid * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const float bjA = bias[jA], bjB = bias[jA + kBlk];
     uint32_t sh4 = 4;
@@ -1342,8 +1350,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
         const uint32_t zero16 = zero_addr >> 4, base16 = lds_base >> 4;
         auto conv = [&](uint32_t two) -> uint32_t {
             const uint32_t lo = two & 0xFFFFu, hi = two >> 16;
-            const uint32_t a = lo == kNoSlot ? zero16 : base16 + (tile_offset(lo) >> 4);
-            const uint32_t c = hi == kNoSlot ? zero16 : base16 + (tile_offset(hi) >> 4);
+            const uint32_t a = base16 + (tile_offset(lo) >> 4);  // padding codes are slots of the zero entries
+            const uint32_t c = base16 + (tile_offset(hi) >> 4);
             return a | (c << 16);
         };
 #pragma unroll
@@ -1507,14 +1515,15 @@ __global__ void wide_slots_kernel(const uint2* __restrict__ pk, uint4* __restric
         // step 8*octet + k of this lane: pk index ((bs*(S/2) + step/2)*kBlk + lane)*2 + step%2
         const size_t step = 8 * octet + k;
         const uint2 e = pk[(((bs * (S / 2) + (step >> 1)) * kBlk + lane) << 1) | (step & 1)];
-        h[k] = e.y == 0u ? kNoSlot : (e.x & 0xFFFFu);
+        h[k] = e.y != 0u ? (e.x & 0xFFFFu) : kPadSlot | (e.x & 15u);  // weight 0: zeros from the same quad
     }
     ps[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
 }
 
 // Spilled connections in the form fused_wide_pair4_kernel keeps in LDS: stage << 14 | (tile byte
 // offset of the column's entry >> 4), 0xFFFF where the list has no entry.  One thread per entry.
-constexpr int kPair4LdsExtra = 2 * kBufSkew + 2 * kSpill * kBlk * 2;  // zero entries + spill table behind the tile pair
+constexpr int kPadLds = 2 * kBufSkew;  // the zero entries behind the tile pair
+constexpr int kPair4LdsExtra = kPadLds + 2 * kSpill * kBlk * 2;  // zero entries + spill table behind the tile pair
 __global__ void wide_spill16_kernel(const uint16_t* __restrict__ spill_col, const float* __restrict__ spill_val,
                                     uint16_t* __restrict__ sp16, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // (block * kSpill + e) * kBlk + lane
@@ -2143,6 +2152,10 @@ __global__ __launch_bounds__(kOrderThreads) void wide_pack_kernel(const int32_t*
             W.keep[l] = keep;
         }
         if (nsteps == 0) continue;
+        uint16_t quads_of_step[32];  // bank quads the set's real reads use at each step
+        uint32_t steps_of_lane[kGroup];
+        for (int i = 0; i < 32; ++i) quads_of_step[i] = 0;
+        for (int l = 0; l < kGroup; ++l) steps_of_lane[l] = 0;
         order_group(
             W.order, nsteps,
             [&](int l, int k) -> unsigned {
@@ -2152,10 +2165,22 @@ __global__ __launch_bounds__(kOrderThreads) void wide_pack_kernel(const int32_t*
                 const size_t src = (size_t)neuron(l) * kNnz + k;
                 const int c = idx[src];
                 const bool ok = c >= 0 && c < N;
+                const uint32_t slot = col_slot((uint32_t)(ok ? c - c_lo : 0) & (kCap - 1));
                 pk[entry(step, wave0 + lane_of_group(set, l))] =
-                    make_uint2(col_slot((uint32_t)(ok ? c - c_lo : 0) & (kCap - 1)),
-                               __builtin_bit_cast(uint32_t, ok ? val[src] : 0.0f));
+                    make_uint2(slot, __builtin_bit_cast(uint32_t, ok ? val[src] : 0.0f));
+                quads_of_step[step] |= (uint16_t)(1u << (slot & 15u));
+                steps_of_lane[l] |= 1u << step;
             });
+        // Steps a lane does not fill carry weight 0.  The lanes of a set are served in the same clock, so
+        // the padding of a step reads from a quad that none of the set's real reads of that step uses
+        // (there is one whenever there is padding); lanes that read the same entry do not collide.
+        for (int step = 0; step < nsteps; ++step) {
+            const uint32_t free_quads = ~(uint32_t)quads_of_step[step] & 0xFFFFu;
+            const uint32_t q = free_quads ? (uint32_t)__builtin_ctz(free_quads) : 15u;
+            for (int l = 0; l < kGroup; ++l)
+                if (!((steps_of_lane[l] >> step) & 1u))
+                    pk[entry(step, wave0 + lane_of_group(set, l))] = make_uint2(q, 0u);  // slot q lies in quad q
+        }
     }
 }
 
