@@ -237,3 +237,50 @@ def test_general_errors_and_edges():
     ref = oracle.infer(idx, val, bias, one, ptr=ptr)
     n, rows, Y = gpu_infer_general(ptr, idx, val, bias, one)
     check_against_oracle(ref, n, rows, Y, what="general one row")
+
+
+def _sweep_case(seed):
+    """One seeded case of the sweep below: shapes, pattern kind, weights and neuron lengths all drawn."""
+    rng = np.random.default_rng(9000 + seed)
+    N = int(rng.choice([32, 36, 100, 512, 1024, 1028, 2048, 3000, 4096, 6148, 8192]))
+    L = int(rng.integers(1, 4))
+    batch = int(rng.integers(1, 98))
+    kind = ["fixed", "short", "long"][seed % 3]
+    width = [None, 64, 1024][int(rng.integers(0, 3))]
+    uniform = bool(rng.integers(0, 2))
+    kmax = {"fixed": 32, "short": int(rng.integers(1, 33)), "long": int(rng.integers(33, 90))}[kind]
+    ptr, idx, val = [], [], []
+    for _ in range(L):
+        deg = np.full(N, 32) if kind == "fixed" else rng.integers(0, kmax + 1, size=N)
+        p = np.zeros(N + 1, dtype=np.int32)
+        np.cumsum(deg, out=p[1:])
+        nnz = int(p[N])
+        owner = np.repeat(np.arange(N), deg)
+        if width is None or width >= N:
+            a = rng.integers(0, N, size=nnz)
+        else:
+            a = np.clip((owner // width) * width + rng.integers(0, width, size=nnz), 0, N - 1)
+        v = np.full(nnz, 0.0625, np.float32) if uniform else rng.uniform(0.0, 4.0 / max(kmax, 1), size=nnz).astype(np.float32)
+        ptr.append(p)
+        idx.append(a.astype(np.int32))
+        val.append(v)
+    bias = -rng.uniform(0.0, 0.3, size=N).astype(np.float32)
+    Y0 = (rng.uniform(size=(batch, N)) < rng.uniform(0.05, 0.7, size=(batch, 1))).astype(np.float32)
+    return dict(N=N, L=L, batch=batch, kind=kind, width=width, uniform=uniform, kmax=kmax), ptr, idx, val, bias, Y0
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_seeded_sweep_of_shapes_patterns_and_lengths(seed):
+    """Thirty drawn combinations of N (ragged blocks, one to eight blocks), depth, batch, window width,
+    one weight or many, and neuron lengths (exactly 32 through spdnn_create, 0..32 and 33..89 through
+    spdnn_create_csr): each against the oracle."""
+    import paper_2007_14152_amd as sp
+    from parity_util import gpu_infer
+    what, ptr, idx, val, bias, Y0 = _sweep_case(seed)
+    ref = oracle.infer(idx, val, bias, Y0, ptr=ptr)
+    if what["kind"] == "fixed":
+        N = what["N"]
+        n, rows, Y = gpu_infer([a.reshape(N, 32) for a in idx], [v.reshape(N, 32) for v in val], bias, Y0)
+    else:
+        n, rows, Y = gpu_infer_general(ptr, idx, val, bias, Y0)
+    check_against_oracle(ref, n, rows, Y, what=str(what))
