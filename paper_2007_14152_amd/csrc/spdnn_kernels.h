@@ -396,6 +396,58 @@ __device__ __forceinline__ void fma_block8ps(float (&acc)[4], uint32_t p0, uint3
         : "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "memory");
 }
 
+// Workgroup -> (column block, row groups).  A launch has ncb column blocks (output blocks,
+// or 2048-neuron units) times Q row chunks.  Consecutive workgroup ids go to consecutive
+// XCDs (8 of them, each with its own L2); the G column blocks that read the same rows
+// through overlapping windows get ids that are equal modulo 8, so they share one L2.
+// *count_ptr = number of active rows A; a workgroup takes the row groups [g0, g1) of
+// ceil(A / 4).  Returns false for a workgroup with nothing to do.
+struct WorkItem {
+    int cb, A, g0, g1;
+};
+__device__ __forceinline__ bool my_work(int ncb, int G, int Q, const int* __restrict__ count_ptr, WorkItem& w) {
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int unit = (slot / G) * 8 + xcd;
+    const int sub = slot - (slot / G) * G;
+    const int ngrp = ncb / G;
+    if (unit >= ngrp * Q) return false;
+    const int q = unit / ngrp;
+    w.cb = (unit - q * ngrp) * G + sub;
+    w.A = *count_ptr;
+    const int ngroups = (w.A + kRows - 1) / kRows;
+    const int per = (ngroups + Q - 1) / Q;
+    w.g0 = q * per;
+    w.g1 = min(ngroups, w.g0 + per);
+    return w.g0 < w.g1;
+}
+
+// Tile staging shared by the fused kernels.  A lane owns 4 neighbouring columns of the
+// tile: stage_load fetches them from the tile's 4 rows (16 bytes per row; rows past the
+// last active one re-read the last active row and are never stored), stage_store
+// transposes the 4x4 block in registers and writes one 16-byte entry (the 4 rows of a
+// column) per column.  addr = LDS address of the lane's store group in the buffer to
+// fill; qp = bank quad (times 16) of each of the 4 columns inside its group's 256-byte
+// row, one per byte (0 for layouts where the address already says it all).
+__device__ __forceinline__ void stage_load(f32x4 (&st)[kRows], const float* __restrict__ Yin, int N, int4 c4,
+                                           int row0, int A, int cat_last, size_t coff) {
+    st[0] = *reinterpret_cast<const f32x4*>(Yin + (size_t)c4.x * N + coff);
+    st[1] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N + coff);
+    st[2] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N + coff);
+    st[3] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N + coff);
+}
+__device__ __forceinline__ void stage_store(f32x4 (&st)[kRows], uint32_t addr, uint32_t qp) {
+    using lds_f4 = __attribute__((address_space(3))) f32x4;
+    // The loads of this tile were issued a step ago.  Pin the point where their results are
+    // first touched, otherwise the register shuffles of the transpose are scheduled right
+    // behind the loads and every load turns synchronous.
+    asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
+    *reinterpret_cast<lds_f4*>(addr + (qp & 0xffu) + 0 * 512) = f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
+    *reinterpret_cast<lds_f4*>(addr + ((qp >> 8) & 0xffu) + 1 * 512) = f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
+    *reinterpret_cast<lds_f4*>(addr + ((qp >> 16) & 0xffu) + 2 * 512) = f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
+    *reinterpret_cast<lds_f4*>(addr + (qp >> 24) + 3 * 512) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+}
+
 // Epilogue of one 4-row group of one neuron (Eq. 1: bias, ReLU, clip at 32): lane 4q+i
 // holds rows 0..3 of neuron 4q+i; a 4x4 transpose inside each lane quartet (two DPP
 // exchanges) leaves it with row i of neurons 4q..4q+3, which is one 16-byte store.
@@ -517,25 +569,9 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
 
-    // Workgroup -> (output block b, row chunk q).  Consecutive workgroup ids go to
-    // consecutive XCDs (8 of them, each with its own L2).  The G output blocks that
-    // read the same rows through overlapping windows form a unit; a unit's
-    // workgroups are given ids that are equal modulo 8, so they share one L2.
-    const int xcd = blockIdx.x & 7;
-    const int slot = blockIdx.x >> 3;
-    const int unit = (slot / G) * 8 + xcd;
-    const int sub = slot - (slot / G) * G;
-    const int ngrp = nblk / G;
-    if (unit >= ngrp * Q) return;
-    const int q = unit / ngrp;
-    const int b = (unit - q * ngrp) * G + sub;
-
-    const int A = *count_ptr;
-    const int ngroups = (A + kRows - 1) / kRows;
-    const int per = (ngroups + Q - 1) / Q;
-    const int g0 = q * per;
-    const int g1 = min(ngroups, g0 + per);
-    if (g0 >= g1) return;
+    WorkItem wi;  // my output block and row groups
+    if (!my_work(nblk, G, Q, count_ptr, wi)) return;
+    const int b = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
 
     const int j = b * kBlk + tid;
     const bool jok = j < N;
@@ -604,29 +640,14 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         if (wave_col >= left) return;
         const int row0 = (g0 + gi) * kRows;
         const size_t coff = (size_t)c_lo + (size_t)s * kCap + (size_t)min(4 * tid, left - 4);
-        st[0] = *reinterpret_cast<const f32x4*>(Yin + (size_t)c4.x * N + coff);
-        st[1] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N + coff);
-        st[2] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N + coff);
-        st[3] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N + coff);
+        stage_load(st, Yin, N, c4, row0, A, cat_last, coff);
     };
     auto store_tile = [&](int P, int t) {
         const int gi = MULTI ? t / nstage : t;
         const int s = MULTI ? t - gi * nstage : 0;
         const int left = ncols - s * kCap;
         if (wave_col >= left) return;
-        using lds_f4 = __attribute__((address_space(3))) f32x4;
-        // The loads of this tile were issued a step ago.  Pin the point where their
-        // results are first touched, otherwise the register shuffles of the transpose
-        // are scheduled right behind the loads and every load turns synchronous.
-        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
-        *reinterpret_cast<lds_f4*>(st_addr + (qp & 0xffu) + 0 * 512 + P * kBufSkew) =
-            f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
-        *reinterpret_cast<lds_f4*>(st_addr + ((qp >> 8) & 0xffu) + 1 * 512 + P * kBufSkew) =
-            f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
-        *reinterpret_cast<lds_f4*>(st_addr + ((qp >> 16) & 0xffu) + 2 * 512 + P * kBufSkew) =
-            f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
-        *reinterpret_cast<lds_f4*>(st_addr + (qp >> 24) + 3 * 512 + P * kBufSkew) =
-            f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+        stage_store(st, st_addr + P * kBufSkew, qp);
     };
 
     float acc[kRows] = {0.f, 0.f, 0.f, 0.f};
@@ -736,22 +757,10 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
-    const int xcd = blockIdx.x & 7;
-    const int slot = blockIdx.x >> 3;
-    const int unit = (slot / G) * 8 + xcd;
-    const int sub = slot - (slot / G) * G;
-    const int ngrp = nunit / G;
-    if (unit >= ngrp * Q) return;
-    const int q = unit / ngrp;
-    const int u = (unit - q * ngrp) * G + sub;
+    WorkItem wi;
+    if (!my_work(nunit, G, Q, count_ptr, wi)) return;
+    const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const int b = 2 * u;  // first of the unit's two output blocks
-
-    const int A = *count_ptr;
-    const int ngroups = (A + kRows - 1) / kRows;
-    const int per = (ngroups + Q - 1) / Q;
-    const int g0 = q * per;
-    const int g1 = min(ngroups, g0 + per);
-    if (g0 >= g1) return;
 
     const int jA = b * kBlk + tid, jB = jA + kBlk;  // N is a multiple of 2048 here: both exist
     const int2 win = w.win[b];
@@ -783,23 +792,11 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
         if (wave_col >= ncols) return;
         const int row0 = (g0 + t) * kRows;
         const size_t coff = (size_t)c_lo + (size_t)min(4 * tid, ncols - 4);
-        st[0] = *reinterpret_cast<const f32x4*>(Yin + (size_t)c4.x * N + coff);
-        st[1] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N + coff);
-        st[2] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N + coff);
-        st[3] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N + coff);
+        stage_load(st, Yin, N, c4, row0, A, cat_last, coff);
     };
     auto store_tile = [&](int P) {
         if (wave_col >= ncols) return;
-        using lds_f4 = __attribute__((address_space(3))) f32x4;
-        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));  // first touch of the loaded tile
-        *reinterpret_cast<lds_f4*>(st_addr + (qp & 0xffu) + 0 * 512 + P * kBufSkew) =
-            f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
-        *reinterpret_cast<lds_f4*>(st_addr + ((qp >> 8) & 0xffu) + 1 * 512 + P * kBufSkew) =
-            f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
-        *reinterpret_cast<lds_f4*>(st_addr + ((qp >> 16) & 0xffu) + 2 * 512 + P * kBufSkew) =
-            f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
-        *reinterpret_cast<lds_f4*>(st_addr + (qp >> 24) + 3 * 512 + P * kBufSkew) =
-            f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+        stage_store(st, st_addr + P * kBufSkew, qp);
     };
 
     float accA[kRows] = {0.f, 0.f, 0.f, 0.f}, accB[kRows] = {0.f, 0.f, 0.f, 0.f};
@@ -878,21 +875,9 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
-    const int xcd = blockIdx.x & 7;
-    const int slotid = blockIdx.x >> 3;
-    const int unit = (slotid / G) * 8 + xcd;
-    const int sub = slotid - (slotid / G) * G;
-    const int ngrp = nblk / G;
-    if (unit >= ngrp * Q) return;
-    const int q = unit / ngrp;
-    const int b = (unit - q * ngrp) * G + sub;
-
-    const int A = *count_ptr;
-    const int ngroups = (A + kRows - 1) / kRows;
-    const int per = (ngroups + Q - 1) / Q;
-    const int g0 = q * per;
-    const int g1 = min(ngroups, g0 + per);
-    if (g0 >= g1) return;
+    WorkItem wi;
+    if (!my_work(nblk, G, Q, count_ptr, wi)) return;
+    const int b = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
 
     const int j = b * kBlk + tid;
     const bool jok = j < N;
@@ -931,22 +916,14 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
         if (wave_col >= left) return;
         const int row0 = g * kRows;
         const size_t coff = (size_t)c_lo + (size_t)s * kCap + (size_t)min(4 * tid, left - 4);
-        st[0] = *reinterpret_cast<const f32x4*>(Yin + (size_t)c4.x * N + coff);
-        st[1] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N + coff);
-        st[2] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N + coff);
-        st[3] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N + coff);
+        stage_load(st, Yin, N, c4, row0, A, cat_last, coff);
     };
     auto store_tile = [&](int P, int t) {
         int s;
         (void)group_of(t, s);
         const int left = ncols - s * kCap;
         if (wave_col >= left) return;
-        using lds_f4 = __attribute__((address_space(3))) f32x4;
-        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
-        *reinterpret_cast<lds_f4*>(st_addr + 0 * 512 + P * kBufSkew) = f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
-        *reinterpret_cast<lds_f4*>(st_addr + 1 * 512 + P * kBufSkew) = f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
-        *reinterpret_cast<lds_f4*>(st_addr + 2 * 512 + P * kBufSkew) = f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
-        *reinterpret_cast<lds_f4*>(st_addr + 3 * 512 + P * kBufSkew) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+        stage_store(st, st_addr + P * kBufSkew, 0u);
     };
 
     float acc[kChunk][kRows];
@@ -1091,22 +1068,10 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
-    const int xcd = blockIdx.x & 7;
-    const int slotid = blockIdx.x >> 3;
-    const int unit = (slotid / G) * 8 + xcd;
-    const int sub = slotid - (slotid / G) * G;
-    const int ngrp = nunit / G;
-    if (unit >= ngrp * Q) return;
-    const int q = unit / ngrp;
-    const int u = (unit - q * ngrp) * G + sub;
+    WorkItem wi;
+    if (!my_work(nunit, G, Q, count_ptr, wi)) return;
+    const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const int b = 2 * u;  // first of the unit's two output blocks (same window for both)
-
-    const int A = *count_ptr;
-    const int ngroups = (A + kRows - 1) / kRows;
-    const int per = (ngroups + Q - 1) / Q;
-    const int g0 = q * per;
-    const int g1 = min(ngroups, g0 + per);
-    if (g0 >= g1) return;
 
     const int jA = b * kBlk + tid, jB = jA + kBlk;  // N is a multiple of 2048 here
     const int2 win = w.win[b];
@@ -1150,22 +1115,14 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
         if (wave_col >= left) return;
         const int row0 = g * kRows;
         const size_t coff = (size_t)c_lo + (size_t)s * kCap + (size_t)min(4 * tid, left - 4);
-        st[0] = *reinterpret_cast<const f32x4*>(Yin + (size_t)c4.x * N + coff);
-        st[1] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N + coff);
-        st[2] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N + coff);
-        st[3] = *reinterpret_cast<const f32x4*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N + coff);
+        stage_load(st, Yin, N, c4, row0, A, cat_last, coff);
     };
     auto store_tile = [&](int P, int t) {
         int s;
         (void)group_of(t, s);
         const int left = ncols - s * kCap;
         if (wave_col >= left) return;
-        using lds_f4 = __attribute__((address_space(3))) f32x4;
-        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
-        *reinterpret_cast<lds_f4*>(st_addr + 0 * 512 + P * kBufSkew) = f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
-        *reinterpret_cast<lds_f4*>(st_addr + 1 * 512 + P * kBufSkew) = f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
-        *reinterpret_cast<lds_f4*>(st_addr + 2 * 512 + P * kBufSkew) = f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
-        *reinterpret_cast<lds_f4*>(st_addr + 3 * 512 + P * kBufSkew) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+        stage_store(st, st_addr + P * kBufSkew, 0u);
     };
 
     float accA[kChunkPair][kRows], accB[kChunkPair][kRows];
@@ -1310,22 +1267,10 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
-    const int xcd = blockIdx.x & 7;
-    const int slotid = blockIdx.x >> 3;
-    const int unit = (slotid / G) * 8 + xcd;
-    const int sub = slotid - (slotid / G) * G;
-    const int ngrp = nunit / G;
-    if (unit >= ngrp * Q) return;
-    const int q = unit / ngrp;
-    const int u = (unit - q * ngrp) * G + sub;
+    WorkItem wi;
+    if (!my_work(nunit, G, Q, count_ptr, wi)) return;
+    const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const int b = 2 * u;
-
-    const int A = *count_ptr;
-    const int ngroups = (A + kRows - 1) / kRows;
-    const int per = (ngroups + Q - 1) / Q;
-    const int g0 = q * per;
-    const int g1 = min(ngroups, g0 + per);
-    if (g0 >= g1) return;
 
     const int jA = b * kBlk + tid;  // neuron B is jA + kBlk; N is a multiple of 2048 here
     const int2 win = w.win[b];
@@ -1445,12 +1390,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     auto store_tile = [&](int P, int t) {
         const int left = ncols - (t & (NS - 1)) * kCap;
         if (wave_col >= left) return;
-        using lds_f4 = __attribute__((address_space(3))) f32x4;
-        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
-        *reinterpret_cast<lds_f4*>(st_addr + 0 * 512 + P * kBufSkew) = f32x4{st[0].x, st[1].x, st[2].x, st[3].x};
-        *reinterpret_cast<lds_f4*>(st_addr + 1 * 512 + P * kBufSkew) = f32x4{st[0].y, st[1].y, st[2].y, st[3].y};
-        *reinterpret_cast<lds_f4*>(st_addr + 2 * 512 + P * kBufSkew) = f32x4{st[0].z, st[1].z, st[2].z, st[3].z};
-        *reinterpret_cast<lds_f4*>(st_addr + 3 * 512 + P * kBufSkew) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
+        stage_store(st, st_addr + P * kBufSkew, 0u);
     };
 
     float accA[kRows] = {0.f, 0.f, 0.f, 0.f}, accB[kRows] = {0.f, 0.f, 0.f, 0.f};
