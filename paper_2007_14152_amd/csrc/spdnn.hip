@@ -173,6 +173,38 @@ hipError_t allow_big_lds() {
 }
 
 
+// The fused kernels and two set-up kernels use more dynamic LDS than the default limit allows.
+int allow_large_lds() {
+    constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
+    constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
+    const int tile_lds = (int)spdnn::tile_pair_bytes(spdnn::kCap);
+    HIP_TRY((allow_big_lds<false, false>()));
+    HIP_TRY((allow_big_lds<true, false>()));
+    HIP_TRY((allow_big_lds<false, true>()));
+    HIP_TRY((allow_big_lds<true, true>()));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::order_pack_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::wide_pack_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<1>)));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<2>)));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPadLds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<4, 16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<2, 32>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    return SPDNN_OK;
+}
+
 // Longest neuron of every layer of a general model -> passes of 32 connections; with idx also the
 // widest column window of any 1024-neuron block (of any aligned pair of blocks when N is a multiple
 // of 2048, as spdnn_scan_windows counts).  scratch: device, 8*L + 8*ceil(N/1024) bytes.
@@ -295,33 +327,9 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     hipDeviceProp_t prop;
     HIP_TRY(hipGetDeviceProperties(&prop, dev));
     m->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    HIP_TRY((allow_big_lds<false, false>()));
-    HIP_TRY((allow_big_lds<true, false>()));
-    HIP_TRY((allow_big_lds<false, true>()));
-    HIP_TRY((allow_big_lds<true, true>()));
+    if (allow_large_lds() != SPDNN_OK) return SPDNN_EHIP;
     constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
     constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
-    const int tile_lds = (int)spdnn::tile_pair_bytes(spdnn::kCap);
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::order_pack_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::wide_pack_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<1>)));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<2>)));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPadLds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<4, 16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<2, 32>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
                           hipHostMallocDefault));
     for (int i = 0; i < kLag; ++i) HIP_TRY(hipEventCreateWithFlags(&m->lag_ev[i], hipEventDisableTiming));
