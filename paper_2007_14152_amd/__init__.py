@@ -334,6 +334,47 @@ class Model:
                             rows.data_ptr(), Yf.data_ptr() if want_Y else 0)
         return n, rows[:n], (Yf[:n] if want_Y else None)
 
+    def infer_batched(self, Y0_host, rows_per_batch, want_Y=True):
+        """Inputs that stay in host memory, processed in serial batches (Section III-B-2): Y0_host is a
+        CPU float32 tensor [batch, N] (pinned memory lets the copies overlap the kernels); while one
+        batch is inferred the next one is copied to the GPU on a second stream.  Returns what infer()
+        returns for the whole input: (n_active, active_rows, Y or None), rows numbered as in Y0_host."""
+        torch = self.torch
+        assert not Y0_host.is_cuda and Y0_host.dtype == torch.float32 and Y0_host.is_contiguous()
+        batch = int(Y0_host.shape[0])
+        step = max(1, int(rows_per_batch))
+        with torch.cuda.device(self.device):
+            copy = torch.cuda.Stream()   # default priority
+            bufs = [torch.empty((min(step, max(batch, 1)), self.N), dtype=torch.float32, device=self.device)
+                    for _ in range(2)]
+            ready = [torch.cuda.Event(), torch.cuda.Event()]
+
+            def fetch(k):   # batch k -> buffer k & 1, on the copy stream
+                lo = k * step
+                n = min(step, batch - lo)
+                with torch.cuda.stream(copy):
+                    bufs[k & 1][:n].copy_(Y0_host[lo:lo + n], non_blocking=True)
+                    ready[k & 1].record(copy)
+                return n
+
+            nb = (batch + step - 1) // step
+            rows_out, Y_out, total = [], [], 0
+            n_next = fetch(0) if nb else 0
+            for k in range(nb):
+                n_cur = n_next
+                ready[k & 1].synchronize()           # infer() runs on the model's stream and drains it,
+                if k + 1 < nb:                        # so the other buffer is free: start the next copy now
+                    n_next = fetch(k + 1)
+                n, rows, Y = self.infer(bufs[k & 1][:n_cur], want_Y=want_Y)
+                total += n
+                rows_out.append(rows + k * step)
+                if want_Y:
+                    Y_out.append(Y.clone())
+            copy.synchronize()
+            rows_all = torch.cat(rows_out) if rows_out else torch.empty(0, dtype=torch.int32, device=self.device)
+            Y_all = (torch.cat(Y_out) if Y_out else torch.empty((0, self.N), device=self.device)) if want_Y else None
+        return total, rows_all, Y_all
+
     def set_profiling(self, on=True):
         spdnn_set_profiling(self.h, on)
 

@@ -510,3 +510,24 @@ def test_scattered_windows():
     m.close()
     common, _ = check_against_oracle(ref, n, rows, Y, what="scattered windows")
     assert common > 0
+
+
+@pytest.mark.parametrize("rows_per_batch", [1000, 257, 64, 5000])
+def test_inputs_in_host_memory_in_serial_batches(rows_per_batch):
+    """Section III-B-2: the inputs stay on the host and go through the GPU batch by batch, the copy of
+    the next batch under the kernels of the current one.  Same result as the whole input at once."""
+    import torch
+    import paper_2007_14152_amd as sp
+    c, idx, val, bias = config_model(0, 6)
+    batch = 1000
+    Y0 = synth.gen_y0(batch, c["N"], c["seed"], density="mixed")
+    m = sp.Model(idx, val, bias)
+    want = m.infer(torch.from_numpy(Y0).to("cuda:0"))
+    host = torch.from_numpy(Y0).pin_memory()
+    for rep in range(2):
+        n, rows, Y = m.infer_batched(host, rows_per_batch)
+        assert n == want[0] and 0 < n < batch
+        assert torch.equal(rows, want[1]) and torch.equal(Y, want[2])
+    n, rows, Y = m.infer_batched(host[:0].contiguous(), rows_per_batch)
+    assert n == 0 and rows.numel() == 0
+    m.close()
