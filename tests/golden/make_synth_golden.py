@@ -28,6 +28,11 @@ def lines():
         yield "cfg%d_y0_row17_ones %d" % (k, int(y[1].sum()))
     ym = synth.gen_y0(64, 1024, 5, density="mixed")
     yield "mixed_y0_sha %s" % digest(ym)
+    ptr, idx, val = synth.gen_layer_general(2048, 2, 20200799, 0, 80)
+    yield "general_layer2_sha %s %s %s" % (digest(ptr), digest(idx), digest(val))
+    yield "general_layer2_neuron5 %s" % ",".join(str(int(x)) for x in idx[ptr[5]:ptr[6]])
+    sc = synth.scatter_columns(synth.gen_layer(8192, 1, 31, 1024), 8192, 1, 31)
+    yield "scattered_layer1_sha %s" % digest(sc)
 
 
 if __name__ == "__main__":
