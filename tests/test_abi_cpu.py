@@ -108,3 +108,16 @@ def test_positive_bias_is_rejected():
         sp.spdnn_create(N, L, [a.ctypes.data for a in idx], [a.ctypes.data for a in val], bias.ctypes.data,
                         sp.SPDNN_HOST, 256 * 4096, sp.spdnn_weights_bytes(N, L))
     assert e.value.code == sp.SPDNN_EBIAS
+
+
+def test_header_is_plain_c_and_a_c_program_links():
+    """include/spdnn.h compiles as C99 on its own, and the C user of the ABI builds and links
+    against the library (it runs in the GPU tests)."""
+    import subprocess
+    import sys
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-fsyntax-only", "-x", "c",
+                    os.path.join(ROOT, "include", "spdnn.h")], check=True)
+    sys.path.insert(0, ROOT)
+    import __graft_entry__ as g
+    exe = g.build_c_check()
+    assert os.path.exists(exe)
