@@ -43,6 +43,9 @@ constexpr size_t kAlign = 256;
 inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 constexpr int kLag = 2;  // the host runs at most this many layers ahead of the GPU
+// Set-up of device-resident layers runs on this many streams, a layer per stream in turn: its kernels
+// are single-wave, latency-bound searches that fill a fraction of the chip, so several layers overlap.
+constexpr int kSetupStreams = 4;
 
 enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2, kPair = 3, kWidePair = 4 };
 struct LayerDesc {
@@ -115,7 +118,7 @@ size_t wide_bytes(int32_t nblk, int nstage) {
 size_t staging_bytes(int32_t N, int32_t L) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
     return up((size_t)N * spdnn::kNnz * sizeof(int32_t)) + up((size_t)N * spdnn::kNnz * sizeof(float)) +
-           up((size_t)nblk * spdnn::kCap * sizeof(uint16_t)) +  // column -> LDS slot table of the layer being set up
+           kSetupStreams * up((size_t)nblk * spdnn::kCap * sizeof(uint16_t)) +  // column -> LDS slot tables of the layers being set up
            up(sizeof(int) * (size_t)nblk) +                     // general layers: smallest column of every block
            up(sizeof(int) * (size_t)(5 * L + 1));  // error flag; per layer: wide failure, widest window, weights differ, pair info[2]
 }
@@ -398,8 +401,9 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     o += up((size_t)N * spdnn::kNnz * sizeof(int32_t));
     float* st_val = reinterpret_cast<float*>(base + o);
     o += up((size_t)N * spdnn::kNnz * sizeof(float));
-    uint16_t* slot_tab = reinterpret_cast<uint16_t*>(base + o);
-    o += up((size_t)nblk * spdnn::kCap * sizeof(uint16_t));
+    uint16_t* slot_tabs = reinterpret_cast<uint16_t*>(base + o);  // one table per set-up stream
+    const size_t slot_tab_elems = up((size_t)nblk * spdnn::kCap * sizeof(uint16_t)) / sizeof(uint16_t);
+    o += kSetupStreams * up((size_t)nblk * spdnn::kCap * sizeof(uint16_t));
     int* blockmin = reinterpret_cast<int*>(base + o);
     o += up(sizeof(int) * (size_t)nblk);
     // [0] bad column seen; [1 + p] pass p could not use the wide format; [1 + P + p] pass p's widest window;
@@ -407,9 +411,33 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     int* err_dev = reinterpret_cast<int*>(base + o);
     HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int) * (size_t)(5 * P + 1), stream));
 
+    // Layers that are already on the device and need no staging are set up on several streams in turn.
+    struct SetupStreams {
+        hipStream_t s[kSetupStreams] = {};
+        hipEvent_t start = nullptr;
+        int n = 1;
+        ~SetupStreams() {
+            for (int i = 1; i < n; ++i)
+                if (s[i]) (void)hipStreamDestroy(s[i]);
+            if (start) (void)hipEventDestroy(start);
+        }
+    } ss;
+    ss.s[0] = stream;
+    if (!ptr && where == SPDNN_DEVICE && !ooc && P > 1) {
+        HIP_TRY(hipEventCreateWithFlags(&ss.start, hipEventDisableTiming));
+        HIP_TRY(hipEventRecord(ss.start, stream));  // bias and cleared flags are in place
+        for (int i = 1; i < kSetupStreams; ++i) {
+            HIP_TRY(hipStreamCreateWithFlags(&ss.s[i], hipStreamNonBlocking));
+            ss.n = i + 1;
+            HIP_TRY(hipStreamWaitEvent(ss.s[i], ss.start, 0));
+        }
+    }
+
     const size_t raw = (size_t)N * spdnn::kNnz;
     std::vector<int2> hw((size_t)P * nblk);
     for (int32_t l = 0; l < P; ++l) {  // l = pass; it belongs to layer ll
+        hipStream_t stream = ss.s[l % ss.n];  // everything of this pass goes to one stream
+        uint16_t* slot_tab = slot_tabs + (size_t)(l % ss.n) * slot_tab_elems;
         const int32_t ll = layer_of[l];
         const int32_t* di = idx[ll];
         const float* dv = val[ll];
@@ -488,6 +516,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
                                    hipMemcpyDeviceToHost, stream));
         if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
     }
+    for (int i = 1; i < ss.n; ++i) HIP_TRY(hipStreamSynchronize(ss.s[i]));
     // error flag and the layers whose patterns did not fit the wide format
     std::vector<int> herr((size_t)P + 1, 0);
     HIP_TRY(hipMemcpyAsync(herr.data(), err_dev, sizeof(int) * (size_t)(P + 1), hipMemcpyDeviceToHost, stream));
