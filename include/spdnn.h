@@ -173,13 +173,15 @@ int spdnn_destroy(spdnn_t h);
 const char* spdnn_last_error(void);
 
 /* Measurement aid (not part of the paper's method): with profiling on, spdnn_infer brackets
- * every fused-layer launch with HIP events on the model's stream. */
+ * every layer's fused launches (one, or one per pass of a general layer) with HIP events on the
+ * model's stream. */
 int spdnn_set_profiling(spdnn_t h, int32_t on);
 
 /* After an spdnn_infer with profiling on: *layers_run = number of layers that were launched
  * (inference stops early once no row is active); for l < min(cap, *layers_run),
  * rows_in[l] = rows active on entry to layer l and fused_ms[l] = duration of that layer's
- * fused SpMM+bias+ReLU kernel in milliseconds.  Either array may be NULL. */
+ * fused SpMM+bias+ReLU kernel (of all its passes, and of any wait for out-of-core weights) in
+ * milliseconds.  Either array may be NULL. */
 int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows_in,
                       float* fused_ms);
 
