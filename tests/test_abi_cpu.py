@@ -121,3 +121,28 @@ def test_header_is_plain_c_and_a_c_program_links():
     import __graft_entry__ as g
     exe = g.build_c_check()
     assert os.path.exists(exe)
+
+
+def test_no_library_no_product_and_no_oracle_in_the_product():
+    """Without csrc/libspdnn.so the binding raises (there is no CPU path to fall back to), and
+    nothing under the package imports or names the oracle."""
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "import paper_2007_14152_amd as sp\n"
+            "from paper_2007_14152_amd import build as b\n"
+            "b.LIB = b.LIB + '.absent'\n"
+            "try:\n"
+            "    sp.spdnn_weights_bytes(64, 1)\n"
+            "except RuntimeError as e:\n"
+            "    assert 'no fallback' in str(e), e\n"
+            "    assert 'oracle' not in sys.modules\n"
+            "    print('raised')\n" % ROOT)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True)
+    assert out.returncode == 0 and "raised" in out.stdout, out.stdout + out.stderr
+    pkg = os.path.join(ROOT, "paper_2007_14152_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f), errors="ignore").read()
+                assert "import oracle" not in text and "from oracle" not in text and "spdnn_oracle" not in text, f
