@@ -36,6 +36,9 @@ def parse():
                          "seeded permutation per layer")
     ap.add_argument("--out-of-core", action="store_true",
                     help="weights in pinned host memory, streamed through two device buffers (ours: the target keeps them resident)")
+    ap.add_argument("--no-sustained", dest="sustained", action="store_false",
+                    help="skip the second leg (same model, mixed row densities: rows alive through all layers)")
+    ap.add_argument("--sustained-steps", type=int, default=2)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
@@ -43,15 +46,19 @@ def parse():
     return ap.parse_args()
 
 
-def measured_traffic(workload_key):
-    """HBM bytes per fused-layer launch from the committed rocprofv3 counter summary
-    (profiles/), if it was taken on this workload; else None."""
+def measured_traffic(workload_key, kernel):
+    """HBM bytes of one full (all rows active) launch of the dominant fused kernel, from the committed
+    rocprofv3 counter summary of this workload -- a stored figure, not something this run counts, so
+    it comes with its source; None if no summary exists for this workload and kernel."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         t = json.load(open(path)).get(workload_key)
-        return float(t["hbm_bytes_per_launch"]) if t else None
     except Exception:
-        return None
+        return None, None
+    if not t or t.get("kernel") != kernel:
+        return None, None
+    return float(t["hbm_bytes_full_launch"]), "stored: %s (rocprofv3 FETCH_SIZE + WRITE_SIZE of %s, scaled by a plain copy)" % (
+        t["source"], t["kernel"])
 
 
 def algorithmic_bytes(rows, N, nnz=None):
@@ -79,15 +86,78 @@ def cpu_baseline(c, L, didx, dval, dbias, density, layers_run, target_s, ptr=Non
         y = synth.gen_y0(batch, N, c["seed"], density=density, rows=ids)
         t0 = time.perf_counter()
         r = oracle.infer(idx, val, bias, y, want_Y=False, ptr=ptr)
-        return time.perf_counter() - t0, len(ids), r
+        return time.perf_counter() - t0, len(ids), r, ids
 
-    t, n, _ = run(16)
+    t, n, _, _ = run(16)
     rows = int(max(16, min(batch, n * target_s / max(t, 1e-6))))
-    t, n, r = run(rows)
+    t, n, r, ids = run(rows)
     edges = float(n) * (N * 32 * L if edges_per_row is None else edges_per_row)
     return {"value": edges / t / 1e12, "unit": "TeraEdges/s", "cores": 1, "kind": "oracle",
             "sample": "%d seeded rows of the same workload, all %d layers (%d evaluated before every "
-                      "sampled row was inactive), %.2f s single-threaded" % (n, L, r.layers_evaluated, t)}
+                      "sampled row was inactive), %.2f s single-threaded" % (n, L, r.layers_evaluated, t)}, ids, r
+
+
+def parity_check(model, y0, ids, ref, final_rows):
+    """Outside the timed region: the library against the oracle on the oracle's row sample.  (1) The
+    final active set of the timed full-batch run, restricted to the sample, is the oracle's.  (2) The
+    library run on the sampled rows alone has the oracle's active-row count on entry to every layer.
+    Rows the oracle marks fragile (a pre-activation within 1e-4 of zero decides them) are excused."""
+    import numpy as np
+    import torch
+    fragile = set(ids[ref.fragile_layer >= 0].tolist())
+    want = set(ids[ref.active_rows].tolist())
+    got = set(np.intersect1d(final_rows, ids).tolist())
+    ok_final = not ((want ^ got) - fragile)
+    model.set_profiling(True)
+    n_s, rows_s, _ = model.infer(y0[torch.from_numpy(ids).to(y0.device)].contiguous(), want_Y=False)
+    run, rows_in, _ = model.profile()
+    model.set_profiling(False)
+    apl = ref.active_per_layer
+    ok_layers = all(abs(int(rows_in[l]) - int(apl[l])) <= len(fragile) for l in range(run))
+    ok_layers = ok_layers and all(int(apl[l]) <= len(fragile) for l in range(run, len(apl)))
+    ok_set = not ((set(ids[rows_s.cpu().numpy()].tolist()) ^ want) - fragile)
+    return bool(ok_final and ok_layers and ok_set), {
+        "rows_compared": int(len(ids)), "fragile_rows_excused": len(fragile), "final_set_matches": bool(ok_final),
+        "per_layer_counts_match": bool(ok_layers), "sample_run_set_matches": bool(ok_set)}
+
+
+def timed_leg(model, y0, steps, warmup, N, nnz):
+    """warmup + steps inferences of one resident input; HIP events on the model's stream around every
+    fused launch (the library's profile).  Returns wall seconds per step and the launch statistics."""
+    import numpy as np
+    import torch
+    for _ in range(warmup):
+        model.infer(y0, want_Y=False)
+    model.set_profiling(True)
+    sum_ms = sum_bytes = full_ms = 0.0
+    launches = full = 0
+    batch = int(y0.shape[0])
+    rows_trace = None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        n_active, rows_final, _ = model.infer(y0, want_Y=False)
+        run, rows_in, ms = model.profile()
+        sum_ms += float(ms.sum())
+        sum_bytes += sum(algorithmic_bytes(r, N, nnz[l] if nnz else None) for l, r in enumerate(rows_in))
+        launches += run
+        sel = rows_in == batch
+        full += int(sel.sum())
+        full_ms += float(ms[sel].sum())
+        rows_trace = rows_in
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    model.set_profiling(False)
+    return {"s_per_step": dt / steps, "sum_ms": sum_ms, "sum_bytes": sum_bytes, "launches": launches,
+            "full_launches": full, "full_ms": full_ms, "rows_trace": np.asarray(rows_trace), "n_active": int(n_active),
+            "rows_final": rows_final.cpu().numpy()}
+
+
+def rows_summary(rows_trace):
+    nz = [int(r) for r in rows_trace if r > 0]
+    return {"layers_launched": int(len(rows_trace)), "layers_with_rows": len(nz),
+            "first": int(rows_trace[0]) if len(rows_trace) else 0, "last_nonempty": nz[-1] if nz else 0,
+            "head": [int(r) for r in rows_trace[:8]]}
 
 
 def main():
@@ -131,34 +201,19 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
 
-    if a.copy_probe_gib > 0:
+    if a.copy_probe_gib > 0:   # a plain device copy of known size: the yardstick for the profiler's traffic counters
         n = int(a.copy_probe_gib * (1 << 30)) // 4
         src = torch.ones(n, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
-            sp.spdnn_copy_probe(dst.data_ptr(), src.data_ptr(), n * 4, torch.cuda.current_stream().cuda_stream)
+            dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(a.warmup):
-        model.infer(y0, want_Y=False)
-    model.set_profiling(True)
-    sum_ms = 0.0
-    sum_bytes = 0.0
-    launches = 0
-    rows_trace = None
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        n_active, _, _ = model.infer(y0, want_Y=False)
-        run, rows_in, ms = model.profile()
-        sum_ms += float(ms.sum())
-        sum_bytes += sum(algorithmic_bytes(r, N, nnz[l] if nnz else None) for l, r in enumerate(rows_in))
-        launches += run
-        rows_trace = rows_in
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    model.set_profiling(False)
+    leg = timed_leg(model, y0, a.steps, a.warmup, N, nnz)
+    dt = leg["s_per_step"] * a.steps
+    rows_trace, launches, sum_ms, sum_bytes = leg["rows_trace"], leg["launches"], leg["sum_ms"], leg["sum_bytes"]
+    n_active = leg["n_active"]
 
     if nnz:   # general layers: an edge is a stored connection
         edges = float(batch) * sum(nnz)
@@ -168,6 +223,16 @@ def main():
         executed = float(sum(int(r) for r in rows_trace)) * N * 32
     ms_per_step = dt / a.steps * 1e3
     achieved = sum_bytes / (sum_ms * 1e-3) / 1e9 if sum_ms > 0 else 0.0
+    kinds = {}
+    for l in range(int(launches // a.steps)):
+        k = sp.KERNEL_NAMES[model.layer_kernel(l)]
+        kinds[k] = kinds.get(k, 0) + 1
+    kernel0 = sp.KERNEL_NAMES[model.layer_kernel(0)]
+    full_bytes = algorithmic_bytes(batch, N, nnz[0] if nnz else None)
+    full_ms = leg["full_ms"] / leg["full_launches"] if leg["full_launches"] else None
+    traffic, traffic_source = measured_traffic("cfg%d_batch%d_%s" % (a.config, batch, density), kernel0)
+    if a.scatter or a.general or a.out_of_core:
+        traffic, traffic_source = None, None
     out = {
         "metric": "TeraEdges/sec (batch*N*32*L/time) at 1 MI355X",
         "value": edges * a.steps / dt / 1e12,
@@ -182,19 +247,44 @@ def main():
                 " windows scattered" if a.scatter else "") + (
                 " weights out of core (%.1f MB on the device, %.1f MB in pinned host memory)" % (
                     model.arena.numel() / 1e6, model.host_arena.numel() / 1e6) if a.out_of_core else ""),
-            "layers_launched": int(launches // a.steps), "rows_in_per_layer": [int(r) for r in rows_trace[:8]],
-            "n_active_final": int(n_active), "executed_TeraEdges_per_s": executed * a.steps / dt / 1e12,
+            "executed_TeraEdges_per_s": executed * a.steps / dt / 1e12,
+            "rows_in_per_layer": rows_summary(rows_trace),
+            "kernels_of_launched_layers": kinds,
+            "n_active_final": int(n_active),
             "setup_s": t_setup},
+        # achieved = algorithmic bytes of all fused launches / their summed duration (HIP events on the
+        # model's stream); full_launch_* = the launches on all `batch` rows alone
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic("cfg%d_L%d_batch%d_%s" % (a.config, L, batch, density)),
-                     "kernel": sp.KERNEL_NAMES[model.layer_kernel(0)], "launches": int(launches),
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": kernel0, "launches": int(launches),
                      "avg_launch_ms": sum_ms / max(launches, 1),
-                     "algorithmic_bytes_per_launch": sum_bytes / max(launches, 1)},
+                     "algorithmic_bytes_per_launch": sum_bytes / max(launches, 1),
+                     "full_launch_ms": full_ms, "full_launches": int(leg["full_launches"]),
+                     "algorithmic_bytes_full_launch": full_bytes,
+                     "full_launch_frac": (full_bytes / (full_ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if full_ms else None},
     }
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(c, L, didx, dval, dbias, density, int(launches // a.steps), a.cpu_seconds,
-                                           ptr=ptr, edges_per_row=float(sum(nnz)) if nnz else None)
+        base, ids, ref = cpu_baseline(c, L, didx, dval, dbias, density, int(launches // a.steps), a.cpu_seconds,
+                                      ptr=ptr, edges_per_row=float(sum(nnz)) if nnz else None)
+        out["cpu_baseline"] = base
+        out["parity"], out["parity_detail"] = parity_check(model, y0, ids, ref, leg["rows_final"])
+    if a.sustained and density != "mixed" and not a.general:
+        # Second leg (ours, labelled as such): the same model on inputs of mixed row densities, so that
+        # thousands of rows stay active through all L layers -- the regime of the paper's Table I, in
+        # which compaction and every layer's kernel matter.  Not part of `value`.
+        del y0
+        ym = synth.gen_y0(batch, N, c["seed"], density="mixed", device=dev)
+        sl = timed_leg(model, ym, a.sustained_steps, 1, N, nnz)
+        ex = float(sum(int(r) for r in sl["rows_trace"])) * N * 32
+        out["sustained_activity"] = {
+            "workload": "same model, Y0 rows of mixed density (ours): every layer runs",
+            "steps": a.sustained_steps, "ms_per_step": sl["s_per_step"] * 1e3,
+            "nominal_TeraEdges_per_s": edges / sl["s_per_step"] / 1e12,
+            "executed_TeraEdges_per_s": ex / sl["s_per_step"] / 1e12,
+            "rows_in_per_layer": rows_summary(sl["rows_trace"]), "n_active_final": sl["n_active"],
+            "fused_ms_per_layer": sl["sum_ms"] / max(sl["launches"], 1),
+            "roofline_frac": sl["sum_bytes"] / (sl["sum_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS if sl["sum_ms"] > 0 else None}
     print(json.dumps(out))
 
 

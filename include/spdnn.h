@@ -47,7 +47,10 @@ enum { SPDNN_HOST = 0, SPDNN_DEVICE = 1 }; /* where the arrays given to spdnn_cr
 
 /* Bytes of device memory spdnn_create needs for a model of L layers of N neurons
  * (re-laid weights of all layers, bias, and staging for one raw layer), whatever the
- * sparsity patterns are.  Patterns whose 1024-neuron blocks each touch a narrow range of
+ * sparsity patterns are.  The weights are held in the compact form whose footprint
+ * Section III-B-2 discusses (16-bit column index + 32-bit value per connection, stored
+ * lane-major as the transposed sliced-ELL of Section III-A-3) plus the tiling structures
+ * of Section III-A-2.  Patterns whose 1024-neuron blocks each touch a narrow range of
  * input columns need less: see spdnn_weights_bytes_for_window. */
 int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes);
 
@@ -60,7 +63,9 @@ int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes);
  * than the arena was sized for run a slower kernel. */
 int spdnn_weights_bytes_for_window(int32_t N, int32_t L, int32_t widest_window, size_t* bytes);
 
-/* Widest column range (in columns) of any 1024-neuron block of any layer -- when N is a
+/* The column footprint that the shared-memory tiling of Section III-A-2 stages per block of
+ * output neurons, measured over the whole model: the
+ * widest column range (in columns) of any 1024-neuron block of any layer -- when N is a
  * multiple of 2048, of any aligned pair of such blocks, which is what layers that run two
  * neurons per lane use.  idx as for spdnn_create.  scratch_dev: device memory, 256-byte aligned, at least N*32*4 + 2*N/128 +
  * 1024 bytes, contents scratch.  Blocks until done.  SPDNN_EINVAL on a column outside [0, N). */
@@ -68,13 +73,14 @@ int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t 
                        size_t scratch_bytes, void* hip_stream, int32_t* widest_window);
 
 /* Bytes of device memory spdnn_infer needs for up to max_batch rows: two feature
- * maps of max_batch x N floats (the ping-pong pair of Listing 1) plus row lists
- * and flags. */
+ * maps of max_batch x N floats (the ping-pong pair of Listing 1; Section III-B's
+ * footprint discussion counts the same two buffers) plus the row lists (`category`,
+ * `globalcategories` of Listing 1) and the per-row activity flags (`active`). */
 int spdnn_work_bytes(int32_t N, int32_t max_batch, size_t* bytes);
 
-/* Build a model (once per network; not part of inference time -- the paper's
- * tiling structures are likewise "constructed once prior to inference",
- * Section III-A-2).
+/* Build a model: once per network, outside inference time, like the tiling
+ * structures of Section III-A-2, which are also built before inference and reused
+ * by every call.
  *   idx, val : host arrays of L pointers.  idx[l][j*32+k] = input column of the k-th
  *              connection of output neuron j of layer l, in [0, N); val[l][j*32+k] its
  *              weight.  Duplicated columns within a neuron are allowed (they add up).
@@ -166,10 +172,31 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
                 size_t work_arena_bytes, int32_t* n_active_host, int32_t* active_rows_dev,
                 float* Y_final_dev);
 
-/* Release the handle (NULL is a no-op).  The arenas stay the caller's. */
+/* Inputs that stay in host memory, handed to the GPU in serial batches (Section III-B-2: the
+ * feature maps of all inputs need not fit the device; a batch is copied in while the one before
+ * it is being inferred).  Y0_host: batch x N floats in host memory, row-major, read during the
+ * call only; pinned memory (hipHostMalloc) lets the copies overlap the kernels, pageable memory
+ * works but serialises them.  rows_per_batch >= 1 rows go through the layers at a time.
+ *   work_arena : device memory, 256-byte aligned, >= spdnn_host_work_bytes(N, rows_per_batch):
+ *            two input buffers of rows_per_batch x N floats plus what spdnn_infer needs for
+ *            rows_per_batch rows; contents are scratch.
+ *   n_active_host, active_rows_dev (capacity batch), Y_final_dev (capacity batch*N, or NULL): as
+ *            for spdnn_infer, over the whole input -- rows are numbered as in Y0_host and come out
+ *            ascending.
+ * Results are those of one spdnn_infer over all rows (rows are independent, Eq. 1).  The copies
+ * run on a second HIP stream that the handle makes on first use (default priority); the call
+ * returns with both streams idle.  batch == 0 is valid. */
+int spdnn_host_work_bytes(int32_t N, int32_t rows_per_batch, size_t* bytes);
+int spdnn_infer_host(spdnn_t h, const float* Y0_host, int32_t batch, int32_t rows_per_batch,
+                     void* work_arena, size_t work_arena_bytes, int32_t* n_active_host,
+                     int32_t* active_rows_dev, float* Y_final_dev);
+
+/* Release the handle (NULL is a no-op): the end of the life of the structures that
+ * Section III-A-2 builds once per network.  The arenas stay the caller's. */
 int spdnn_destroy(spdnn_t h);
 
-/* Message of the last failure on the calling thread ("" if none). */
+/* Message of the last failure on the calling thread ("" if none).  Library plumbing; no
+ * counterpart in the paper. */
 const char* spdnn_last_error(void);
 
 /* Measurement aid (not part of the paper's method): with profiling on, spdnn_infer brackets
@@ -195,6 +222,8 @@ int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows
  * SPDNN_KERNEL_WIDE_PAIR  the same for five to eight stages;
  * SPDNN_KERNEL_WIDE_PAIR4 the same for two to four stages (the step lists of all stages stay in
  *                      registers).
+ * SPDNN_KERNEL_ROW2    one weight, N a multiple of 4096, windows wider than one stage but every
+ *                      4096-neuron unit within 16384 columns: four neurons per lane, tiles of two rows.
  * Returns SPDNN_EINVAL for a NULL handle or pointer or l outside [0, L). */
 /* (A layer of several passes reports the kernel of its first pass.) */
 #define SPDNN_KERNEL_SINGLE 0
@@ -203,16 +232,12 @@ int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows
 #define SPDNN_KERNEL_PAIR 3
 #define SPDNN_KERNEL_WIDE_PAIR 4
 #define SPDNN_KERNEL_WIDE_PAIR4 5
+#define SPDNN_KERNEL_ROW2 6
 int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind);
 
 /* Number of fused-kernel passes layer l takes: 1, or ceil(K/32) for a general layer whose
  * longest neuron has K > 32 connections. */
 int spdnn_layer_passes(spdnn_t h, int32_t l, int32_t* passes);
-
-/* Measurement aid: enqueue a plain device-to-device copy kernel of `bytes` bytes (a multiple
- * of 16; both pointers 16-byte aligned, device memory) on the given stream.  It reads and
- * writes exactly `bytes` each, which calibrates profiler traffic counters. */
-int spdnn_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -27,13 +27,15 @@ SPDNN_KERNEL_WIDE = 2
 SPDNN_KERNEL_PAIR = 3
 SPDNN_KERNEL_WIDE_PAIR = 4
 SPDNN_KERNEL_WIDE_PAIR4 = 5
+SPDNN_KERNEL_ROW2 = 6
 
 EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
-           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_copy_probe",
+           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile",
+           "spdnn_host_work_bytes", "spdnn_infer_host",
            "spdnn_weights_bytes_for_window", "spdnn_scan_windows", "spdnn_layer_kernel",
            "spdnn_csr_passes", "spdnn_create_csr", "spdnn_layer_passes", "spdnn_ooc_bytes", "spdnn_create_ooc")
 KERNEL_NAMES = {0: "fused_layer_kernel<false>", 1: "fused_layer_kernel<true>", 2: "fused_wide_kernel",
-                3: "fused_pair_kernel", 4: "fused_wide_pair_kernel", 5: "fused_wide_pair4_kernel"}
+                3: "fused_pair_kernel", 4: "fused_wide_pair_kernel", 5: "fused_wide_pair4_kernel", 6: "fused_row2_kernel"}
 
 
 class SpdnnError(RuntimeError):
@@ -61,7 +63,8 @@ def lib():
         L.spdnn_last_error.restype = ctypes.c_char_p
         L.spdnn_set_profiling.argtypes = [vp, i32]
         L.spdnn_get_profile.argtypes = [vp, i32, ctypes.POINTER(i32), vp, vp]
-        L.spdnn_copy_probe.argtypes = [vp, vp, sz, vp]
+        L.spdnn_host_work_bytes.argtypes = [i32, i32, ctypes.POINTER(sz)]
+        L.spdnn_infer_host.argtypes = [vp, vp, i32, i32, vp, sz, ctypes.POINTER(i32), vp, vp]
         L.spdnn_weights_bytes_for_window.argtypes = [i32, i32, i32, ctypes.POINTER(sz)]
         L.spdnn_scan_windows.argtypes = [i32, i32, ctypes.POINTER(vp), i32, vp, sz, vp, ctypes.POINTER(i32)]
         L.spdnn_layer_kernel.argtypes = [vp, i32, ctypes.POINTER(i32)]
@@ -215,9 +218,20 @@ def spdnn_layer_passes(h, l: int) -> int:
     return k.value
 
 
-def spdnn_copy_probe(dst_ptr, src_ptr, nbytes, stream=0) -> None:
-    _check(lib().spdnn_copy_probe(ctypes.c_void_p(int(dst_ptr)), ctypes.c_void_p(int(src_ptr)), nbytes,
-                                  ctypes.c_void_p(int(stream))))
+def spdnn_host_work_bytes(N: int, rows_per_batch: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().spdnn_host_work_bytes(N, rows_per_batch, ctypes.byref(out)))
+    return out.value
+
+
+def spdnn_infer_host(h, y0_host_ptr, batch, rows_per_batch, work_ptr, work_bytes, active_rows_ptr, y_final_ptr) -> int:
+    """Inputs in host memory, inferred in serial batches of rows_per_batch rows.  Returns n_active."""
+    n = ctypes.c_int32(-1)
+    _check(lib().spdnn_infer_host(ctypes.c_void_p(h), ctypes.c_void_p(int(y0_host_ptr)), batch, rows_per_batch,
+                                  ctypes.c_void_p(int(work_ptr)), work_bytes, ctypes.byref(n),
+                                  ctypes.c_void_p(int(active_rows_ptr)),
+                                  ctypes.c_void_p(int(y_final_ptr)) if y_final_ptr else None))
+    return n.value
 
 
 class Model:
@@ -335,45 +349,22 @@ class Model:
         return n, rows[:n], (Yf[:n] if want_Y else None)
 
     def infer_batched(self, Y0_host, rows_per_batch, want_Y=True):
-        """Inputs that stay in host memory, processed in serial batches (Section III-B-2): Y0_host is a
-        CPU float32 tensor [batch, N] (pinned memory lets the copies overlap the kernels); while one
-        batch is inferred the next one is copied to the GPU on a second stream.  Returns what infer()
-        returns for the whole input: (n_active, active_rows, Y or None), rows numbered as in Y0_host."""
+        """Inputs that stay in host memory, processed in serial batches (Section III-B-2) by
+        spdnn_infer_host: Y0_host is a CPU float32 tensor [batch, N] (pinned memory lets the copies
+        overlap the kernels).  Returns what infer() returns for the whole input."""
         torch = self.torch
         assert not Y0_host.is_cuda and Y0_host.dtype == torch.float32 and Y0_host.is_contiguous()
         batch = int(Y0_host.shape[0])
-        step = max(1, int(rows_per_batch))
+        assert Y0_host.shape[1] == self.N
+        step = max(1, min(int(rows_per_batch), max(batch, 1)))
         with torch.cuda.device(self.device):
-            copy = torch.cuda.Stream()   # default priority
-            bufs = [torch.empty((min(step, max(batch, 1)), self.N), dtype=torch.float32, device=self.device)
-                    for _ in range(2)]
-            ready = [torch.cuda.Event(), torch.cuda.Event()]
-
-            def fetch(k):   # batch k -> buffer k & 1, on the copy stream
-                lo = k * step
-                n = min(step, batch - lo)
-                with torch.cuda.stream(copy):
-                    bufs[k & 1][:n].copy_(Y0_host[lo:lo + n], non_blocking=True)
-                    ready[k & 1].record(copy)
-                return n
-
-            nb = (batch + step - 1) // step
-            rows_out, Y_out, total = [], [], 0
-            n_next = fetch(0) if nb else 0
-            for k in range(nb):
-                n_cur = n_next
-                ready[k & 1].synchronize()           # infer() runs on the model's stream and drains it,
-                if k + 1 < nb:                        # so the other buffer is free: start the next copy now
-                    n_next = fetch(k + 1)
-                n, rows, Y = self.infer(bufs[k & 1][:n_cur], want_Y=want_Y)
-                total += n
-                rows_out.append(rows + k * step)
-                if want_Y:
-                    Y_out.append(Y.clone())
-            copy.synchronize()
-            rows_all = torch.cat(rows_out) if rows_out else torch.empty(0, dtype=torch.int32, device=self.device)
-            Y_all = (torch.cat(Y_out) if Y_out else torch.empty((0, self.N), device=self.device)) if want_Y else None
-        return total, rows_all, Y_all
+            need = spdnn_host_work_bytes(self.N, step)
+            work = torch.empty(need, dtype=torch.uint8, device=self.device)
+            rows = torch.empty(max(batch, 1), dtype=torch.int32, device=self.device)
+            Yf = torch.empty((max(batch, 1), self.N), dtype=torch.float32, device=self.device) if want_Y else None
+            n = spdnn_infer_host(self.h, Y0_host.data_ptr(), batch, step, work.data_ptr(), need, rows.data_ptr(),
+                                 Yf.data_ptr() if want_Y else 0)
+        return n, rows[:n], (Yf[:n] if want_Y else None)
 
     def set_profiling(self, on=True):
         spdnn_set_profiling(self.h, on)

@@ -2,7 +2,9 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
+import sys
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
@@ -20,12 +22,47 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+NO_SCRATCH_KERNELS = ["fused_row2_kernel"]
+
+
+def _resource_usage(text):
+    """Per kernel (mangled name): the figures of the compiler's -Rpass-analysis=kernel-resource-usage remarks."""
+    out, cur = {}, None
+    for line in text.splitlines():
+        m = re.search(r"remark: +Function Name: (\S+)", line)
+        if m:
+            cur = out.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark: +([A-Za-z \[\]/]+): (\d+)", line)
+        if m and cur is not None:
+            cur[m.group(1).strip()] = int(m.group(2))
+    return out
+
+
 def build(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + SOURCES + ["-o", LIB]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage"] + list(extra) + SOURCES + ["-o", LIB]
     if verbose:
         print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
+    res = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    usage = _resource_usage(res.stderr)
+    if res.returncode != 0:
+        sys.stderr.write("\n".join(l for l in res.stderr.splitlines() if "kernel-resource-usage" not in l) + "\n")
+        raise subprocess.CalledProcessError(res.returncode, cmd)
+    # Kernels that issue their global loads as inline instructions keep the loaded values in registers
+    # the compiler believes to be ready; a spill between load and wait would save stale data.
+    for kernel in NO_SCRATCH_KERNELS:
+        hits = {k: v for k, v in usage.items() if kernel in k}
+        if not hits:
+            raise RuntimeError("build check: kernel %s not found in the compiler's resource report" % kernel)
+        for k, v in hits.items():
+            if v.get("ScratchSize [bytes/lane]", 0) != 0:
+                raise RuntimeError("build check: %s uses %d bytes of scratch per lane; it must use none"
+                                   % (k, v["ScratchSize [bytes/lane]"]))
+    if verbose:
+        for k, v in sorted(usage.items()):
+            if "fused_" in k:
+                print("%s: VGPRs %s, scratch %s B/lane" % (k, v.get("VGPRs"), v.get("ScratchSize [bytes/lane]")))
     subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", ORDER_HOST_LIB, ORDER_HOST_SRC],
                    check=True)
     return LIB

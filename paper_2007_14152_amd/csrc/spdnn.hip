@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdint>
@@ -42,15 +43,18 @@ int fail(int code, const char* fmt, ...) {
 constexpr size_t kAlign = 256;
 inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-constexpr int kLag = 2;  // the host runs at most this many layers ahead of the GPU
+constexpr int kLag = 4;  // the host runs at most this many layers ahead of the GPU
 // Set-up of device-resident layers runs on this many streams, a layer per stream in turn: its kernels
 // are single-wave, latency-bound searches that fill a fraction of the chip, so several layers overlap.
 constexpr int kSetupStreams = 4;
 
-enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2, kPair = 3, kWidePair = 4 };
+enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2, kPair = 3, kWidePair = 4, kRow2 = 5 };
 struct LayerDesc {
     spdnn::LayerWeights w;
     spdnn::WideWeights ww;
+    spdnn::Row2Weights r2;
+    // kRow2: one weight for the whole layer, N a multiple of 4096, every 4096-neuron unit's window within 16384
+    // columns but wider than one LDS stage: four neurons per lane, two rows per tile (fused_row2_kernel);
     // kSingle: every window fits one LDS stage; kStaged: 2 stages (or fallback); kWide: 3+ stages;
     // kPair: one stage, one weight for the whole layer, two output neurons per lane; kWidePair: the same for 3-8 stages
     int mode;
@@ -71,7 +75,7 @@ struct spdnn_model {
     std::vector<LayerDesc> layers;     // one per pass; a layer is one pass unless some neuron has more than 32 connections
     std::vector<int32_t> first_pass;   // L+1 entries: layer l is passes first_pass[l] .. first_pass[l+1]-1
     int* host_counts = nullptr;  // pinned, L+1 entries: rows active on entry to layer l
-    hipEvent_t lag_ev[kLag] = {nullptr, nullptr};
+    hipEvent_t lag_ev[kLag] = {};
     // out-of-core weights: pass p's block lives in host memory and is copied into device slot p & 1
     const char* ooc_host = nullptr;
     char* ooc_slot[2] = {nullptr, nullptr};
@@ -79,6 +83,9 @@ struct spdnn_model {
     hipStream_t ooc_stream = nullptr;
     hipEvent_t ooc_ready[2] = {nullptr, nullptr};  // the copy into the slot has landed
     hipEvent_t ooc_freed[2] = {nullptr, nullptr};  // the kernels that read the slot are done
+    // inputs in host memory (spdnn_infer_host): copy stream and "batch has landed" events, made on first use
+    hipStream_t in_stream = nullptr;
+    hipEvent_t in_ready[2] = {nullptr, nullptr};
     // profiling
     int profiling = 0;
     std::vector<hipEvent_t> t0, t1;
@@ -201,6 +208,8 @@ int allow_large_lds() {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair4_kernel<2, 32>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPair4LdsExtra));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_row2_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, spdnn::kRow2LdsBytes));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<16>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
@@ -304,7 +313,9 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     if (where == SPDNN_HOST) {
         std::memcpy(hb.data(), bias, sizeof(float) * N);
     } else {
-        HIP_TRY(hipMemcpy(hb.data(), bias, sizeof(float) * N, hipMemcpyDeviceToHost));
+        // on the model's stream: the caller may have produced the bias there
+        HIP_TRY(hipMemcpyAsync(hb.data(), bias, sizeof(float) * N, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
     }
     for (int32_t j = 0; j < N; ++j)
         if (!(hb[j] <= 0.0f) || !std::isfinite(hb[j]))
@@ -474,6 +485,35 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         HIP_TRY(hipStreamSynchronize(stream));
         const int pair = pair_info[0] == 1;        // two neurons per lane, single stage
         const bool wide_pair = pair_info[0] == 2;  // ... if the layer also fits the wide format
+        // one weight, every block wider than one stage, and every 4096-neuron unit within 16384 columns:
+        // four neurons per lane on two-row tiles; needs nothing of the other formats
+        bool row2 = wide_pair && !d.multi && N % spdnn::kUnit4 == 0 && d.ww.ps != nullptr;
+        for (int32_t u = 0; row2 && u < nblk / 4; ++u) {
+            int lo = 1 << 30, hi = 0;
+            for (int i = 0; i < 4; ++i) {
+                lo = std::min(lo, hw[(size_t)l * nblk + 4 * u + i].x);
+                hi = std::max(hi, hw[(size_t)l * nblk + 4 * u + i].x + hw[(size_t)l * nblk + 4 * u + i].y);
+            }
+            row2 = hi - lo <= spdnn::kRow2Cols;
+        }
+        if (row2) {
+            // the windows read back above are the blocks' own; pair_merge_kernel has widened them on the device to
+            // common windows of block pairs, whose unions per unit are the same
+            d.r2 = spdnn::Row2Weights{reinterpret_cast<const uint4*>(d.ww.ps), win_dev[l]};
+            const int groups = N / spdnn::kGroup32;
+            spdnn::row2_pack_kernel<<<(groups + spdnn::kRow2PackThreads - 1) / spdnn::kRow2PackThreads,
+                                      spdnn::kRow2PackThreads, 0, stream>>>(
+                di, N, win_dev[l], reinterpret_cast<uint16_t*>(const_cast<uint4*>(d.ww.ps)));
+            HIP_TRY(hipGetLastError());
+            d.mode = kRow2;
+            d.lds_cols = spdnn::kRow2Cols;
+            std::memcpy(&d.wuni, &pair_info[1], sizeof(float));
+            if (ooc)
+                HIP_TRY(hipMemcpyAsync(static_cast<char*>(host_arena) + (size_t)l * blk_bytes, m->ooc_slot[l & 1], blk_bytes,
+                                       hipMemcpyDeviceToHost, stream));
+            if (where == SPDNN_HOST) HIP_TRY(hipStreamSynchronize(stream));  // staging is reused
+            continue;
+        }
         if (pair)
             spdnn::balance_kernel<2><<<nblk / 2, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<2>), stream>>>(
                 di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
@@ -529,236 +569,22 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     return SPDNN_OK;
 }
 
-}  // namespace
 
-extern "C" {
-
-const char* spdnn_last_error(void) { return g_err.c_str(); }
-
-#ifdef SPDNN_TIMELINE
-int spdnn_debug_timeline(void* dst) {
-    return hipMemcpyFromSymbol(dst, HIP_SYMBOL(spdnn::spdnn_tl), sizeof(spdnn::spdnn_tl)) == hipSuccess ? 0 : -3;
-}
-#endif
-
-int spdnn_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream) {
-    if (!dst_dev || !src_dev || bytes % 16 || reinterpret_cast<uintptr_t>(dst_dev) % 16 ||
-        reinterpret_cast<uintptr_t>(src_dev) % 16)
-        return fail(SPDNN_EINVAL, "copy probe needs non-null 16-byte aligned buffers and a multiple of 16 bytes");
-    if (bytes == 0) return SPDNN_OK;
-    spdnn::copy_probe_kernel<<<8192, 256, 0, reinterpret_cast<hipStream_t>(hip_stream)>>>(
-        static_cast<const float4*>(src_dev), static_cast<float4*>(dst_dev), bytes / 16);
-    HIP_TRY(hipGetLastError());
-    return SPDNN_OK;
-}
-
-int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes) {
-    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
-    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
-    *bytes = arena_bytes_for(N, L, stages_of(N));
-    return SPDNN_OK;
-}
-
-int spdnn_weights_bytes_for_window(int32_t N, int32_t L, int32_t widest_window, size_t* bytes) {
-    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
-    if (!valid_n(N) || L < 1 || widest_window < 1)
-        return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1, widest_window >= 1");
-    *bytes = arena_bytes_for(N, L, stages_of(std::min(widest_window, N)));
-    return SPDNN_OK;
-}
-
-int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t where, void* scratch_dev,
-                       size_t scratch_bytes, void* hip_stream, int32_t* widest_window) {
-    if (!widest_window) return fail(SPDNN_EINVAL, "widest_window is NULL");
-    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
-    if (!idx || !scratch_dev) return fail(SPDNN_EINVAL, "null argument");
-    if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
-    const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
-    const size_t raw = up((size_t)N * spdnn::kNnz * sizeof(int32_t));
-    const size_t need = raw + up((size_t)nblk * sizeof(int2)) + up(sizeof(int));
-    if (scratch_bytes < need) return fail(SPDNN_ESIZE, "scan scratch has %zu bytes, %zu needed", scratch_bytes, need);
-    if (reinterpret_cast<uintptr_t>(scratch_dev) % kAlign) return fail(SPDNN_EINVAL, "scratch must be 256-byte aligned");
-    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-    char* base = static_cast<char*>(scratch_dev);
-    int32_t* st_idx = reinterpret_cast<int32_t*>(base);
-    int2* win = reinterpret_cast<int2*>(base + raw);
-    int* err = reinterpret_cast<int*>(base + raw + up((size_t)nblk * sizeof(int2)));
-    HIP_TRY(hipMemsetAsync(err, 0, 2 * sizeof(int), stream));  // error flag, widest window (unused here)
-    std::vector<int2> hw(nblk);
-    int widest = 4;
-    for (int32_t l = 0; l < L; ++l) {
-        if (!idx[l]) return fail(SPDNN_EINVAL, "idx[%d] is NULL", l);
-        const int32_t* di = idx[l];
-        if (where == SPDNN_HOST) {
-            HIP_TRY(hipMemcpyAsync(st_idx, idx[l], (size_t)N * spdnn::kNnz * sizeof(int32_t), hipMemcpyHostToDevice, stream));
-            di = st_idx;
-        }
-        spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win, err, err + 1);
-        HIP_TRY(hipGetLastError());
-        HIP_TRY(hipMemcpyAsync(hw.data(), win, sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
-        HIP_TRY(hipStreamSynchronize(stream));
-        for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[b].y);
-        // layers that run two neurons per lane give blocks 2u and 2u+1 their common window
-        if (N % (2 * spdnn::kBlk) == 0)
-            for (int32_t b = 0; b + 1 < nblk; b += 2) {
-                const int lo = std::min(hw[b].x, hw[b + 1].x);
-                const int hi = std::max(hw[b].x + hw[b].y, hw[b + 1].x + hw[b + 1].y);
-                widest = std::max(widest, hi - lo);
-            }
+// No entry point lets an exception out (a failed host allocation in a std::vector, for example).
+template <typename F>
+int guarded(F f) {
+    try {
+        return f();
+    } catch (const std::bad_alloc&) {
+        return fail(SPDNN_EHIP, "out of host memory");
+    } catch (...) {
+        return fail(SPDNN_EHIP, "unexpected exception");
     }
-    int herr = 0;
-    HIP_TRY(hipMemcpy(&herr, err, sizeof(int), hipMemcpyDeviceToHost));
-    if (herr) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
-    *widest_window = widest;
-    return SPDNN_OK;
 }
 
-int spdnn_work_bytes(int32_t N, int32_t max_batch, size_t* bytes) {
-    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
-    if (!valid_n(N) || max_batch < 0) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, batch >= 0");
-    *bytes = carve_work(N, max_batch, nullptr, nullptr);
-    return SPDNN_OK;
-}
-
-int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, const float* const* val,
-                 const float* bias, int32_t where, void* weights_arena, size_t weights_arena_bytes,
-                 void* hip_stream) {
-    if (!out) return fail(SPDNN_EINVAL, "out is NULL");
-    *out = nullptr;
-    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
-    if (!idx || !val || !bias || !weights_arena) return fail(SPDNN_EINVAL, "null argument");
-    if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
-    if (reinterpret_cast<uintptr_t>(weights_arena) % kAlign) return fail(SPDNN_EINVAL, "weights_arena must be 256-byte aligned");
-    for (int32_t l = 0; l < L; ++l)
-        if (!idx[l] || !val[l]) return fail(SPDNN_EINVAL, "idx[%d] or val[%d] is NULL", l, l);
-    return create_impl(out, N, L, std::vector<int32_t>((size_t)L, 1), nullptr, idx, val, bias, where, weights_arena,
-                       weights_arena_bytes, reinterpret_cast<hipStream_t>(hip_stream));
-}
-
-int spdnn_ooc_bytes(int32_t N, int32_t L, int32_t widest_window, size_t* device_bytes, size_t* host_bytes) {
-    if (!device_bytes || !host_bytes) return fail(SPDNN_EINVAL, "null argument");
-    if (!valid_n(N) || L < 1 || widest_window < 1)
-        return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1, widest_window >= 1");
-    const int cap = stages_of(std::min(widest_window, N));
-    *device_bytes = ooc_device_bytes_for(N, L, cap);
-    *host_bytes = (size_t)L * block_bytes(N, cap);
-    return SPDNN_OK;
-}
-
-int spdnn_create_ooc(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, const float* const* val,
-                     const float* bias, int32_t where, void* device_arena, size_t device_arena_bytes,
-                     void* host_arena, size_t host_arena_bytes, void* hip_stream) {
-    if (!out) return fail(SPDNN_EINVAL, "out is NULL");
-    *out = nullptr;
-    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
-    if (!idx || !val || !bias || !device_arena || !host_arena) return fail(SPDNN_EINVAL, "null argument");
-    if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
-    if (reinterpret_cast<uintptr_t>(device_arena) % kAlign || reinterpret_cast<uintptr_t>(host_arena) % 16)
-        return fail(SPDNN_EINVAL, "device_arena must be 256-byte aligned, host_arena 16-byte aligned");
-    for (int32_t l = 0; l < L; ++l)
-        if (!idx[l] || !val[l]) return fail(SPDNN_EINVAL, "idx[%d] or val[%d] is NULL", l, l);
-    return create_impl(out, N, L, std::vector<int32_t>((size_t)L, 1), nullptr, idx, val, bias, where, device_arena,
-                       device_arena_bytes, reinterpret_cast<hipStream_t>(hip_stream), host_arena, host_arena_bytes);
-}
-
-int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx, void* scratch_dev,
-                     size_t scratch_bytes, void* hip_stream, int32_t* passes, int32_t* total, int32_t* widest_window) {
-    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
-    if (!ptr || !scratch_dev || !total) return fail(SPDNN_EINVAL, "null argument");
-    if (widest_window && !idx) return fail(SPDNN_EINVAL, "widest_window needs idx");
-    std::vector<int32_t> po;
-    const int rc = scan_csr(N, L, ptr, scratch_dev, scratch_bytes, reinterpret_cast<hipStream_t>(hip_stream), &po, idx,
-                            widest_window);
-    if (rc != SPDNN_OK) return rc;
-    int64_t sum = 0;
-    for (int32_t l = 0; l < L; ++l) {
-        if (passes) passes[l] = po[l];
-        sum += po[l];
-    }
-    if (sum > INT32_MAX) return fail(SPDNN_EINVAL, "too many passes");
-    *total = (int32_t)sum;
-    return SPDNN_OK;
-}
-
-int spdnn_create_csr(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx,
-                     const float* const* val, const float* bias, void* weights_arena, size_t weights_arena_bytes,
-                     void* hip_stream) {
-    if (!out) return fail(SPDNN_EINVAL, "out is NULL");
-    *out = nullptr;
-    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
-    if (!ptr || !idx || !val || !bias || !weights_arena) return fail(SPDNN_EINVAL, "null argument");
-    if (reinterpret_cast<uintptr_t>(weights_arena) % kAlign) return fail(SPDNN_EINVAL, "weights_arena must be 256-byte aligned");
-    for (int32_t l = 0; l < L; ++l)
-        if (!ptr[l] || !idx[l] || !val[l]) return fail(SPDNN_EINVAL, "ptr[%d], idx[%d] or val[%d] is NULL", l, l, l);
-    // the arena's head serves as scratch for the scan; nothing else is in it yet
-    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-    std::vector<int32_t> passes_of;
-    const int rc = scan_csr(N, L, ptr, weights_arena, weights_arena_bytes, stream, &passes_of);
-    if (rc != SPDNN_OK) return rc;
-    return create_impl(out, N, L, passes_of, ptr, idx, val, bias, SPDNN_DEVICE, weights_arena, weights_arena_bytes, stream);
-}
-
-int spdnn_destroy(spdnn_t h) {
-    if (!h) return SPDNN_OK;
-    if (h->host_counts) (void)hipHostFree(h->host_counts);
-    for (int i = 0; i < kLag; ++i)
-        if (h->lag_ev[i]) (void)hipEventDestroy(h->lag_ev[i]);
-    for (int i = 0; i < 2; ++i) {
-        if (h->ooc_ready[i]) (void)hipEventDestroy(h->ooc_ready[i]);
-        if (h->ooc_freed[i]) (void)hipEventDestroy(h->ooc_freed[i]);
-    }
-    if (h->ooc_stream) (void)hipStreamDestroy(h->ooc_stream);
-    for (hipEvent_t e : h->t0) (void)hipEventDestroy(e);
-    for (hipEvent_t e : h->t1) (void)hipEventDestroy(e);
-    delete h;
-    return SPDNN_OK;
-}
-
-int spdnn_set_profiling(spdnn_t h, int32_t on) {
-    if (!h) return fail(SPDNN_EINVAL, "handle is NULL");
-    if (on && h->t0.empty()) {
-        h->t0.resize(h->L, nullptr);
-        h->t1.resize(h->L, nullptr);
-        for (int32_t l = 0; l < h->L; ++l) {
-            HIP_TRY(hipEventCreate(&h->t0[l]));
-            HIP_TRY(hipEventCreate(&h->t1[l]));
-        }
-    }
-    h->profiling = on ? 1 : 0;
-    return SPDNN_OK;
-}
-
-int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind) {
-    if (!h || !kind) return fail(SPDNN_EINVAL, "null argument");
-    if (l < 0 || l >= h->L) return fail(SPDNN_EINVAL, "layer %d outside [0, %d)", l, h->L);
-    static_assert(kSingle == SPDNN_KERNEL_SINGLE && kStaged == SPDNN_KERNEL_STAGED && kWide == SPDNN_KERNEL_WIDE &&
-                      kPair == SPDNN_KERNEL_PAIR && kWidePair == SPDNN_KERNEL_WIDE_PAIR,
-                  "layer modes are the header's kernel kinds");
-    const LayerDesc& d = h->layers[h->first_pass[l]];
-    *kind = (d.mode == kWidePair && d.pair4) ? SPDNN_KERNEL_WIDE_PAIR4 : d.mode;
-    return SPDNN_OK;
-}
-
-int spdnn_layer_passes(spdnn_t h, int32_t l, int32_t* passes) {
-    if (!h || !passes) return fail(SPDNN_EINVAL, "null argument");
-    if (l < 0 || l >= h->L) return fail(SPDNN_EINVAL, "layer %d outside [0, %d)", l, h->L);
-    *passes = h->first_pass[l + 1] - h->first_pass[l];
-    return SPDNN_OK;
-}
-
-int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows_in, float* fused_ms) {
-    if (!h || !layers_run) return fail(SPDNN_EINVAL, "null argument");
-    *layers_run = h->prof_layers;
-    const int32_t n = std::min<int32_t>(cap, h->prof_layers);
-    for (int32_t l = 0; l < n; ++l) {
-        if (rows_in) rows_in[l] = h->prof_rows[l];
-        if (fused_ms) fused_ms[l] = l < (int32_t)h->prof_ms.size() ? h->prof_ms[l] : 0.0f;
-    }
-    return SPDNN_OK;
-}
-
-int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena, size_t work_arena_bytes,
-                int32_t* n_active_host, int32_t* active_rows_dev, float* Y_final_dev) {
+// Argument checks shared by the inference entry points; batch == 0 is answered here (n_active = 0).
+int check_infer_args(spdnn_t h, const float* Y0_dev, int32_t batch, int32_t* n_active_host,
+                     const int32_t* active_rows_dev, const float* Y_final_dev) {
     if (!h) return fail(SPDNN_EINVAL, "handle is NULL");
     if (!n_active_host) return fail(SPDNN_EINVAL, "n_active_host is NULL");
     if (batch < 0) return fail(SPDNN_EINVAL, "batch < 0");
@@ -767,20 +593,31 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         *n_active_host = 0;
         return SPDNN_OK;
     }
-    if (!Y0_dev || !work_arena || !active_rows_dev) return fail(SPDNN_EINVAL, "null argument");
+    if (!Y0_dev || !active_rows_dev) return fail(SPDNN_EINVAL, "null argument");
     if (reinterpret_cast<uintptr_t>(Y0_dev) % 16) return fail(SPDNN_EINVAL, "Y0 must be 16-byte aligned");
     if (Y_final_dev && reinterpret_cast<uintptr_t>(Y_final_dev) % 16) return fail(SPDNN_EINVAL, "Y_final must be 16-byte aligned");
-    if (reinterpret_cast<uintptr_t>(work_arena) % kAlign) return fail(SPDNN_EINVAL, "work_arena must be 256-byte aligned");
-    const int32_t N = h->N, L = h->L;
-    const size_t need = carve_work(N, batch, nullptr, nullptr);
-    if (work_arena_bytes < need) return fail(SPDNN_ESIZE, "work arena has %zu bytes, %zu needed", work_arena_bytes, need);
-    WorkView wv;
-    carve_work(N, batch, static_cast<char*>(work_arena), &wv);
-    hipStream_t s = h->stream;
+    return SPDNN_OK;
+}
 
-    spdnn::init_lists_kernel<<<(batch + 255) / 256, 256, 0, s>>>(wv.cat[0], wv.gid[0], wv.flags[0], wv.flags[1], wv.count[0],
-                                                                 batch);
+// All L layers on `batch` rows whose first row has the original number row_offset; wv = the carved
+// work memory.  Returns with the model's stream drained, also when a HIP call fails half way.
+int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv, int32_t row_offset,
+               int32_t* n_active_host, int32_t* active_rows_dev, float* Y_final_dev) {
+    const int32_t N = h->N, L = h->L;
+    hipStream_t s = h->stream;
+    // Kernels may be queued when a later HIP call fails: nothing of this call is left running on return.
+    struct DrainModel {
+        hipStream_t s;
+        bool armed = true;
+        ~DrainModel() {
+            if (armed) (void)hipStreamSynchronize(s);
+        }
+    } drain_model{s};
+
+    for (int32_t l = 1; l <= L; ++l) h->host_counts[l] = -1;  // "not reported yet"
     h->host_counts[0] = batch;
+    spdnn::init_lists_kernel<<<(batch + 255) / 256, 256, 0, s>>>(wv.cat[0], wv.gid[0], wv.flags[0], wv.flags[1], wv.count[0],
+                                                                 batch, row_offset);
     int32_t bound = batch;  // upper bound of the rows active at the layer being launched
     int32_t run = 0;        // layers launched
     // Out-of-core weights (Section III-B-1): pass p runs from device slot p & 1.  The copy stream fills
@@ -810,15 +647,16 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
             const LayerDesc& d = h->layers[p];
             if (h->ooc_host) HIP_TRY(hipStreamWaitEvent(s, h->ooc_ready[p & 1], 0));
             // launch shape: one workgroup per CU; the rows are cut into Q chunks per output block
-            const int32_t ngroups = (bound + spdnn::kRows - 1) / spdnn::kRows;
+            const int32_t rows_per_group = d.mode == kRow2 ? spdnn::kRows2 : spdnn::kRows;
+            const int32_t ngroups = (bound + rows_per_group - 1) / rows_per_group;
             // kPair: the workgroups' column blocks are pairs of output blocks
             const bool two = d.mode == kPair || d.mode == kWidePair;
-            const int32_t ncb = two ? h->nblk / 2 : h->nblk;
+            const int32_t ncb = d.mode == kRow2 ? h->nblk / 4 : two ? h->nblk / 2 : h->nblk;
             // Workgroups that read the same rows go to one XCD (32 CUs, one L2).  In a wide layer every
             // column block reads whole rows: as many of them as possible share an XCD, so that a row is
             // fetched from memory once, not once per XCD.
             int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1) : h->G;
-            if (d.mode == kWide || d.mode == kWidePair)
+            if (d.mode == kWide || d.mode == kWidePair || d.mode == kRow2)
                 for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
                     if (ncb % g == 0) {
                         G = g;
@@ -829,12 +667,15 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
             const int32_t units = (ncb / G) * Q;
             const int32_t grid = (units + 7) / 8 * 8 * G;
             const size_t lds = spdnn::tile_pair_bytes((d.lds_cols + 255) / 256 * 256);  // whole waves of 256 columns
-            if (d.multi && d.mode == kStaged)
+            if (d.mode == kRow2)
+                spdnn::fused_row2_kernel<<<grid, spdnn::kBlk, spdnn::kRow2LdsBytes, s>>>(
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.r2, h->bias_dev, N, ncb, G, Q, d.wuni);
+            else if (d.multi && d.mode == kStaged)
                 spdnn::fused_layer_kernel<true, true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, h->G, Q, d.pass);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, G, Q, d.pass);
             else if (d.multi)
                 spdnn::fused_layer_kernel<false, true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, h->G, Q, d.pass);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, G, Q, d.pass);
             else if (d.mode == kPair)
                 spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
                     Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
@@ -849,16 +690,16 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
                     Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWide && d.ww.nstage > 8)
                 spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, h->nblk, h->G, Q);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q);
             else if (d.mode == kWide)
                 spdnn::fused_wide_kernel<16><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, h->nblk, h->G, Q);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q);
             else if (d.mode == kStaged)
                 spdnn::fused_layer_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, h->G, Q);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, G, Q);
             else
                 spdnn::fused_layer_kernel<false><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, h->G, Q);
+                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, G, Q);
             if (h->ooc_host) {  // the slot is free once this kernel is done: refill it with pass p + 2
                 HIP_TRY(hipEventRecord(h->ooc_freed[p & 1], s));
                 if (p + 2 < P) {
@@ -874,16 +715,33 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(h->lag_ev[l % kLag], s));
         run = l + 1;
-        // feedback with bounded lag: wait for layer l+1-kLag, whose survivor count bounds all later ones
+        // Feedback with bounded lag: the survivor count of layer l+1-kLag bounds all later ones.  The
+        // compaction kernel stores it to pinned host memory, which is polled here; the layer's event is
+        // looked at only so that a failed launch ends the wait.
         if (l + 1 >= kLag) {
             const int32_t lr = l + 1 - kLag;
-            HIP_TRY(hipEventSynchronize(h->lag_ev[lr % kLag]));
-            bound = h->host_counts[lr + 1];
+            volatile int* slot = h->host_counts + lr + 1;
+            int32_t c = *slot;
+            for (uint32_t spin = 1; c < 0; ++spin) {
+                if ((spin & 1023u) == 0) {
+                    const hipError_t q = hipEventQuery(h->lag_ev[lr % kLag]);
+                    if (q == hipSuccess) {  // the layer is done: its count has been stored
+                        c = *slot;
+                        if (c < 0) return fail(SPDNN_EHIP, "layer %d finished without reporting its active rows", lr);
+                        break;
+                    }
+                    if (q != hipErrorNotReady) HIP_TRY(q);
+                }
+                c = *slot;
+            }
+            std::atomic_thread_fence(std::memory_order_acquire);
+            bound = c;
             if (bound == 0) break;
         }
     }
     HIP_TRY(hipStreamSynchronize(s));
     const int32_t n = h->host_counts[run];
+    if (n < 0) return fail(SPDNN_EHIP, "layer %d finished without reporting its active rows", run - 1);
     *n_active_host = n;
     if (n > 0) {
         const int32_t lf = run - 1;  // == L-1 here: rows survive only if every layer ran
@@ -900,6 +758,7 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         }
         HIP_TRY(hipStreamSynchronize(s));
     }
+    drain_model.armed = false;
     if (h->profiling) {
         h->prof_layers = run;
         h->prof_ms.assign(run, 0.0f);
@@ -910,6 +769,313 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         }
     }
     return SPDNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* spdnn_last_error(void) { return g_err.c_str(); }
+
+int spdnn_weights_bytes(int32_t N, int32_t L, size_t* bytes) {
+    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
+    if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+    *bytes = arena_bytes_for(N, L, stages_of(N));
+    return SPDNN_OK;
+}
+
+int spdnn_weights_bytes_for_window(int32_t N, int32_t L, int32_t widest_window, size_t* bytes) {
+    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
+    if (!valid_n(N) || L < 1 || widest_window < 1)
+        return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1, widest_window >= 1");
+    *bytes = arena_bytes_for(N, L, stages_of(std::min(widest_window, N)));
+    return SPDNN_OK;
+}
+
+int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t where, void* scratch_dev,
+                       size_t scratch_bytes, void* hip_stream, int32_t* widest_window) {
+    return guarded([&]() -> int {
+        if (!widest_window) return fail(SPDNN_EINVAL, "widest_window is NULL");
+        if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+        if (!idx || !scratch_dev) return fail(SPDNN_EINVAL, "null argument");
+        if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
+        const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
+        const size_t raw = up((size_t)N * spdnn::kNnz * sizeof(int32_t));
+        const size_t need = raw + up((size_t)nblk * sizeof(int2)) + up(sizeof(int));
+        if (scratch_bytes < need) return fail(SPDNN_ESIZE, "scan scratch has %zu bytes, %zu needed", scratch_bytes, need);
+        if (reinterpret_cast<uintptr_t>(scratch_dev) % kAlign) return fail(SPDNN_EINVAL, "scratch must be 256-byte aligned");
+        hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+        char* base = static_cast<char*>(scratch_dev);
+        int32_t* st_idx = reinterpret_cast<int32_t*>(base);
+        int2* win = reinterpret_cast<int2*>(base + raw);
+        int* err = reinterpret_cast<int*>(base + raw + up((size_t)nblk * sizeof(int2)));
+        HIP_TRY(hipMemsetAsync(err, 0, 2 * sizeof(int), stream));  // error flag, widest window (unused here)
+        std::vector<int2> hw(nblk);
+        int widest = 4;
+        for (int32_t l = 0; l < L; ++l) {
+            if (!idx[l]) return fail(SPDNN_EINVAL, "idx[%d] is NULL", l);
+            const int32_t* di = idx[l];
+            if (where == SPDNN_HOST) {
+                HIP_TRY(hipMemcpyAsync(st_idx, idx[l], (size_t)N * spdnn::kNnz * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+                di = st_idx;
+            }
+            spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win, err, err + 1);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(hipMemcpyAsync(hw.data(), win, sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
+            HIP_TRY(hipStreamSynchronize(stream));
+            for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[b].y);
+            // layers that run two neurons per lane give blocks 2u and 2u+1 their common window
+            if (N % (2 * spdnn::kBlk) == 0)
+                for (int32_t b = 0; b + 1 < nblk; b += 2) {
+                    const int lo = std::min(hw[b].x, hw[b + 1].x);
+                    const int hi = std::max(hw[b].x + hw[b].y, hw[b + 1].x + hw[b + 1].y);
+                    widest = std::max(widest, hi - lo);
+                }
+        }
+        int herr = 0;
+        HIP_TRY(hipMemcpy(&herr, err, sizeof(int), hipMemcpyDeviceToHost));
+        if (herr) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
+        *widest_window = widest;
+        return SPDNN_OK;
+    });
+}
+
+int spdnn_work_bytes(int32_t N, int32_t max_batch, size_t* bytes) {
+    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
+    if (!valid_n(N) || max_batch < 0) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, batch >= 0");
+    *bytes = carve_work(N, max_batch, nullptr, nullptr);
+    return SPDNN_OK;
+}
+
+int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, const float* const* val,
+                 const float* bias, int32_t where, void* weights_arena, size_t weights_arena_bytes,
+                 void* hip_stream) {
+    return guarded([&]() -> int {
+        if (!out) return fail(SPDNN_EINVAL, "out is NULL");
+        *out = nullptr;
+        if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+        if (!idx || !val || !bias || !weights_arena) return fail(SPDNN_EINVAL, "null argument");
+        if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
+        if (reinterpret_cast<uintptr_t>(weights_arena) % kAlign) return fail(SPDNN_EINVAL, "weights_arena must be 256-byte aligned");
+        for (int32_t l = 0; l < L; ++l)
+            if (!idx[l] || !val[l]) return fail(SPDNN_EINVAL, "idx[%d] or val[%d] is NULL", l, l);
+        return create_impl(out, N, L, std::vector<int32_t>((size_t)L, 1), nullptr, idx, val, bias, where, weights_arena,
+                           weights_arena_bytes, reinterpret_cast<hipStream_t>(hip_stream));
+    });
+}
+
+int spdnn_ooc_bytes(int32_t N, int32_t L, int32_t widest_window, size_t* device_bytes, size_t* host_bytes) {
+    if (!device_bytes || !host_bytes) return fail(SPDNN_EINVAL, "null argument");
+    if (!valid_n(N) || L < 1 || widest_window < 1)
+        return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1, widest_window >= 1");
+    const int cap = stages_of(std::min(widest_window, N));
+    *device_bytes = ooc_device_bytes_for(N, L, cap);
+    *host_bytes = (size_t)L * block_bytes(N, cap);
+    return SPDNN_OK;
+}
+
+int spdnn_create_ooc(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx, const float* const* val,
+                     const float* bias, int32_t where, void* device_arena, size_t device_arena_bytes,
+                     void* host_arena, size_t host_arena_bytes, void* hip_stream) {
+    return guarded([&]() -> int {
+        if (!out) return fail(SPDNN_EINVAL, "out is NULL");
+        *out = nullptr;
+        if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+        if (!idx || !val || !bias || !device_arena || !host_arena) return fail(SPDNN_EINVAL, "null argument");
+        if (where != SPDNN_HOST && where != SPDNN_DEVICE) return fail(SPDNN_EINVAL, "where must be SPDNN_HOST or SPDNN_DEVICE");
+        if (reinterpret_cast<uintptr_t>(device_arena) % kAlign || reinterpret_cast<uintptr_t>(host_arena) % 16)
+            return fail(SPDNN_EINVAL, "device_arena must be 256-byte aligned, host_arena 16-byte aligned");
+        for (int32_t l = 0; l < L; ++l)
+            if (!idx[l] || !val[l]) return fail(SPDNN_EINVAL, "idx[%d] or val[%d] is NULL", l, l);
+        return create_impl(out, N, L, std::vector<int32_t>((size_t)L, 1), nullptr, idx, val, bias, where, device_arena,
+                           device_arena_bytes, reinterpret_cast<hipStream_t>(hip_stream), host_arena, host_arena_bytes);
+    });
+}
+
+int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx, void* scratch_dev,
+                     size_t scratch_bytes, void* hip_stream, int32_t* passes, int32_t* total, int32_t* widest_window) {
+    return guarded([&]() -> int {
+        if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+        if (!ptr || !scratch_dev || !total) return fail(SPDNN_EINVAL, "null argument");
+        if (widest_window && !idx) return fail(SPDNN_EINVAL, "widest_window needs idx");
+        std::vector<int32_t> po;
+        const int rc = scan_csr(N, L, ptr, scratch_dev, scratch_bytes, reinterpret_cast<hipStream_t>(hip_stream), &po, idx,
+                                widest_window);
+        if (rc != SPDNN_OK) return rc;
+        int64_t sum = 0;
+        for (int32_t l = 0; l < L; ++l) {
+            if (passes) passes[l] = po[l];
+            sum += po[l];
+        }
+        if (sum > INT32_MAX) return fail(SPDNN_EINVAL, "too many passes");
+        *total = (int32_t)sum;
+        return SPDNN_OK;
+    });
+}
+
+int spdnn_create_csr(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx,
+                     const float* const* val, const float* bias, void* weights_arena, size_t weights_arena_bytes,
+                     void* hip_stream) {
+    return guarded([&]() -> int {
+        if (!out) return fail(SPDNN_EINVAL, "out is NULL");
+        *out = nullptr;
+        if (!valid_n(N) || L < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, L >= 1");
+        if (!ptr || !idx || !val || !bias || !weights_arena) return fail(SPDNN_EINVAL, "null argument");
+        if (reinterpret_cast<uintptr_t>(weights_arena) % kAlign) return fail(SPDNN_EINVAL, "weights_arena must be 256-byte aligned");
+        for (int32_t l = 0; l < L; ++l)
+            if (!ptr[l] || !idx[l] || !val[l]) return fail(SPDNN_EINVAL, "ptr[%d], idx[%d] or val[%d] is NULL", l, l, l);
+        // the arena's head serves as scratch for the scan; nothing else is in it yet
+        hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+        std::vector<int32_t> passes_of;
+        const int rc = scan_csr(N, L, ptr, weights_arena, weights_arena_bytes, stream, &passes_of);
+        if (rc != SPDNN_OK) return rc;
+        return create_impl(out, N, L, passes_of, ptr, idx, val, bias, SPDNN_DEVICE, weights_arena, weights_arena_bytes, stream);
+    });
+}
+
+int spdnn_destroy(spdnn_t h) {
+    return guarded([&]() -> int {
+        if (!h) return SPDNN_OK;
+        if (h->host_counts) (void)hipHostFree(h->host_counts);
+        for (int i = 0; i < kLag; ++i)
+            if (h->lag_ev[i]) (void)hipEventDestroy(h->lag_ev[i]);
+        for (int i = 0; i < 2; ++i) {
+            if (h->ooc_ready[i]) (void)hipEventDestroy(h->ooc_ready[i]);
+            if (h->ooc_freed[i]) (void)hipEventDestroy(h->ooc_freed[i]);
+        }
+        if (h->ooc_stream) (void)hipStreamDestroy(h->ooc_stream);
+        for (int i = 0; i < 2; ++i)
+            if (h->in_ready[i]) (void)hipEventDestroy(h->in_ready[i]);
+        if (h->in_stream) (void)hipStreamDestroy(h->in_stream);
+        for (hipEvent_t e : h->t0) (void)hipEventDestroy(e);
+        for (hipEvent_t e : h->t1) (void)hipEventDestroy(e);
+        delete h;
+        return SPDNN_OK;
+    });
+}
+
+int spdnn_set_profiling(spdnn_t h, int32_t on) {
+    return guarded([&]() -> int {
+        if (!h) return fail(SPDNN_EINVAL, "handle is NULL");
+        if (on && h->t0.empty()) {
+            h->t0.resize(h->L, nullptr);
+            h->t1.resize(h->L, nullptr);
+            for (int32_t l = 0; l < h->L; ++l) {
+                HIP_TRY(hipEventCreate(&h->t0[l]));
+                HIP_TRY(hipEventCreate(&h->t1[l]));
+            }
+        }
+        h->profiling = on ? 1 : 0;
+        return SPDNN_OK;
+    });
+}
+
+int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind) {
+    if (!h || !kind) return fail(SPDNN_EINVAL, "null argument");
+    if (l < 0 || l >= h->L) return fail(SPDNN_EINVAL, "layer %d outside [0, %d)", l, h->L);
+    static_assert(kSingle == SPDNN_KERNEL_SINGLE && kStaged == SPDNN_KERNEL_STAGED && kWide == SPDNN_KERNEL_WIDE &&
+                      kPair == SPDNN_KERNEL_PAIR && kWidePair == SPDNN_KERNEL_WIDE_PAIR,
+                  "layer modes are the header's kernel kinds");
+    const LayerDesc& d = h->layers[h->first_pass[l]];
+    *kind = (d.mode == kWidePair && d.pair4) ? SPDNN_KERNEL_WIDE_PAIR4 : d.mode == kRow2 ? SPDNN_KERNEL_ROW2 : d.mode;
+    return SPDNN_OK;
+}
+
+int spdnn_layer_passes(spdnn_t h, int32_t l, int32_t* passes) {
+    if (!h || !passes) return fail(SPDNN_EINVAL, "null argument");
+    if (l < 0 || l >= h->L) return fail(SPDNN_EINVAL, "layer %d outside [0, %d)", l, h->L);
+    *passes = h->first_pass[l + 1] - h->first_pass[l];
+    return SPDNN_OK;
+}
+
+int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows_in, float* fused_ms) {
+    return guarded([&]() -> int {
+        if (!h || !layers_run) return fail(SPDNN_EINVAL, "null argument");
+        *layers_run = h->prof_layers;
+        const int32_t n = std::min<int32_t>(cap, h->prof_layers);
+        for (int32_t l = 0; l < n; ++l) {
+            if (rows_in) rows_in[l] = h->prof_rows[l];
+            if (fused_ms) fused_ms[l] = l < (int32_t)h->prof_ms.size() ? h->prof_ms[l] : 0.0f;
+        }
+        return SPDNN_OK;
+    });
+}
+
+int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena, size_t work_arena_bytes,
+                int32_t* n_active_host, int32_t* active_rows_dev, float* Y_final_dev) {
+    return guarded([&]() -> int {
+        const int rc = check_infer_args(h, Y0_dev, batch, n_active_host, active_rows_dev, Y_final_dev);
+        if (rc != SPDNN_OK || batch == 0) return rc;
+        if (!work_arena) return fail(SPDNN_EINVAL, "null argument");
+        if (reinterpret_cast<uintptr_t>(work_arena) % kAlign) return fail(SPDNN_EINVAL, "work_arena must be 256-byte aligned");
+        const size_t need = carve_work(h->N, batch, nullptr, nullptr);
+        if (work_arena_bytes < need) return fail(SPDNN_ESIZE, "work arena has %zu bytes, %zu needed", work_arena_bytes, need);
+        WorkView wv;
+        carve_work(h->N, batch, static_cast<char*>(work_arena), &wv);
+        return infer_impl(h, Y0_dev, batch, wv, 0, n_active_host, active_rows_dev, Y_final_dev);
+    });
+}
+
+int spdnn_host_work_bytes(int32_t N, int32_t rows_per_batch, size_t* bytes) {
+    if (!bytes) return fail(SPDNN_EINVAL, "bytes is NULL");
+    if (!valid_n(N) || rows_per_batch < 1) return fail(SPDNN_EINVAL, "need 32 <= N <= 65536, N %% 4 == 0, rows_per_batch >= 1");
+    *bytes = 2 * up((size_t)rows_per_batch * N * sizeof(float)) + carve_work(N, rows_per_batch, nullptr, nullptr);
+    return SPDNN_OK;
+}
+
+int spdnn_infer_host(spdnn_t h, const float* Y0_host, int32_t batch, int32_t rows_per_batch, void* work_arena,
+                     size_t work_arena_bytes, int32_t* n_active_host, int32_t* active_rows_dev, float* Y_final_dev) {
+    return guarded([&]() -> int {
+        if (!h) return fail(SPDNN_EINVAL, "handle is NULL");
+        if (!n_active_host) return fail(SPDNN_EINVAL, "n_active_host is NULL");
+        if (batch < 0 || rows_per_batch < 1) return fail(SPDNN_EINVAL, "need batch >= 0 and rows_per_batch >= 1");
+        h->prof_layers = 0;
+        *n_active_host = 0;
+        if (batch == 0) return SPDNN_OK;
+        if (!Y0_host || !work_arena || !active_rows_dev) return fail(SPDNN_EINVAL, "null argument");
+        if (Y_final_dev && reinterpret_cast<uintptr_t>(Y_final_dev) % 16) return fail(SPDNN_EINVAL, "Y_final must be 16-byte aligned");
+        if (reinterpret_cast<uintptr_t>(work_arena) % kAlign) return fail(SPDNN_EINVAL, "work_arena must be 256-byte aligned");
+        const int32_t N = h->N;
+        const int32_t step = std::min(rows_per_batch, batch);
+        const size_t in_bytes = up((size_t)step * N * sizeof(float));
+        const size_t need = 2 * in_bytes + carve_work(N, step, nullptr, nullptr);
+        if (work_arena_bytes < need) return fail(SPDNN_ESIZE, "work arena has %zu bytes, %zu needed", work_arena_bytes, need);
+        char* base = static_cast<char*>(work_arena);
+        float* in[2] = {reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + in_bytes)};
+        WorkView wv;
+        carve_work(N, step, base + 2 * in_bytes, &wv);
+        if (!h->in_stream) {  // made on first use: a second stream of default priority, and one event per input buffer
+            HIP_TRY(hipStreamCreateWithFlags(&h->in_stream, hipStreamNonBlocking));
+            for (int i = 0; i < 2; ++i) HIP_TRY(hipEventCreateWithFlags(&h->in_ready[i], hipEventDisableTiming));
+        }
+        // whatever happens below, the copy stream is idle again when the call returns
+        struct Drain {
+            hipStream_t cs;
+            ~Drain() { (void)hipStreamSynchronize(cs); }
+        } drain{h->in_stream};
+        const int32_t nb = (batch + step - 1) / step;
+        auto rows_of = [&](int32_t k) { return std::min(step, batch - k * step); };
+        auto fetch = [&](int32_t k) -> hipError_t {  // batch k -> input buffer k & 1, on the copy stream
+            hipError_t e = hipMemcpyAsync(in[k & 1], Y0_host + (size_t)k * step * N, sizeof(float) * (size_t)rows_of(k) * N,
+                                          hipMemcpyHostToDevice, h->in_stream);
+            return e != hipSuccess ? e : hipEventRecord(h->in_ready[k & 1], h->in_stream);
+        };
+        HIP_TRY(fetch(0));
+        int32_t total = 0;
+        for (int32_t k = 0; k < nb; ++k) {
+            HIP_TRY(hipStreamWaitEvent(h->stream, h->in_ready[k & 1], 0));
+            // the other buffer was last read by batch k-1, whose inference has drained the model's stream:
+            // its refill runs under the kernels of batch k
+            if (k + 1 < nb) HIP_TRY(fetch(k + 1));
+            int32_t n = 0;
+            const int rc = infer_impl(h, in[k & 1], rows_of(k), wv, k * step, &n, active_rows_dev + total,
+                                      Y_final_dev ? Y_final_dev + (size_t)total * N : nullptr);
+            if (rc != SPDNN_OK) return rc;
+            total += n;
+        }
+        *n_active_host = total;
+        return SPDNN_OK;
+    });
 }
 
 }  // extern "C"

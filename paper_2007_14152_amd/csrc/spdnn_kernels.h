@@ -32,21 +32,6 @@ constexpr float kClip = 32.0f;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Optional per-phase cycle stamps of a few waves of workgroup 0 (development aid,
-// compiled in only with -DSPDNN_TIMELINE).
-#ifdef SPDNN_TIMELINE
-__device__ unsigned long long spdnn_tl[4][64][8];
-#define SPDNN_TL(T_, P_)                                                                     \
-    do {                                                                                     \
-        if (blockIdx.x == SPDNN_TIMELINE && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) % 5 == 0 && (T_) < 64) \
-            spdnn_tl[(threadIdx.x >> 6) / 5][(T_)][(P_)] = clock64();                        \
-    } while (0)
-#else
-#define SPDNN_TL(T_, P_) \
-    do {                 \
-    } while (0)
-#endif
-
 struct LayerWeights {
     const uint16_t* rel;  // [nblk][32][kBlk] stage << 12 | LDS slot of (column - c_lo) within the stage
     const float* val;     // [nblk][32][kBlk]
@@ -401,11 +386,12 @@ __device__ __forceinline__ void fma_block8ps(float (&acc)[4], uint32_t p0, uint3
 // XCDs (8 of them, each with its own L2); the G column blocks that read the same rows
 // through overlapping windows get ids that are equal modulo 8, so they share one L2.
 // *count_ptr = number of active rows A; a workgroup takes the row groups [g0, g1) of
-// ceil(A / 4).  Returns false for a workgroup with nothing to do.
+// ceil(A / rows_per_group).  Returns false for a workgroup with nothing to do.
 struct WorkItem {
     int cb, A, g0, g1;
 };
-__device__ __forceinline__ bool my_work(int ncb, int G, int Q, const int* __restrict__ count_ptr, WorkItem& w) {
+__device__ __forceinline__ bool my_work(int ncb, int G, int Q, const int* __restrict__ count_ptr, WorkItem& w,
+                                        int rows_per_group = kRows) {
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;
     const int unit = (slot / G) * 8 + xcd;
@@ -415,7 +401,7 @@ __device__ __forceinline__ bool my_work(int ncb, int G, int Q, const int* __rest
     const int q = unit / ngrp;
     w.cb = (unit - q * ngrp) * G + sub;
     w.A = *count_ptr;
-    const int ngroups = (w.A + kRows - 1) / kRows;
+    const int ngroups = (w.A + rows_per_group - 1) / rows_per_group;
     const int per = (ngroups + Q - 1) / Q;
     w.g0 = q * per;
     w.g1 = min(ngroups, w.g0 + per);
@@ -709,18 +695,13 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         constexpr int P = decltype(Ptag)::value;
         const int gi = MULTI ? t / nstage : t;
         const int s = MULTI ? t - gi * nstage : 0;
-        SPDNN_TL(t, 0);
         if (t + 2 < T) fetch_rows(t + 2);
         compute(Ptag, s, std::integral_constant<int, 0>{});
-        SPDNN_TL(t, 2);
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
         if (t + 2 < T) load_tile(t + 2);
-        SPDNN_TL(t, 4);
         compute(Ptag, s, std::integral_constant<int, 16>{});
         if (s == nstage - 1) epilogue(g0 + gi);
-        SPDNN_TL(t, 5);
         __syncthreads();
-        SPDNN_TL(t, 6);
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
@@ -991,7 +972,6 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
     // buffer and the loads of the tile after it, then the other 8 connections.
     auto step = [&](int t, auto Ptag, float (&a)[kRows]) {
         constexpr int P = decltype(Ptag)::value;
-        SPDNN_TL(t, 0);
         if (t + 2 < T) fetch_rows(t + 2);
         if (nb > 0) {
             uint32_t o8[8];
@@ -1003,10 +983,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
             }
             fma_block8<P>(a, o8, v8);
         }
-        SPDNN_TL(t, 2);
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
         if (t + 2 < T) load_tile(t + 2);
-        SPDNN_TL(t, 4);
         if (S > 8 && nb > 1) {
             uint32_t o8[8];
             float v8[8];
@@ -1017,9 +995,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
             }
             fma_block8<P>(a, o8, v8);
         }
-        SPDNN_TL(t, 5);
         __syncthreads();
-        SPDNN_TL(t, 6);
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
@@ -1442,6 +1418,10 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     }
 }
 
+}  // namespace spdnn
+#include "spdnn_row2.h"
+namespace spdnn {
+
 // Compact form of a wide layer's steps for the two-neurons-per-lane wide kernels: the 16-bit
 // LDS slot of every step, 0xFFFF where the step carries no connection (weight 0 in pk).  One
 // thread per 16-byte output (eight steps of one lane); S = steps per stage (16 or 32).
@@ -1601,13 +1581,15 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict
     }
 }
 
-// Start of an inference: identity lists, both flag buffers cleared, A = batch.
+// Start of an inference: identity lists, both flag buffers cleared, A = batch.  Row i of the
+// input carries the original row number row_offset + i (inputs handed over in serial batches,
+// Section III-B-2, are numbered through).
 __global__ void init_lists_kernel(int* __restrict__ cat, int* __restrict__ gid, uint8_t* __restrict__ flags0,
-                                  uint8_t* __restrict__ flags1, int* __restrict__ count, int batch) {
+                                  uint8_t* __restrict__ flags1, int* __restrict__ count, int batch, int row_offset) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < batch) {
         cat[i] = i;
-        gid[i] = i;
+        gid[i] = row_offset + i;
         flags0[i] = 0;
         flags1[i] = 0;
     }
@@ -2122,13 +2104,6 @@ __global__ __launch_bounds__(kOrderThreads) void wide_pack_kernel(const int32_t*
                     pk[entry(step, wave0 + lane_of_group(set, l))] = make_uint2(q, 0u);  // slot q lies in quad q
         }
     }
-}
-
-// Plain copy, 16 bytes per lane and iteration: a traffic yardstick for profiler
-// counters (known bytes in, known bytes out).
-__global__ void copy_probe_kernel(const float4* __restrict__ src, float4* __restrict__ dst, size_t n16) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
-        dst[i] = src[i];
 }
 
 }  // namespace spdnn

@@ -62,4 +62,12 @@ SPDNN_HD inline uint32_t store_group(uint32_t c) {  // of stage-local column c
     return (((t >> 6) << 2) | set_of_lane(t & 63u)) << 2 | (c & 3u);
 }
 
+// Tile of the two-rows-per-entry kernel (fused_row2_kernel): an entry is 8 bytes, the two rows'
+// values of one column, at byte 8 * row2_pos(c) for stage-local column c.  Staging lane t owns columns
+// 4t..4t+3 and writes them with 8-byte stores, one per column; a ds_write_b64 / ds_read_b64 is served
+// half a wave (32 lanes) at a time from 32 pairs of banks, so within every span of 128 columns
+// (32 lanes) the entries are transposed: column-in-lane | lane-in-half-wave.  An entry's bank pair is
+// row2_pos(c) mod 32 = (c >> 2) mod 32.
+SPDNN_HD inline uint32_t row2_pos(uint32_t c) { return (c & ~127u) | ((c & 3u) << 5) | ((c >> 2) & 31u); }
+
 }  // namespace spdnn

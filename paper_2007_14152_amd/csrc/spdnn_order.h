@@ -203,4 +203,141 @@ SPDNN_HD inline int order_cost(QuadAt quad_at) {
     return total;
 }
 
+// The same ordering problem for the kernel that reads two rows per LDS entry (ds_read_b64):
+// gfx950 serves such a read half a wave at a time -- lanes 0..31, then 32..63 -- from 32 "pairs"
+// of neighbouring 4-byte banks (measured with a pairwise-conflict probe), so a group is 32
+// neighbouring neurons and a step is conflict-free when their 32 entries fall in 32 different
+// bank pairs.  Every lane has exactly 32 connections and places one per step.
+//
+// Per step: a maximum bipartite matching pairs <-> lanes by augmenting paths (breadth-first),
+// pairs offered by urgency -- first those that hold at least as many unplaced connections as
+// there are steps left (they must be served in every remaining step or cost an extra cycle
+// later), then by what they still hold.  A lane left without a pair of its own shares the least
+// used pair it can.  Cost of a group = sum over the steps of the largest pair multiplicity;
+// the lower bound is max(32, the busiest pair's total).
+constexpr int kGroup32 = 32;
+struct Order32Scratch {
+    uint8_t pair[kGroup32][32];   // bank pair of connection k of lane l
+    uint32_t unplaced[kGroup32];  // connections of lane l not placed yet (bit k)
+    uint32_t adj[32];             // lanes that still have a connection in pair q
+    uint16_t remq[32];            // connections not placed yet in pair q, whole group
+    int8_t lane_of_pair[32];      // matching of the current step
+    int8_t pair_of_lane[kGroup32];
+    int8_t parent[kGroup32];      // pair from which the search reached lane l
+    uint8_t queue[36];
+    uint8_t mult[32];             // lanes using pair q in the current step
+};
+
+SPDNN_HD inline int ctz32(uint32_t m) {
+    int n = 0;
+    while (!(m & 1u)) {
+        m >>= 1;
+        ++n;
+    }
+    return n;
+}
+
+// pair_of(l, k): bank pair (0..31) of connection k of lane l.  emit(l, step, k): connection k of
+// lane l goes to step `step`; called exactly once per (l, k), once per (l, step).
+template <typename PairOf, typename Emit>
+SPDNN_HD inline void order_group32(Order32Scratch& S, PairOf pair_of, Emit emit) {
+    for (int l = 0; l < kGroup32; ++l) {
+        for (int k = 0; k < 32; ++k) S.pair[l][k] = (uint8_t)(pair_of(l, k) & 31u);
+        S.unplaced[l] = 0xFFFFFFFFu;
+    }
+    for (int step = 0; step < 32; ++step) {
+        const int left = 32 - step;
+        for (int q = 0; q < 32; ++q) {
+            S.adj[q] = 0;
+            S.remq[q] = 0;
+            S.lane_of_pair[q] = -1;
+            S.mult[q] = 0;
+        }
+        for (int l = 0; l < kGroup32; ++l) {
+            S.pair_of_lane[l] = -1;
+            uint32_t m = S.unplaced[l];
+            while (m) {
+                const int k = ctz32(m);
+                m &= m - 1;
+                const int q = S.pair[l][k];
+                S.adj[q] |= 1u << l;
+                S.remq[q]++;
+            }
+        }
+        uint32_t done = 0;  // pairs already offered
+        for (int r = 0; r < 32; ++r) {
+            int q0 = -1, best = -1;
+            for (int q = 0; q < 32; ++q) {
+                if ((done >> q) & 1u) continue;
+                const int key = (S.remq[q] >= left ? 4096 : 0) + S.remq[q];
+                if (key > best) {
+                    best = key;
+                    q0 = q;
+                }
+            }
+            done |= 1u << q0;
+            if (S.remq[q0] == 0) break;  // the rest are empty too
+            // breadth-first search for an augmenting path from pair q0 to a lane without a pair
+            int head = 0, tail = 0, found = -1;
+            uint32_t seen = 0;
+            S.queue[tail++] = (uint8_t)q0;
+            while (head < tail && found < 0) {
+                const int q = S.queue[head++];
+                uint32_t cand = S.adj[q] & ~seen;
+                while (cand) {
+                    const int l = ctz32(cand);
+                    cand &= cand - 1;
+                    seen |= 1u << l;
+                    S.parent[l] = (int8_t)q;
+                    if (S.pair_of_lane[l] < 0) {
+                        found = l;
+                        break;
+                    }
+                    S.queue[tail++] = (uint8_t)S.pair_of_lane[l];  // a lane is seen once: at most 32 entries follow q0
+                }
+            }
+            if (found < 0) continue;
+            for (int cur = found;;) {
+                const int q = S.parent[cur];
+                const int next = S.lane_of_pair[q];  // the lane that gives q up (meaningful unless q == q0)
+                S.lane_of_pair[q] = (int8_t)cur;
+                S.pair_of_lane[cur] = (int8_t)q;
+                if (q == q0) break;
+                cur = next;
+            }
+        }
+        for (int l = 0; l < kGroup32; ++l)
+            if (S.pair_of_lane[l] >= 0) S.mult[S.pair_of_lane[l]]++;
+        for (int l = 0; l < kGroup32; ++l) {
+            if (S.pair_of_lane[l] >= 0) continue;
+            int bq = -1, bkey = 1 << 30;
+            for (int q = 0; q < 32; ++q) {
+                if (!((S.adj[q] >> l) & 1u)) continue;
+                const int key = (int)S.mult[q] * 65536 - (int)S.remq[q];
+                if (key < bkey) {
+                    bkey = key;
+                    bq = q;
+                }
+            }
+            S.pair_of_lane[l] = (int8_t)bq;
+            S.mult[bq]++;
+        }
+        for (int l = 0; l < kGroup32; ++l) {
+            const int q = S.pair_of_lane[l];
+            uint32_t m = S.unplaced[l];
+            int k = -1;
+            while (m) {
+                const int kk = ctz32(m);
+                m &= m - 1;
+                if (S.pair[l][kk] == q) {
+                    k = kk;
+                    break;
+                }
+            }
+            S.unplaced[l] &= ~(1u << k);
+            emit(l, step, k);
+        }
+    }
+}
+
 }  // namespace spdnn

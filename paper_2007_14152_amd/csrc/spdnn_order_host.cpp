@@ -31,6 +31,41 @@ int spdnn_order_cost_host(const uint8_t* quads) {
     return spdnn::order_cost([&](int l, int step) -> unsigned { return quads[l * 32 + step]; });
 }
 
+// pairs: [32][32] bank pair (0..31) of every connection of 32 neighbouring neurons.
+// step_of: [32][32] out, step at which connection k of lane l is placed.
+// Returns the cost (sum over the 32 steps of the largest pair multiplicity), -1 if a lane got two
+// connections in one step or a connection was never placed.
+int spdnn_order_group32_host(const uint8_t* pairs, uint8_t* step_of) {
+    static spdnn::Order32Scratch S;
+    uint8_t at[32][32];  // pair used by lane l at step s
+    for (int i = 0; i < 32 * 32; ++i) {
+        step_of[i] = 255;
+        (&at[0][0])[i] = 255;
+    }
+    bool bad = false;
+    spdnn::order_group32(
+        S, [&](int l, int k) -> unsigned { return pairs[l * 32 + k]; },
+        [&](int l, int step, int k) {
+            if (k < 0 || k > 31 || step_of[l * 32 + k] != 255 || at[l][step] != 255) {
+                bad = true;
+                return;
+            }
+            step_of[l * 32 + k] = (uint8_t)step;
+            at[l][step] = pairs[l * 32 + k];
+        });
+    if (bad) return -1;
+    int total = 0;
+    for (int step = 0; step < 32; ++step) {
+        int m[32] = {0}, mx = 0;
+        for (int l = 0; l < 32; ++l) {
+            if (at[l][step] == 255) return -1;
+            if (++m[at[l][step]] > mx) mx = m[at[l][step]];
+        }
+        total += mx;
+    }
+    return total;
+}
+
 // Tile layout functions, one call per value.
 uint32_t spdnn_tile_offset_host(uint32_t slot) { return spdnn::tile_offset(slot); }
 uint32_t spdnn_tile_pair_bytes_host(uint32_t cols) { return spdnn::tile_pair_bytes(cols); }
@@ -39,5 +74,6 @@ uint32_t spdnn_set_of_lane_host(uint32_t lane) { return spdnn::set_of_lane(lane)
 uint32_t spdnn_rank_in_set_host(uint32_t lane) { return spdnn::rank_in_set(lane); }
 uint32_t spdnn_col_slot_host(uint32_t c) { return spdnn::col_slot(c); }
 uint32_t spdnn_store_group_host(uint32_t c) { return spdnn::store_group(c); }
+uint32_t spdnn_row2_pos_host(uint32_t c) { return spdnn::row2_pos(c); }
 
 }  // extern "C"

@@ -1,0 +1,357 @@
+// a1 for layers whose blocks read (nearly) whole feature rows, with one weight for the whole
+// layer: two rows per LDS entry, four output neurons per lane.
+//
+// A uniform pattern at N = 16384 makes every block of output neurons read the whole row, so
+// what a workgroup stages is the row, whatever neurons it owns, and the bytes the CUs pull out
+// of L2 are (row bytes) x (workgroups per row).  This kernel makes the workgroup as large as
+// the register file allows -- 4096 neurons, four per lane, their 32 LDS addresses packed two
+// per register (64 registers) -- so a row is staged by N / 4096 workgroups.  The tile is the
+// whole column window (up to 16384 columns) of TWO rows, 8 bytes per column (128 KB of LDS):
+// every connection is one ds_read_b64 feeding two FMAs, a neuron takes exactly its 32 steps
+// (no stages, hence no padding steps), and the sum runs in the order the set-up chose for the
+// LDS banks (row2_pack_kernel), one fused multiply-add per connection, bias last.
+//
+// One tile fills the LDS, so there is one buffer: the next tile waits in registers and is written
+// between two barriers once every wave is done reading; that write phase is not hidden (about a
+// sixth of a step).  The loads of the next tile are issued in four bursts spread over the compute
+// phase, as instructions with a scalar base (no vector registers for addresses; the wait for them is
+// written out by hand).  The staged values must never be spilled between a load and that wait --
+// the compiler does not know they arrive late -- so the build checks that this kernel uses no
+// scratch memory.
+#pragma once
+
+namespace spdnn {
+
+constexpr int kRows2 = 2;            // feature rows per tile
+constexpr int kUnit4 = 4 * kBlk;     // output neurons per workgroup
+constexpr int kRow2Cols = 16384;     // columns a tile holds
+constexpr int kRow2Bursts = 4;       // bursts in which a tile's eight loads per lane are issued (2, 4 or 8; measured: 4)
+constexpr int kRow2Seg = 4096;       // columns staged per lane and segment (1024 lanes x 4 columns)
+constexpr int kRow2TileBytes = kRow2Cols * kRows2 * 4;
+constexpr int kRow2LdsBytes = kRow2TileBytes + kUnit4 * 4;  // the tile, then the unit's biases
+
+struct Row2Weights {
+    const uint4* codes;  // [nunit][4][4][kBlk]: neuron slot s of lane t, steps 8o .. 8o+7 as 16-bit tile positions
+                         // (row2_pos of the column inside the unit's window)
+    const int2* win;     // [nblk] per 1024-neuron block {c_lo, ncols}; a unit's window is the union of its four
+};
+
+// Column window of unit u: the union of its four blocks' windows (c_lo a multiple of 4).
+__device__ __forceinline__ int2 row2_window(const int2* __restrict__ win, int u) {
+    int lo = 1 << 30, hi = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int2 w = win[4 * u + i];
+        lo = min(lo, w.x);
+        hi = max(hi, w.x + w.y);
+    }
+    return make_int2(lo, hi - lo);
+}
+
+// 16 connections of one neuron: acc[r] = fma(tile[col_k][r], w, acc[r]), k = 0..15 in that order.
+// p[i] holds the (LDS byte address >> 3) of connections 2i and 2i+1 in its halves; an SDWA shift
+// turns a half into the byte address, written into the first register of the read's own
+// destination; s3 (scalar) holds 3.  Two reads in flight in v124..v127 (with 16 waves per CU the LDS
+// stays busy at this depth, and the kernel needs every other register).
+__device__ __forceinline__ void fma_row2_block16(float (&acc)[kRows2], const uint32_t* p, float w, uint32_t s3) {
+    asm volatile(
+        "v_lshlrev_b32_sdwa v120, %[s3], %[p0] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b64 v[120:121], v120\n\t"
+        "v_lshlrev_b32_sdwa v122, %[s3], %[p0] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b64 v[122:123], v122\n\t"
+        "v_lshlrev_b32_sdwa v124, %[s3], %[p1] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b64 v[124:125], v124\n\t"
+        "v_lshlrev_b32_sdwa v126, %[s3], %[p1] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b64 v[126:127], v126\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_lshlrev_b32_sdwa v120, %[s3], %[p2] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b64 v[120:121], v120\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v122\n\t"
+        "v_fmac_f32 %[a1], %[w], v123\n\t"
+        "v_lshlrev_b32_sdwa v122, %[s3], %[p2] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b64 v[122:123], v122\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_lshlrev_b32_sdwa v124, %[s3], %[p3] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b64 v[124:125], v124\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v126\n\t"
+        "v_fmac_f32 %[a1], %[w], v127\n\t"
+        "v_lshlrev_b32_sdwa v126, %[s3], %[p3] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b64 v[126:127], v126\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_lshlrev_b32_sdwa v120, %[s3], %[p4] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b64 v[120:121], v120\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v122\n\t"
+        "v_fmac_f32 %[a1], %[w], v123\n\t"
+        "v_lshlrev_b32_sdwa v122, %[s3], %[p4] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b64 v[122:123], v122\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_lshlrev_b32_sdwa v124, %[s3], %[p5] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b64 v[124:125], v124\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v126\n\t"
+        "v_fmac_f32 %[a1], %[w], v127\n\t"
+        "v_lshlrev_b32_sdwa v126, %[s3], %[p5] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b64 v[126:127], v126\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "v_lshlrev_b32_sdwa v120, %[s3], %[p6] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b64 v[120:121], v120\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v122\n\t"
+        "v_fmac_f32 %[a1], %[w], v123\n\t"
+        "v_lshlrev_b32_sdwa v122, %[s3], %[p6] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b64 v[122:123], v122\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "v_lshlrev_b32_sdwa v124, %[s3], %[p7] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "ds_read_b64 v[124:125], v124\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v126\n\t"
+        "v_fmac_f32 %[a1], %[w], v127\n\t"
+        "v_lshlrev_b32_sdwa v126, %[s3], %[p7] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b64 v[126:127], v126\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %[a0], %[w], v120\n\t"
+        "v_fmac_f32 %[a1], %[w], v121\n\t"
+        "s_waitcnt lgkmcnt(2)\n\t"
+        "v_fmac_f32 %[a0], %[w], v122\n\t"
+        "v_fmac_f32 %[a1], %[w], v123\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %[a0], %[w], v124\n\t"
+        "v_fmac_f32 %[a1], %[w], v125\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "v_fmac_f32 %[a0], %[w], v126\n\t"
+        "v_fmac_f32 %[a1], %[w], v127\n\t"
+        : [a0] "+v"(acc[0]), [a1] "+v"(acc[1])
+        : [p0] "v"(p[0]), [p1] "v"(p[1]), [p2] "v"(p[2]), [p3] "v"(p[3]), [p4] "v"(p[4]), [p5] "v"(p[5]), [p6] "v"(p[6]),
+          [p7] "v"(p[7]), [w] "s"(w), [s3] "s"(s3)
+        : "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "memory");
+}
+
+// 4x4 transpose inside every quartet of lanes (two DPP exchanges): lane 4q+i ends up with
+// element i of lanes 4q .. 4q+3, in y0..y3.
+__device__ __forceinline__ void quartet_transpose(float& y0, float& y1, float& y2, float& y3, int lane) {
+    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
+    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
+    const bool b0 = lane & 1, b1 = lane & 2;
+    {
+        const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
+        const float r0 = xor2(s0), r1 = xor2(s1);
+        y0 = b1 ? r0 : y0;
+        y1 = b1 ? r1 : y1;
+        y2 = b1 ? y2 : r0;
+        y3 = b1 ? y3 : r1;
+    }
+    {
+        const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
+        const float r0 = xor1(s0), r1 = xor1(s1);
+        y0 = b0 ? r0 : y0;
+        y1 = b0 ? y1 : r0;
+        y2 = b0 ? r1 : y2;
+        y3 = b0 ? y3 : r1;
+    }
+}
+
+__global__ __launch_bounds__(kBlk) void fused_row2_kernel(
+    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
+    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, Row2Weights w,
+    const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
+    extern __shared__ float4 lds4[];
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    using lds_f2 = __attribute__((address_space(3))) f32x2;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+
+    WorkItem wi;  // my unit and my groups of two rows
+    if (!my_work(nunit, G, Q, count_ptr, wi, kRows2)) return;
+    const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
+    const int2 win = row2_window(w.win, u);
+    const int c_lo = win.x;
+    const int ncols = win.y;  // <= kRow2Cols, a multiple of 4
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
+    uint32_t s3 = 3;
+    asm volatile("" : "+s"(s3));  // the shift count of fma_row2_block32, kept in a scalar register
+
+    // step lists of my four neurons (u * 4096 + s * 1024 + tid), two LDS addresses (>> 3) per register
+    uint32_t p[4][16];
+    {
+        const uint32_t base8 = lds_base >> 3;
+        const uint32_t both = base8 | (base8 << 16);
+        const uint4* q = w.codes + (size_t)u * 16 * kBlk + tid;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const uint4 v = q[(s * 4 + o) * kBlk];
+                p[s][o * 4 + 0] = v.x + both;
+                p[s][o * 4 + 1] = v.y + both;
+                p[s][o * 4 + 2] = v.z + both;
+                p[s][o * 4 + 3] = v.w + both;
+            }
+    }
+
+    // Staging.  Lane t owns columns 4t .. 4t+3 of each 4096-column segment of the window: one
+    // 16-byte load per row and segment, one 8-byte LDS entry (the two rows of a column) per column.
+    // Addresses are a scalar row base plus a 32-bit lane offset.
+    const int nseg = (ncols + kRow2Seg - 1) / kRow2Seg;
+    f32x4 st[4][kRows2];
+    const uint32_t st_addr = lds_base + 8u * (((4u * tid) & ~127u) | (tid & 31u));  // entry of column 4t; +256 per column
+    const int cat_last = cat[A - 1];
+    const int T = g1 - g0;
+    // Byte offset of my four columns inside a segment: 16 * tid, except that in a narrower last segment
+    // the lanes past the window re-read its last columns.  The segment's own offset is scalar.
+    const int last_cols = ncols - (nseg - 1) * kRow2Seg;  // columns of the last segment (a multiple of 4, >= 4)
+    const uint32_t off_full = 16u * (uint32_t)tid;
+    const uint32_t off_last = 4u * (uint32_t)min(4 * tid, last_cols - 4);
+    const char* ld_row[kRows2] = {nullptr, nullptr};  // row bases of the tile being loaded, at the window's first column
+    auto tile_rows = [&](int t) {
+        const int2 c2 = *reinterpret_cast<const int2*>(cat + (size_t)(g0 + t) * kRows2);
+        const int row0 = (g0 + t) * kRows2;
+        ld_row[0] = reinterpret_cast<const char*>(Yin + (size_t)c2.x * N + c_lo);
+        ld_row[1] = reinterpret_cast<const char*>(Yin + (size_t)(row0 + 1 < A ? c2.y : cat_last) * N + c_lo);
+    };
+    // One 16-byte load per lane: scalar base + 32-bit lane offset.  Written as an instruction so that the
+    // addresses stay out of the vector registers; the compiler therefore does not know that the result
+    // arrives later, and the wait for it is written out in the main loop (wait_tile).
+    auto load_piece = [&](int i) {  // piece i = row i & 1 of segment i >> 1; i is a constant wherever this is called
+        const int s = i >> 1, r = i & 1;
+        if (s < nseg) {
+            const char* base = ld_row[r] + (size_t)s * (kRow2Seg * 4);
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(st[s][r]) : "v"(s == nseg - 1 ? off_last : off_full), "s"(base) : "memory");
+        }
+    };
+    auto wait_tile = [&]() {  // every load (and store) issued so far has completed; the staged values may be touched
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int s = 0; s < 4; ++s) asm volatile("" : "+v"(st[s][0]), "+v"(st[s][1]));
+    };
+    // The eight loads of a tile are issued back to back.  The memory pipeline accepts them only as fast as
+    // L2 delivers (about 22 bytes per clock and CU), so the last wave starts computing some 6000 clocks
+    // after the first; spreading the loads over the compute phase instead was measured slower (every wave
+    // then waits at every load).
+    auto load_tile = [&](int t) {
+        tile_rows(t);
+        load_piece(0);
+        load_piece(1);
+        load_piece(2);
+        load_piece(3);
+        load_piece(4);
+        load_piece(5);
+        load_piece(6);
+        load_piece(7);
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (s < nseg) {
+                const uint32_t a = st_addr + (uint32_t)s * (kRow2Seg * 8u);
+                *reinterpret_cast<lds_f2*>(a + 0 * 256) = f32x2{st[s][0].x, st[s][1].x};
+                *reinterpret_cast<lds_f2*>(a + 1 * 256) = f32x2{st[s][0].y, st[s][1].y};
+                *reinterpret_cast<lds_f2*>(a + 2 * 256) = f32x2{st[s][0].z, st[s][1].z};
+                *reinterpret_cast<lds_f2*>(a + 3 * 256) = f32x2{st[s][0].w, st[s][1].w};
+            }
+        }
+    };
+
+    // my four biases wait in LDS behind the tile (registers are what this kernel is short of)
+    using lds_f1 = __attribute__((address_space(3))) float;
+    const uint32_t bias_addr = lds_base + kRow2TileBytes + 4u * tid;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) *reinterpret_cast<lds_f1*>(bias_addr + s * (4 * kBlk)) = bias[u * kUnit4 + s * kBlk + tid];
+    // Output: after the transpose lane 4q+i holds row (i & 1) of neurons 4q..4q+3 of slot 2h + (i >> 1).
+    // Byte offset of that 16-byte piece from the start of the row group's first output row, for h = 0:
+    const uint32_t out_off = 4u * ((uint32_t)(lane & 1) * (uint32_t)N + (uint32_t)(u * kUnit4 + (tid & ~3)) +
+                                   (uint32_t)((lane >> 1) & 1) * kBlk);
+
+    load_tile(0);
+    wait_tile();
+    store_tile();
+    __syncthreads();
+    for (int t = 0; t < T; ++t) {
+        const int row0 = (g0 + t) * kRows2;
+        const int nlive = min(kRows2, A - row0);
+        char* out_row = reinterpret_cast<char*>(Yout + (size_t)row0 * N);
+        unsigned pos = 0;
+        const bool more = t + 1 < T;
+        if (more) tile_rows(t + 1);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {  // two neuron slots at a time: compute, then Eq. 1's bias, ReLU and clip
+            // The loads of the next tile go out in kRow2Bursts bursts spread over the compute phase, one before
+            // every (8 / kRow2Bursts)-th block of 16 connections.  A wave that issues loads is stuck until the
+            // memory pipeline has taken them, which it does only as fast as L2 delivers (about 22 bytes per
+            // clock and CU): all eight loads back to back leave the last wave 6000 clocks behind the first.
+            float a0[kRows2] = {0.0f, 0.0f}, a1[kRows2] = {0.0f, 0.0f};
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {  // block b of this pair of slots = block 4h + b of the step
+                constexpr int every = 8 / kRow2Bursts;
+                if (more && (4 * h + b) % every == 0) {
+#pragma unroll
+                    for (int i = 0; i < every; ++i) load_piece(4 * h + b + i);
+                }
+                fma_row2_block16(b < 2 ? a0 : a1, &p[2 * h + (b >> 1)][8 * (b & 1)], wuni, s3);
+            }
+            const float b0 = *reinterpret_cast<const lds_f1*>(bias_addr + (2 * h) * (4 * kBlk));
+            const float b1 = *reinterpret_cast<const lds_f1*>(bias_addr + (2 * h + 1) * (4 * kBlk));
+            float y0 = fminf(fmaxf(a0[0] + b0, 0.0f), kClip), y1 = fminf(fmaxf(a0[1] + b0, 0.0f), kClip);
+            float y2 = fminf(fmaxf(a1[0] + b1, 0.0f), kClip), y3 = fminf(fmaxf(a1[1] + b1, 0.0f), kClip);
+            pos |= (__builtin_amdgcn_ballot_w64(y0 > 0.0f || y2 > 0.0f) != 0ull ? 1u : 0u) |
+                   (__builtin_amdgcn_ballot_w64(y1 > 0.0f || y3 > 0.0f) != 0ull ? 2u : 0u);
+            quartet_transpose(y0, y1, y2, y3, lane);
+            if ((lane & 1) < nlive)
+                *reinterpret_cast<float4*>(out_row + (out_off + (uint32_t)h * (2u * kBlk * 4u))) = make_float4(y0, y1, y2, y3);
+        }
+        if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;  // lane r raises row r's flag
+        __syncthreads();  // every wave is done reading tile t
+        if (more) {
+            wait_tile();
+            store_tile();
+            __syncthreads();
+        }
+    }
+}
+
+// a0 for fused_row2_kernel: one thread per group of 32 neighbouring neurons of one neuron slot
+// (the lanes a ds_read_b64 serves together).  Orders the group's connections so that in every
+// step the 32 lanes read 32 different bank pairs whenever possible (order_group32) and writes the
+// steps as 16-bit tile positions, eight per 16-byte word, lane-major.
+// The search diverges from group to group, so the groups do not share a wave: one thread per workgroup,
+// and the layer's N / 32 groups spread over all CUs.
+constexpr int kRow2PackThreads = 1;
+__global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32_t* __restrict__ idx, int N,
+                                                                     const int2* __restrict__ win,
+                                                                     uint16_t* __restrict__ codes) {
+    __shared__ Order32Scratch scratch[kRow2PackThreads];
+    const int g = blockIdx.x * kRow2PackThreads + threadIdx.x;  // group: unit, slot, 32 lanes
+    const int groups_per_unit = kUnit4 / kGroup32;
+    const int u = g / groups_per_unit;
+    if (u * kUnit4 >= N) return;
+    const int in_unit = g - u * groups_per_unit;
+    const int s = in_unit / (kBlk / kGroup32);
+    const int lane0 = (in_unit - s * (kBlk / kGroup32)) * kGroup32;
+    const int c_lo = row2_window(win, u).x;
+    auto pos_of = [&](int l, int k) -> uint32_t {  // out-of-range columns were reported; keep them harmless
+        const int c = idx[((size_t)u * kUnit4 + s * kBlk + lane0 + l) * kNnz + k];
+        return row2_pos((c < 0 || c >= N) ? 0u : (uint32_t)(c - c_lo) & (kRow2Cols - 1));
+    };
+    order_group32(
+        scratch[threadIdx.x], [&](int l, int k) -> unsigned { return pos_of(l, k) & 31u; },
+        [&](int l, int step, int k) {
+            const size_t word = ((size_t)(u * 4 + s) * 4 + (step >> 3)) * kBlk + lane0 + l;
+            codes[word * 8 + (step & 7)] = (uint16_t)pos_of(l, k);
+        });
+}
+
+}  // namespace spdnn

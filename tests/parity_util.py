@@ -10,7 +10,10 @@ import synth
 
 RTOL = 1e-5
 ATOL = 1e-6
-
+# On the benchmark configurations (and the sustained-activity variants of them) the fragile rule may
+# excuse at most this share of the compared rows (measured there: 0 to 0.03 %); tests of those workloads
+# pass it as max_fragile_frac.  Random toy models, where exact-zero pre-activations are common, do not.
+MAX_FRAGILE_FRAC = 1e-3
 
 def close(a, b):
     a = np.asarray(a, dtype=np.float64)
@@ -33,11 +36,15 @@ def gpu_infer(idx, val, bias, Y0, device="cuda:0", model=None):
     return out
 
 
-def check_against_oracle(ref, n, rows, Y, row_ids=None, what=""):
+def check_against_oracle(ref, n, rows, Y, row_ids=None, what="", max_fragile_frac=None):
     """ref: OracleResult for the rows row_ids (None = all rows, ids 0..batch-1).
     n, rows, Y: the library's output restricted to the same rows (original ids)."""
     ids = np.arange(len(ref.fragile_layer)) if row_ids is None else np.asarray(row_ids)
     fragile = set(ids[ref.fragile_layer >= 0].tolist())
+    # the rule is for rounding ties (a handful of rows), not a way round the comparison
+    if max_fragile_frac is not None:
+        assert len(fragile) <= max(1, int(np.ceil(max_fragile_frac * len(ids)))), "%s: %d of %d rows fragile" % (
+            what, len(fragile), len(ids))
     ora_rows = ids[ref.active_rows] if row_ids is not None else ref.active_rows
     g, o = set(rows.tolist()), set(ora_rows.tolist())
     assert n == len(rows)
@@ -52,6 +59,24 @@ def check_against_oracle(ref, n, rows, Y, row_ids=None, what=""):
         assert ok.all(), "%s: %d values outside tolerance, worst abs %g" % (
             what, (~ok).sum(), np.abs(Y[gi].astype(np.float64) - ref.Y[oi]).max())
     return len(common), len(fragile)
+
+
+def launch_row_chunk_bounds(model, batch):
+    """First rows of the row chunks the library cuts a full launch of `batch` rows into (one workgroup
+    per CU: column blocks x row chunks, row groups of 4 rows dealt out evenly), so that parity samples
+    can sit on both sides of every boundary."""
+    import torch
+    import paper_2007_14152_amd as sp
+    kind = model.layer_kernel(0)
+    two = kind in (sp.SPDNN_KERNEL_PAIR, sp.SPDNN_KERNEL_WIDE_PAIR, sp.SPDNN_KERNEL_WIDE_PAIR4)
+    nblk = (model.N + 1023) // 1024
+    ncb = nblk // 4 if kind == sp.SPDNN_KERNEL_ROW2 else nblk // 2 if two else nblk
+    rows = 2 if kind == sp.SPDNN_KERNEL_ROW2 else 4          # rows per group (per LDS tile)
+    cus = torch.cuda.get_device_properties(model.device).multi_processor_count
+    ngroups = (batch + rows - 1) // rows
+    Q = max(1, min(max(1, cus // ncb), ngroups))
+    per = (ngroups + Q - 1) // Q
+    return [q * per * rows for q in range(1, Q) if q * per * rows < batch]
 
 
 def config_model(cfg, layers, device=None):

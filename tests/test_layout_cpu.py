@@ -85,3 +85,21 @@ def test_store_groups_of_the_balanced_layout(lay):
     off0 = np.array([lay.spdnn_tile_offset_host(int(g) << 4) for g in grp])
     for a in range(1, 4):
         assert np.all(off0[a::4] == off0[0::4] + 512 * a)
+
+
+def test_two_row_tile_layout(lay):
+    """Tile of the two-rows-per-entry kernel: row2_pos is a permutation of every 128-column span,
+    the four columns of a staging lane sit 32 entries (256 bytes) apart, and the 32 lanes that an
+    8-byte LDS access serves together (half a wave) hit 32 different bank pairs."""
+    lay.spdnn_row2_pos_host.argtypes = [ctypes.c_uint32]
+    lay.spdnn_row2_pos_host.restype = ctypes.c_uint32
+    pos = np.array([lay.spdnn_row2_pos_host(c) for c in range(16384)])
+    assert sorted(pos.tolist()) == list(range(16384))
+    for span in range(0, 16384, 128):
+        assert sorted(pos[span:span + 128].tolist()) == list(range(span, span + 128))
+    t = np.arange(4096)
+    for a in range(4):
+        assert np.all(pos[4 * t + a] == pos[4 * t] + 32 * a)
+        for half in range(0, 4096, 32):           # lanes half .. half+31 store their column a together
+            assert sorted((pos[4 * t[half:half + 32] + a] % 32).tolist()) == list(range(32))
+    assert np.all(pos % 32 == (np.arange(16384) >> 2) % 32)

@@ -104,3 +104,57 @@ def test_benchmark_patterns_get_close_to_the_bound(lib):
     assert np.mean(nat) > 90            # random order: about three lanes per quad in the worst quad
     assert np.mean(cost) < 1.12 * np.mean(lb)
     assert np.mean(cost) < 0.5 * np.mean(nat)
+
+
+# ---- groups of 32 lanes and 32 bank pairs (the two-rows-per-entry kernel) ----
+
+def order32(lib, pairs):
+    lib.spdnn_order_group32_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    pairs = np.ascontiguousarray(pairs, dtype=np.uint8)
+    step_of = np.full((32, 32), 255, dtype=np.uint8)
+    cost = lib.spdnn_order_group32_host(pairs.ctypes.data, step_of.ctypes.data)
+    return cost, step_of
+
+
+def brute_cost32(pairs, step_of):
+    total = 0
+    for s in range(32):
+        q = [pairs[l, np.nonzero(step_of[l] == s)[0][0]] for l in range(32)]
+        total += int(np.bincount(q, minlength=32).max())
+    return total
+
+
+def test_group32_places_every_connection_once(lib):
+    rng = np.random.default_rng(1)
+    for _ in range(30):
+        pairs = rng.integers(0, 32, size=(32, 32)).astype(np.uint8)
+        cost, step_of = order32(lib, pairs)
+        assert cost > 0
+        for l in range(32):
+            assert sorted(step_of[l].tolist()) == list(range(32))     # one connection per lane and step
+        assert cost == brute_cost32(pairs, step_of)
+        assert cost >= max(32, int(np.bincount(pairs.ravel(), minlength=32).max()))
+
+
+def test_group32_latin_square_and_worst_case(lib):
+    latin = (np.arange(32)[:, None] + np.arange(32)[None, :]) % 32     # any order is conflict-free... if steps align
+    rng = np.random.default_rng(2)
+    shuffled = np.stack([rng.permutation(latin[l]) for l in range(32)])
+    cost, _ = order32(lib, shuffled)
+    assert cost == 32, cost
+    cost, _ = order32(lib, np.full((32, 32), 7))
+    assert cost == 32 * 32
+
+
+def test_group32_uniform_patterns_close_to_the_bound(lib):
+    """Uniform columns at N = 16384 (the benchmark's 16384-neuron configuration): the cost stays within
+    15 % of the lower bound max(32, busiest pair)."""
+    c = synth.config(3)
+    cols = synth.gen_layer(c["N"], 0, c["seed"])[:32 * 24]
+    tot = lb = 0
+    for g in range(24):
+        pairs = ((cols[32 * g:32 * g + 32] >> 2) & 31).astype(np.uint8)
+        cost, _ = order32(lib, pairs)
+        tot += cost
+        lb += max(32, int(np.bincount(pairs.ravel(), minlength=32).max()))
+    assert tot <= 1.15 * lb, (tot, lb)
