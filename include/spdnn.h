@@ -172,6 +172,21 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
                 size_t work_arena_bytes, int32_t* n_active_host, int32_t* active_rows_dev,
                 float* Y_final_dev);
 
+/* spdnn_infer for callers that cannot allocate device memory and have no work arena to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * results as spdnn_infer, but the work memory is a fixed array of SPDNN_STATIC_SCRATCH_BYTES bytes
+ * that the library keeps in the memory of every GPU it runs on, from the time the library is loaded
+ * until the process ends.  The call allocates nothing (no hipMalloc, no hipFree, no allocating
+ * library routine) and fails with SPDNN_ESIZE, before any GPU work, when spdnn_work_bytes(N, batch)
+ * exceeds the array (with N = 1024: up to about 8000 rows).  All handles and all calls on one GPU
+ * share the array, and it keeps the last call's contents (every call re-initialises the lists, flags
+ * and counters it reads): calls that overlap in time on one GPU race, on the same handle or on
+ * different ones, also with different streams -- serialise them.  Inputs and outputs remain the
+ * caller's. */
+#define SPDNN_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int spdnn_infer_static(spdnn_t h, const float* Y0_dev, int32_t batch, int32_t* n_active_host,
+                       int32_t* active_rows_dev, float* Y_final_dev);
+
 /* Inputs that stay in host memory, handed to the GPU in serial batches (Section III-B-2: the
  * feature maps of all inputs need not fit the device; a batch is copied in while the one before
  * it is being inferred).  Y0_host: batch x N floats in host memory, row-major, read during the

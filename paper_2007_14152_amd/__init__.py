@@ -30,7 +30,7 @@ SPDNN_KERNEL_WIDE_PAIR4 = 5
 SPDNN_KERNEL_ROW2 = 6
 
 EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_infer", "spdnn_destroy",
-           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile",
+           "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_infer_static",
            "spdnn_host_work_bytes", "spdnn_infer_host",
            "spdnn_weights_bytes_for_window", "spdnn_scan_windows", "spdnn_layer_kernel",
            "spdnn_csr_passes", "spdnn_create_csr", "spdnn_layer_passes", "spdnn_ooc_bytes", "spdnn_create_ooc")
@@ -63,6 +63,7 @@ def lib():
         L.spdnn_last_error.restype = ctypes.c_char_p
         L.spdnn_set_profiling.argtypes = [vp, i32]
         L.spdnn_get_profile.argtypes = [vp, i32, ctypes.POINTER(i32), vp, vp]
+        L.spdnn_infer_static.argtypes = [vp, vp, i32, ctypes.POINTER(i32), vp, vp]
         L.spdnn_host_work_bytes.argtypes = [i32, i32, ctypes.POINTER(sz)]
         L.spdnn_infer_host.argtypes = [vp, vp, i32, i32, vp, sz, ctypes.POINTER(i32), vp, vp]
         L.spdnn_weights_bytes_for_window.argtypes = [i32, i32, i32, ctypes.POINTER(sz)]
@@ -218,6 +219,18 @@ def spdnn_layer_passes(h, l: int) -> int:
     return k.value
 
 
+SPDNN_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def spdnn_infer_static(h, y0_ptr, batch, active_rows_ptr, y_final_ptr) -> int:
+    """spdnn_infer with the library's static scratch array as work memory.  Returns n_active."""
+    n = ctypes.c_int32(-1)
+    _check(lib().spdnn_infer_static(ctypes.c_void_p(h), ctypes.c_void_p(int(y0_ptr)), batch, ctypes.byref(n),
+                                    ctypes.c_void_p(int(active_rows_ptr)),
+                                    ctypes.c_void_p(int(y_final_ptr)) if y_final_ptr else None))
+    return n.value
+
+
 def spdnn_host_work_bytes(N: int, rows_per_batch: int) -> int:
     out = ctypes.c_size_t(0)
     _check(lib().spdnn_host_work_bytes(N, rows_per_batch, ctypes.byref(out)))
@@ -346,6 +359,17 @@ class Model:
             Yf = torch.empty((max(batch, 1), self.N), dtype=torch.float32, device=self.device) if want_Y else None
             n = spdnn_infer(self.h, Y0.data_ptr(), batch, self.work.data_ptr(), self.work.numel(),
                             rows.data_ptr(), Yf.data_ptr() if want_Y else 0)
+        return n, rows[:n], (Yf[:n] if want_Y else None)
+
+    def infer_static(self, Y0, want_Y=True):
+        """infer() through spdnn_infer_static: the library's fixed scratch array is the work memory."""
+        torch = self.torch
+        assert Y0.is_cuda and Y0.dtype == torch.float32 and Y0.is_contiguous() and Y0.shape[1] == self.N
+        batch = int(Y0.shape[0])
+        with torch.cuda.device(self.device):
+            rows = torch.empty(max(batch, 1), dtype=torch.int32, device=self.device)
+            Yf = torch.empty((max(batch, 1), self.N), dtype=torch.float32, device=self.device) if want_Y else None
+            n = spdnn_infer_static(self.h, Y0.data_ptr(), batch, rows.data_ptr(), Yf.data_ptr() if want_Y else 0)
         return n, rows[:n], (Yf[:n] if want_Y else None)
 
     def infer_batched(self, Y0_host, rows_per_batch, want_Y=True):

@@ -12,11 +12,18 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
 #include "spdnn_kernels.h"
+
+// Work memory of spdnn_infer_static, the entry point for callers that cannot allocate: a fixed array in
+// every GPU's memory instead of a caller-made work arena.  In host code this name is only a stand-in for
+// the symbol; the device address comes from hipGetSymbolAddress (see static_scratch()).
+constexpr size_t kStaticScratchBytes = SPDNN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -31,6 +38,8 @@ int fail(int code, const char* fmt, ...) {
     g_err = buf;
     return code;
 }
+
+int static_scratch(void** out);  // defined below
 
 #define HIP_TRY(expr)                                                                         \
     do {                                                                                      \
@@ -342,6 +351,10 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     HIP_TRY(hipGetDeviceProperties(&prop, dev));
     m->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     if (allow_large_lds() != SPDNN_OK) return SPDNN_EHIP;
+    {  // set-up is also where this device's copy of the static scratch array is looked up
+        void* unused = nullptr;
+        if (static_scratch(&unused) != SPDNN_OK) return SPDNN_EHIP;
+    }
     constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
     constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
@@ -596,6 +609,27 @@ int check_infer_args(spdnn_t h, const float* Y0_dev, int32_t batch, int32_t* n_a
     if (!Y0_dev || !active_rows_dev) return fail(SPDNN_EINVAL, "null argument");
     if (reinterpret_cast<uintptr_t>(Y0_dev) % 16) return fail(SPDNN_EINVAL, "Y0 must be 16-byte aligned");
     if (Y_final_dev && reinterpret_cast<uintptr_t>(Y_final_dev) % 16) return fail(SPDNN_EINVAL, "Y_final must be 16-byte aligned");
+    return SPDNN_OK;
+}
+
+// Address of the current device's copy of the static scratch array.  The array's name is only a
+// host-side stand-in; every GPU holds its own copy at its own address, looked up once per device
+// (at spdnn_create, else on the first spdnn_infer_static on that device) and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+int static_scratch(void** out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SPDNN_EINVAL, "device %d: only devices 0..%d are supported", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || reinterpret_cast<uintptr_t>(p) % kAlign) return fail(SPDNN_EHIP, "static scratch array has no usable device address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
     return SPDNN_OK;
 }
 
@@ -1012,6 +1046,26 @@ int spdnn_infer(spdnn_t h, const float* Y0_dev, int32_t batch, void* work_arena,
         if (work_arena_bytes < need) return fail(SPDNN_ESIZE, "work arena has %zu bytes, %zu needed", work_arena_bytes, need);
         WorkView wv;
         carve_work(h->N, batch, static_cast<char*>(work_arena), &wv);
+        return infer_impl(h, Y0_dev, batch, wv, 0, n_active_host, active_rows_dev, Y_final_dev);
+    });
+}
+
+int spdnn_infer_static(spdnn_t h, const float* Y0_dev, int32_t batch, int32_t* n_active_host,
+                       int32_t* active_rows_dev, float* Y_final_dev) {
+    return guarded([&]() -> int {
+        const int rc = check_infer_args(h, Y0_dev, batch, n_active_host, active_rows_dev, Y_final_dev);
+        if (rc != SPDNN_OK || batch == 0) return rc;
+        const size_t need = carve_work(h->N, batch, nullptr, nullptr);
+        if (need > kStaticScratchBytes)
+            return fail(SPDNN_ESIZE,
+                        "batch %d x N %d needs %zu bytes of scratch, the static scratch array holds %zu: use spdnn_infer "
+                        "with a work arena",
+                        batch, h->N, need, kStaticScratchBytes);
+        void* ptr = nullptr;
+        const int rs = static_scratch(&ptr);  // this device's copy of the array (looked up at spdnn_create)
+        if (rs != SPDNN_OK) return rs;
+        WorkView wv;
+        carve_work(h->N, batch, static_cast<char*>(ptr), &wv);
         return infer_impl(h, Y0_dev, batch, wv, 0, n_active_host, active_rows_dev, Y_final_dev);
     });
 }
