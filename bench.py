@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--scatter", action="store_true",
                     help="scattered-window variant (ours): the members of every window are spread over the row by a "
                          "seeded permutation per layer")
+    ap.add_argument("--strided", default=None, metavar="S[,S...]",
+                    help="strided variant (ours): neuron j reads columns (j + k*S) mod N, k = 0..31; several strides are "
+                         "used by the layers in turn, as in a mixed-radix RadiX-Net")
     ap.add_argument("--out-of-core", action="store_true",
                     help="weights in pinned host memory, streamed through two device buffers (ours: the target keeps them resident)")
     ap.add_argument("--no-sustained", dest="sustained", action="store_false",
@@ -41,6 +44,9 @@ def parse():
     ap.add_argument("--sustained-steps", type=int, default=2)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stream-probe-gib", type=float, default=0.0,
+                    help="instead of the benchmark: time plain streaming kernels over this many GiB (torch's fill, sum and "
+                         "copy: write-only, read-only, half and half) -- what the chip gives a kernel that only moves data")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
                     help="also run a plain device copy of this many GiB (calibrates rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -121,6 +127,32 @@ def parity_check(model, y0, ids, ref, final_rows):
         "per_layer_counts_match": bool(ok_layers), "sample_run_set_matches": bool(ok_set)}
 
 
+def stream_probe(gib, dev):
+    """GB/s of plain streaming kernels (torch's own: fill_, sum, copy_) over `gib` GiB: the rates at which
+    this chip moves data when a kernel does nothing else, to set beside the fused kernel's rate."""
+    import torch
+    n = int(gib * (1 << 30)) // 4
+    src = torch.ones(n, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    out = {"probe": "streaming kernels over %.1f GiB float32 (torch fill_, sum, copy_)" % gib, "peak_GBs": HBM_PEAK_GBS}
+
+    def rate(fn, nbytes, reps=10):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    out["write_only_GBs"] = rate(lambda: dst.fill_(1.0), n * 4)
+    out["read_only_GBs"] = rate(lambda: src.sum(), n * 4)
+    out["copy_GBs_read_plus_write"] = rate(lambda: dst.copy_(src), 2 * n * 4)
+    return out
+
+
 def timed_leg(model, y0, steps, warmup, N, nnz):
     """warmup + steps inferences of one resident input; HIP events on the model's stream around every
     fused launch (the library's profile).  Returns wall seconds per step and the launch statistics."""
@@ -171,6 +203,9 @@ def main():
     import paper_2007_14152_amd as sp
 
     dev = "cuda:0"
+    if a.stream_probe_gib > 0:
+        print(json.dumps(stream_probe(a.stream_probe_gib, dev)))
+        return
     c = synth.config(a.config)
     if a.batch:
         c["batch"] = a.batch
@@ -193,6 +228,9 @@ def main():
             didx[l] = synth.gen_layer(N, l, c["seed"], c["window"], device=dev)
             if a.scatter:
                 didx[l] = synth.scatter_columns(didx[l], N, l, c["seed"], device=dev)
+            if a.strided:
+                strides = [int(x) for x in a.strided.split(",")]
+                didx[l] = synth.gen_layer_strided(N, strides[l % len(strides)], device=dev)
         dval = torch.full((L, N, 32), synth.WEIGHT, dtype=torch.float32, device=dev)
         dbias = synth.gen_bias(N, c["bias"], device=dev)
         model = sp.Model([didx[l] for l in range(L)], [dval[l] for l in range(L)], dbias, device=dev,
@@ -231,7 +269,7 @@ def main():
     full_bytes = algorithmic_bytes(batch, N, nnz[0] if nnz else None)
     full_ms = leg["full_ms"] / leg["full_launches"] if leg["full_launches"] else None
     traffic, traffic_source = measured_traffic("cfg%d_batch%d_%s" % (a.config, batch, density), kernel0)
-    if a.scatter or a.general or a.out_of_core:
+    if a.scatter or a.general or a.out_of_core or a.strided:
         traffic, traffic_source = None, None
     out = {
         "metric": "TeraEdges/sec (batch*N*32*L/time) at 1 MI355X",
@@ -244,7 +282,7 @@ def main():
             a.config, N, L, batch, c["bias"], c["window"], density) + (
                 " general layers %s connections per neuron, passes %s" % (
                     a.general, [model.layer_passes(l) for l in range(L)]) if a.general else "") + (
-                " windows scattered" if a.scatter else "") + (
+                " windows scattered" if a.scatter else "") + (" strided columns, strides %s" % a.strided if a.strided else "") + (
                 " weights out of core (%.1f MB on the device, %.1f MB in pinned host memory)" % (
                     model.arena.numel() / 1e6, model.host_arena.numel() / 1e6) if a.out_of_core else ""),
             "executed_TeraEdges_per_s": executed * a.steps / dt / 1e12,

@@ -52,7 +52,7 @@ int static_scratch(void** out);  // defined below
 constexpr size_t kAlign = 256;
 inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-constexpr int kLag = 4;  // the host runs at most this many layers ahead of the GPU
+constexpr int kLag = 2;  // the host runs at most this many layers ahead of the GPU
 // Set-up of device-resident layers runs on this many streams, a layer per stream in turn: its kernels
 // are single-wave, latency-bound searches that fill a fraction of the chip, so several layers overlap.
 constexpr int kSetupStreams = 4;
@@ -62,6 +62,9 @@ struct LayerDesc {
     spdnn::LayerWeights w;
     spdnn::WideWeights ww;
     spdnn::Row2Weights r2;
+    uint16_t* r2_codes = nullptr;  // arena room for the two-row-tile format (NULL: none)
+    int32_t* r2_map = nullptr;
+    int* r2_ngroups = nullptr;
     // kRow2: one weight for the whole layer, N a multiple of 4096, every 4096-neuron unit's window within 16384
     // columns but wider than one LDS stage: four neurons per lane, two rows per tile (fused_row2_kernel);
     // kSingle: every window fits one LDS stage; kStaged: 2 stages (or fallback); kWide: 3+ stages;
@@ -122,6 +125,13 @@ size_t wide_steps_max(int nstage) {
     return m;
 }
 bool wide_has_slots(int nstage) { return nstage <= 8; }  // the compact 16-bit form exists for 2..8 stages
+// the two-row-tile format (fused_row2_kernel): step codes, gathered-footprint list, groups per unit
+size_t row2_bytes(int32_t nblk) {
+    if (nblk % 4) return 0;
+    const size_t nunit = nblk / 4;
+    return up((size_t)nblk * spdnn::kBlk * spdnn::kNnz * sizeof(uint16_t)) +
+           up(nunit * (spdnn::kRow2Cols / 4) * sizeof(int32_t)) + up(nunit * sizeof(int));
+}
 size_t wide_bytes(int32_t nblk, int nstage) {
     if (nstage < 2) return 0;
     const size_t e = (size_t)nblk * wide_steps_max(nstage) * spdnn::kBlk;
@@ -129,7 +139,8 @@ size_t wide_bytes(int32_t nblk, int nstage) {
     return up(e * sizeof(uint2)) + up((size_t)nblk * nstage * 16) + up(sp * sizeof(uint16_t)) +
            up(sp * sizeof(float)) + up((size_t)nblk * 16) +
            (wide_has_slots(nstage) ? up(e * sizeof(uint16_t)) + up(sp * sizeof(uint16_t))
-                                   : 0);  // last: compact slots and spills
+                                   : 0) +  // compact slots and spills
+           row2_bytes(nblk);
 }
 size_t staging_bytes(int32_t N, int32_t L) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
@@ -417,6 +428,15 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
                 ww.sp16 = reinterpret_cast<uint16_t*>(base + o);
                 o += up(sp * sizeof(uint16_t));
             }
+            if (nblk % 4 == 0) {
+                const size_t nunit = nblk / 4;
+                m->layers[l].r2_codes = reinterpret_cast<uint16_t*>(base + o);
+                o += up((size_t)nblk * spdnn::kBlk * spdnn::kNnz * sizeof(uint16_t));
+                m->layers[l].r2_map = reinterpret_cast<int32_t*>(base + o);
+                o += up(nunit * (spdnn::kRow2Cols / 4) * sizeof(int32_t));
+                m->layers[l].r2_ngroups = reinterpret_cast<int*>(base + o);
+                o += up(nunit * sizeof(int));
+            }
         }
         m->layers[l].ww = ww;
     }
@@ -500,7 +520,8 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         const bool wide_pair = pair_info[0] == 2;  // ... if the layer also fits the wide format
         // one weight, every block wider than one stage, and every 4096-neuron unit within 16384 columns:
         // four neurons per lane on two-row tiles; needs nothing of the other formats
-        bool row2 = wide_pair && !d.multi && N % spdnn::kUnit4 == 0 && d.ww.ps != nullptr;
+        const bool row2_ok = wide_pair && !d.multi && N % spdnn::kUnit4 == 0 && d.r2_codes != nullptr;
+        bool row2 = row2_ok;
         for (int32_t u = 0; row2 && u < nblk / 4; ++u) {
             int lo = 1 << 30, hi = 0;
             for (int i = 0; i < 4; ++i) {
@@ -509,14 +530,32 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
             }
             row2 = hi - lo <= spdnn::kRow2Cols;
         }
+        // Windows too wide for the tile: the gathered footprint (Section III-A-2's preload list at 4-column
+        // granularity) may still fit it -- every unit's connections within 4096 groups of four columns.
+        // The rank table is set-up scratch: this stream's column -> slot table, which such a layer does not use.
+        const int32_t* gather_map = nullptr;
+        const uint16_t* gather_rank = nullptr;
+        if (row2_ok && !row2 && (size_t)(nblk / 4) * (N / 4) <= slot_tab_elems) {
+            const int32_t nunit = nblk / 4;
+            spdnn::row2_gather_kernel<<<nunit, spdnn::kBlk, 0, stream>>>(di, N, d.r2_map, slot_tab, d.r2_ngroups);
+            HIP_TRY(hipGetLastError());
+            std::vector<int> ngr((size_t)nunit);
+            HIP_TRY(hipMemcpyAsync(ngr.data(), d.r2_ngroups, sizeof(int) * (size_t)nunit, hipMemcpyDeviceToHost, stream));
+            HIP_TRY(hipStreamSynchronize(stream));
+            row2 = true;
+            for (int32_t u = 0; u < nunit; ++u) row2 = row2 && ngr[u] <= spdnn::kRow2Cols / 4;
+            if (row2) {
+                gather_map = d.r2_map;
+                gather_rank = slot_tab;
+            }
+        }
         if (row2) {
             // the windows read back above are the blocks' own; pair_merge_kernel has widened them on the device to
             // common windows of block pairs, whose unions per unit are the same
-            d.r2 = spdnn::Row2Weights{reinterpret_cast<const uint4*>(d.ww.ps), win_dev[l]};
+            d.r2 = spdnn::Row2Weights{reinterpret_cast<const uint4*>(d.r2_codes), win_dev[l], gather_map};
             const int groups = N / spdnn::kGroup32;
             spdnn::row2_pack_kernel<<<(groups + spdnn::kRow2PackThreads - 1) / spdnn::kRow2PackThreads,
-                                      spdnn::kRow2PackThreads, 0, stream>>>(
-                di, N, win_dev[l], reinterpret_cast<uint16_t*>(const_cast<uint4*>(d.ww.ps)));
+                                      spdnn::kRow2PackThreads, 0, stream>>>(di, N, win_dev[l], gather_rank, d.r2_codes);
             HIP_TRY(hipGetLastError());
             d.mode = kRow2;
             d.lds_cols = spdnn::kRow2Cols;

@@ -34,6 +34,10 @@ struct Row2Weights {
     const uint4* codes;  // [nunit][4][4][kBlk]: neuron slot s of lane t, steps 8o .. 8o+7 as 16-bit tile positions
                          // (row2_pos of the column inside the unit's window)
     const int2* win;     // [nblk] per 1024-neuron block {c_lo, ncols}; a unit's window is the union of its four
+    const int32_t* map;  // NULL: the tile is the unit's contiguous window.  Else the gathered footprint (the preload
+                         // list of Section III-A-2, at 4-column granularity): [nunit][4096] first column of the
+                         // group of four columns that tile slot g holds, ascending; entries past the unit's
+                         // last group repeat it.  Tile column 4g + a is then row column map[g] + a.
 };
 
 // Column window of unit u: the union of its four blocks' windows (c_lo a multiple of 4).
@@ -178,7 +182,8 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     WorkItem wi;  // my unit and my groups of two rows
     if (!my_work(nunit, G, Q, count_ptr, wi, kRows2)) return;
     const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
-    const int2 win = row2_window(w.win, u);
+    const bool gathered = w.map != nullptr;  // the tile is a gathered list of 4-column groups, not a window
+    const int2 win = gathered ? make_int2(0, kRow2Cols) : row2_window(w.win, u);
     const int c_lo = win.x;
     const int ncols = win.y;  // <= kRow2Cols, a multiple of 4
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
@@ -212,10 +217,16 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     const int cat_last = cat[A - 1];
     const int T = g1 - g0;
     // Byte offset of my four columns inside a segment: 16 * tid, except that in a narrower last segment
-    // the lanes past the window re-read its last columns.  The segment's own offset is scalar.
+    // the lanes past the window re-read its last columns.  The segment's own offset is scalar.  With a
+    // gathered footprint the offsets come from the unit's list instead (and the segment offset is zero).
     const int last_cols = ncols - (nseg - 1) * kRow2Seg;  // columns of the last segment (a multiple of 4, >= 4)
-    const uint32_t off_full = 16u * (uint32_t)tid;
-    const uint32_t off_last = 4u * (uint32_t)min(4 * tid, last_cols - 4);
+    uint32_t off[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        off[s] = s == nseg - 1 ? 4u * (uint32_t)min(4 * tid, last_cols - 4) : 16u * (uint32_t)tid;
+        if (gathered) off[s] = 4u * (uint32_t)w.map[(size_t)u * (kRow2Cols / 4) + s * kBlk + tid];
+    }
+    const size_t seg_bytes = gathered ? 0 : (size_t)kRow2Seg * 4;
     const char* ld_row[kRows2] = {nullptr, nullptr};  // row bases of the tile being loaded, at the window's first column
     auto tile_rows = [&](int t) {
         const int2 c2 = *reinterpret_cast<const int2*>(cat + (size_t)(g0 + t) * kRows2);
@@ -229,8 +240,8 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     auto load_piece = [&](int i) {  // piece i = row i & 1 of segment i >> 1; i is a constant wherever this is called
         const int s = i >> 1, r = i & 1;
         if (s < nseg) {
-            const char* base = ld_row[r] + (size_t)s * (kRow2Seg * 4);
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(st[s][r]) : "v"(s == nseg - 1 ? off_last : off_full), "s"(base) : "memory");
+            const char* base = ld_row[r] + (size_t)s * seg_bytes;
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(st[s][r]) : "v"(off[s]), "s"(base) : "memory");
         }
     };
     auto wait_tile = [&]() {  // every load (and store) issued so far has completed; the staged values may be touched
@@ -323,6 +334,52 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     }
 }
 
+// a0 for the gathered footprint: per unit of 4096 neurons, the groups of four columns (column >> 2) that
+// any of its connections touches, in ascending order.  One workgroup per unit: a bitmap of the row's
+// N / 4 groups in LDS, a prefix count over it, and out come
+//   map[u][g]   first column of the unit's g-th group (entries past the last group repeat it),
+//   rank[u][c4] position g of group c4 in that list (meaningful for the groups that are used),
+//   ngroups[u]  number of groups; the tile holds kRow2Cols / 4 of them.
+__global__ __launch_bounds__(kBlk) void row2_gather_kernel(const int32_t* __restrict__ idx, int N,
+                                                           int32_t* __restrict__ map, uint16_t* __restrict__ rank,
+                                                           int* __restrict__ ngroups) {
+    __shared__ uint32_t bits[65536 / 4 / 32];  // one bit per group of four columns
+    __shared__ uint32_t before[65536 / 4 / 32 + 1];
+    const int u = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int words = (N / 4 + 31) / 32;
+    for (int i = tid; i < words; i += kBlk) bits[i] = 0;
+    __syncthreads();
+    for (int e = tid; e < kUnit4 * kNnz; e += kBlk) {
+        const int c = idx[(size_t)u * kUnit4 * kNnz + e];
+        if (c >= 0 && c < N) atomicOr(&bits[c >> 7], 1u << ((c >> 2) & 31));  // bad columns were reported
+    }
+    __syncthreads();
+    if (tid == 0) {  // N / 128 <= 512 words: a serial scan is short
+        uint32_t run = 0;
+        for (int i = 0; i < words; ++i) {
+            before[i] = run;
+            run += __popc(bits[i]);
+        }
+        before[words] = run;
+        ngroups[u] = (int)run;
+    }
+    __syncthreads();
+    const int total = (int)before[words];
+    for (int c4 = tid; c4 < N / 4; c4 += kBlk) {
+        const uint32_t wbits = bits[c4 >> 5];
+        const int g = (int)before[c4 >> 5] + __popc(wbits & ((1u << (c4 & 31)) - 1u));
+        rank[(size_t)u * (N / 4) + c4] = (uint16_t)min(g, kRow2Cols / 4 - 1);
+        if (((wbits >> (c4 & 31)) & 1u) && g < kRow2Cols / 4) {
+            map[(size_t)u * (kRow2Cols / 4) + g] = 4 * c4;
+            if (g == total - 1)  // the last group fills the rest of the list
+                for (int k = g + 1; k < kRow2Cols / 4; ++k) map[(size_t)u * (kRow2Cols / 4) + k] = 4 * c4;
+        }
+    }
+    if (total == 0)
+        for (int k = tid; k < kRow2Cols / 4; k += kBlk) map[(size_t)u * (kRow2Cols / 4) + k] = 0;
+}
+
 // a0 for fused_row2_kernel: one thread per group of 32 neighbouring neurons of one neuron slot
 // (the lanes a ds_read_b64 serves together).  Orders the group's connections so that in every
 // step the 32 lanes read 32 different bank pairs whenever possible (order_group32) and writes the
@@ -332,6 +389,7 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
 constexpr int kRow2PackThreads = 1;
 __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32_t* __restrict__ idx, int N,
                                                                      const int2* __restrict__ win,
+                                                                     const uint16_t* __restrict__ rank,  // NULL: contiguous windows
                                                                      uint16_t* __restrict__ codes) {
     __shared__ Order32Scratch scratch[kRow2PackThreads];
     const int g = blockIdx.x * kRow2PackThreads + threadIdx.x;  // group: unit, slot, 32 lanes
@@ -341,10 +399,13 @@ __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32
     const int in_unit = g - u * groups_per_unit;
     const int s = in_unit / (kBlk / kGroup32);
     const int lane0 = (in_unit - s * (kBlk / kGroup32)) * kGroup32;
-    const int c_lo = row2_window(win, u).x;
+    const int c_lo = rank ? 0 : row2_window(win, u).x;
     auto pos_of = [&](int l, int k) -> uint32_t {  // out-of-range columns were reported; keep them harmless
-        const int c = idx[((size_t)u * kUnit4 + s * kBlk + lane0 + l) * kNnz + k];
-        return row2_pos((c < 0 || c >= N) ? 0u : (uint32_t)(c - c_lo) & (kRow2Cols - 1));
+        int c = idx[((size_t)u * kUnit4 + s * kBlk + lane0 + l) * kNnz + k];
+        if (c < 0 || c >= N) c = c_lo;
+        // tile column: inside the window, or in the gathered list group rank[c >> 2], column c & 3 of it
+        const uint32_t tc = rank ? 4u * rank[(size_t)u * (N / 4) + (c >> 2)] + (uint32_t)(c & 3) : (uint32_t)(c - c_lo);
+        return row2_pos(tc & (kRow2Cols - 1));
     };
     order_group32(
         scratch[threadIdx.x], [&](int l, int k) -> unsigned { return pos_of(l, k) & 31u; },

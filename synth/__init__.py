@@ -303,6 +303,20 @@ def scatter_columns(cols, N, l, seed, device=None):
     return bk.to_i32(out)
 
 
+def gen_layer_strided(N, stride, device=None):
+    """A strided pattern of the kind the RadiX-Net topologies of the challenge networks are built from
+    (Section II-A; ours, the challenge files are not available): neuron j is connected to the 32 columns
+    (j + k * stride) mod N, k = 0..31, sorted.  int32 [N, 32]."""
+    bk = _backend(device)
+    if bk.name == "numpy":
+        j = np.arange(N, dtype=np.int64)[:, None]
+        k = np.arange(NNZ, dtype=np.int64)[None, :]
+        return np.sort((j + k * int(stride)) % N, axis=1).astype(np.int32)
+    j = torch.arange(N, dtype=torch.int64, device=device)[:, None]
+    k = torch.arange(NNZ, dtype=torch.int64, device=device)[None, :]
+    return torch.sort((j + k * int(stride)) % N, dim=1).values.to(torch.int32)
+
+
 def gen_values(N, device=None):
     """Weight values of one layer: float32 [N, 32], all 1/16."""
     if device is None or device == "numpy":

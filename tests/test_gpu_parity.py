@@ -552,6 +552,29 @@ def test_scattered_windows():
     assert common > 0
 
 
+@pytest.mark.parametrize("N,w,batch", [(65536, 4096, 21), (32768, 2048, 9)])
+def test_scattered_windows_gathered_footprint(N, w, batch):
+    """The other reading of "permuted window": the members of every window are scattered over the whole
+    row.  A unit of 4096 output neurons then touches at most 4096 groups of four columns, which the
+    two-row-tile kernel stages as a gathered list (the preload list of Section III-A-2) instead of a
+    contiguous window; results against the oracle."""
+    import paper_2007_14152_amd as sp
+    L = 2
+    idx = [synth.scatter_columns(synth.gen_layer(N, l, 77, w), N, l, 77) for l in range(L)]
+    val = [synth.gen_values(N) for _ in range(L)]
+    bias = synth.gen_bias(N, -0.3)
+    Y0 = synth.gen_y0(batch, N, 77, density="mixed")
+    ref = oracle.infer(idx, val, bias, Y0)
+    assert 0 < ref.n_active < batch
+    m = sp.Model(idx, val, bias)
+    assert m.widest_window > N - 256
+    assert [m.layer_kernel(l) for l in range(L)] == [sp.SPDNN_KERNEL_ROW2] * L
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    m.close()
+    common, _ = check_against_oracle(ref, n, rows, Y, what="scattered windows, gathered footprint")
+    assert common > 0
+
+
 @pytest.mark.parametrize("rows_per_batch", [1000, 257, 64, 5000])
 def test_inputs_in_host_memory_in_serial_batches(rows_per_batch):
     """Section III-B-2: the inputs stay on the host and go through the GPU batch by batch

@@ -73,3 +73,13 @@ def test_scattered_window_variant():
     assert len(np.unique(b)) == len(np.unique(a))
     assert not np.array_equal(b, synth.scatter_columns(a, N, 4, 11))
     assert np.array_equal(b, synth.scatter_columns(torch.from_numpy(a), N, 3, 11, device="cpu").numpy())
+
+
+def test_strided_layers():
+    a = synth.gen_layer_strided(4096, 128)
+    assert a.shape == (4096, 32) and a.dtype == np.int32
+    assert np.all(np.diff(a, axis=1) > 0) and a.min() == 0 and a.max() == 4095
+    j = 777
+    assert sorted(((j + np.arange(32) * 128) % 4096).tolist()) == a[j].tolist()
+    # every column is read by exactly 32 neurons
+    assert np.all(np.bincount(a.ravel(), minlength=4096) == 32)
