@@ -45,8 +45,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stream-probe-gib", type=float, default=0.0,
-                    help="instead of the benchmark: time plain streaming kernels over this many GiB (torch's fill, sum and "
-                         "copy: write-only, read-only, half and half) -- what the chip gives a kernel that only moves data")
+                    help="instead of the benchmark: time plain streaming kernels over this many GiB (torch's fill, sum, "
+                         "elementwise mul and copy: write-only, read-only, half and half) -- what the chip gives a kernel that only moves data")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
                     help="also run a plain device copy of this many GiB (calibrates rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -134,7 +134,7 @@ def stream_probe(gib, dev):
     n = int(gib * (1 << 30)) // 4
     src = torch.ones(n, dtype=torch.float32, device=dev)
     dst = torch.empty_like(src)
-    out = {"probe": "streaming kernels over %.1f GiB float32 (torch fill_, sum, copy_)" % gib, "peak_GBs": HBM_PEAK_GBS}
+    out = {"probe": "streaming kernels over %.1f GiB float32 (torch fill_, sum, elementwise mul, copy_)" % gib, "peak_GBs": HBM_PEAK_GBS}
 
     def rate(fn, nbytes, reps=10):
         for _ in range(3):
@@ -149,7 +149,8 @@ def stream_probe(gib, dev):
 
     out["write_only_GBs"] = rate(lambda: dst.fill_(1.0), n * 4)
     out["read_only_GBs"] = rate(lambda: src.sum(), n * 4)
-    out["copy_GBs_read_plus_write"] = rate(lambda: dst.copy_(src), 2 * n * 4)
+    out["copy_GBs_read_plus_write"] = rate(lambda: torch.mul(src, 1.0, out=dst), 2 * n * 4)   # elementwise kernel
+    out["device_memcpy_GBs_read_plus_write"] = rate(lambda: dst.copy_(src), 2 * n * 4)
     return out
 
 
@@ -244,7 +245,7 @@ def main():
         src = torch.ones(n, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            torch.mul(src, 1.0, out=dst)    # an elementwise kernel (not a DMA copy): reads n*4 bytes, writes n*4 bytes
         torch.cuda.synchronize()
         del src, dst
 
