@@ -763,21 +763,35 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     const int T = g1 - g0;
     f32x4 st[kRows];
     const int wave_col = (tid & ~63) * 4;
+    const bool staging = wave_col < ncols;  // waves whose columns lie past the window stage nothing
     const uint32_t st_addr = lds_base + tile_offset(store_group(4 * tid) << 4);
     const uint32_t qp = w.qsel[(size_t)b * kBlk + tid];
     const int cat_last = cat[A - 1];
-    int4 c4 = make_int4(0, 0, 0, 0);
+    // byte offset of my four columns in a row; lanes past the window re-read its last columns
+    const uint32_t ld_off = 4u * (uint32_t)(c_lo + min(4 * tid, ncols - 4));
+    const char* ld_row[kRows] = {nullptr, nullptr, nullptr, nullptr};  // bases of the 4 rows of the tile to load (scalar)
 
-    auto fetch_rows = [&](int t) { c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + t) * kRows); };
-    auto load_tile = [&](int t) {
-        if (wave_col >= ncols) return;
+    auto fetch_rows = [&](int t) {
+        const int4 c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + t) * kRows);
         const int row0 = (g0 + t) * kRows;
-        const size_t coff = (size_t)c_lo + (size_t)min(4 * tid, ncols - 4);
-        stage_load(st, Yin, N, c4, row0, A, cat_last, coff);
+        ld_row[0] = reinterpret_cast<const char*>(Yin + (size_t)c4.x * N);
+        ld_row[1] = reinterpret_cast<const char*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N);
+        ld_row[2] = reinterpret_cast<const char*>(Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N);
+        ld_row[3] = reinterpret_cast<const char*>(Yin + (size_t)(row0 + 3 < A ? c4.w : cat_last) * N);
+    };
+    // One 16-byte load per lane and row: scalar row base + 32-bit lane offset, written as an instruction so that
+    // no vector register is spent on addresses and the compiler places no wait of its own; the wait is written
+    // out before the values are first touched (wait_tile).  The build checks that this kernel never spills:
+    // the compiler does not know that the loaded values arrive late.
+    auto load_row = [&](int r) {
+        if (staging) asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(st[r]) : "v"(ld_off), "s"(ld_row[r]) : "memory");
+    };
+    auto wait_tile = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
     };
     auto store_tile = [&](int P) {
-        if (wave_col >= ncols) return;
-        stage_store(st, st_addr + P * kBufSkew, qp);
+        if (staging) stage_store(st, st_addr + P * kBufSkew, qp);
     };
 
     float accA[kRows] = {0.f, 0.f, 0.f, 0.f}, accB[kRows] = {0.f, 0.f, 0.f, 0.f};
@@ -801,18 +815,31 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
         return finish_rows(acc, bj, Yout, N, j, true, row0, nlive, lane);
     };
 
-    // One step: neuron A's 32 connections, tile t+1 into the other buffer and the loads of
-    // tile t+2, neuron B's 32 connections, both epilogues.
+    // One step: neuron A's 32 connections; tile t+1 into the other buffer; neuron B's 32 connections with the
+    // loads of tile t+2 in two bursts before its two halves (a wave that issues loads is stuck until the memory
+    // pipeline has taken them, and four loads per lane back to back leave the last wave some 3000 clocks behind
+    // the first); both epilogues.
     using K0 = std::integral_constant<int, 0>;
     using K16 = std::integral_constant<int, 16>;
     auto step = [&](int t, auto Ptag) {
         constexpr int P = decltype(Ptag)::value;
-        if (t + 2 < T) fetch_rows(t + 2);
+        const bool more = t + 2 < T;
         compute(Ptag, accA, offA, K0{});
         compute(Ptag, accA, offA, K16{});
-        if (t + 1 < T) store_tile(P ^ 1);
-        if (t + 2 < T) load_tile(t + 2);
+        if (t + 1 < T) {
+            wait_tile();
+            store_tile(P ^ 1);
+        }
+        if (more) {
+            fetch_rows(t + 2);
+            load_row(0);
+            load_row(1);
+        }
         compute(Ptag, accB, offB, K0{});
+        if (more) {
+            load_row(2);
+            load_row(3);
+        }
         compute(Ptag, accB, offB, K16{});
         const int row0 = (g0 + t) * kRows;
         const int nlive = min(kRows, A - row0);
@@ -823,11 +850,14 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
     fetch_rows(0);
-    load_tile(0);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) load_row(r);
+    wait_tile();
     store_tile(0);
     if (T > 1) {
         fetch_rows(1);
-        load_tile(1);
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) load_row(r);
     }
     __syncthreads();
     int t = 0;
