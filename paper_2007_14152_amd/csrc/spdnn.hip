@@ -55,7 +55,7 @@ inline size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 constexpr int kLag = 2;  // the host runs at most this many layers ahead of the GPU
 // Set-up of device-resident layers runs on this many streams, a layer per stream in turn: its kernels
 // are single-wave, latency-bound searches that fill a fraction of the chip, so several layers overlap.
-constexpr int kSetupStreams = 4;
+constexpr int kSetupStreams = 8;
 
 enum LayerMode { kSingle = 0, kStaged = 1, kWide = 2, kPair = 3, kWidePair = 4, kRow2 = 5 };
 struct LayerDesc {
@@ -205,7 +205,7 @@ hipError_t allow_big_lds() {
 
 // The fused kernels and two set-up kernels use more dynamic LDS than the default limit allows.
 int allow_large_lds() {
-    constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
+    constexpr size_t order_lds = spdnn::kOrderPackThreads * sizeof(spdnn::OrderScratch);
     constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
     const int tile_lds = (int)spdnn::tile_pair_bytes(spdnn::kCap);
     HIP_TRY((allow_big_lds<false, false>()));
@@ -366,7 +366,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         void* unused = nullptr;
         if (static_scratch(&unused) != SPDNN_OK) return SPDNN_EHIP;
     }
-    constexpr size_t order_lds = spdnn::kOrderThreads * sizeof(spdnn::OrderScratch);
+    constexpr size_t order_lds = spdnn::kOrderPackThreads * sizeof(spdnn::OrderScratch);
     constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
                           hipHostMallocDefault));
@@ -572,7 +572,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         else
             spdnn::balance_kernel<1><<<nblk, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<1>), stream>>>(
                 di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
-        spdnn::order_pack_kernel<<<nblk, spdnn::kOrderThreads, order_lds, stream>>>(
+        spdnn::order_pack_kernel<<<nblk * (spdnn::kOrderThreads / spdnn::kOrderPackThreads), spdnn::kOrderPackThreads, order_lds, stream>>>(
             di, dv, N, win_dev[l], widest_dev, slot_tab, pair, const_cast<uint16_t*>(d.w.rel),
             const_cast<float*>(d.w.val));
         HIP_TRY(hipGetLastError());

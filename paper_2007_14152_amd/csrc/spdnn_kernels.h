@@ -1961,8 +1961,11 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
 // (block b, step s, lane t) holds the LDS slot of the connection's column (plus
 // the stage number in bits 12 and up) and its weight, for the connection lane t
 // uses at step s.
-constexpr int kOrderThreads = kBlk / kGroup;
-__global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t* __restrict__ idx,
+constexpr int kOrderThreads = kBlk / kGroup;  // lane sets per output block
+// The search diverges from set to set, so few of them share a wave: kOrderPackThreads threads per workgroup,
+// kOrderThreads / kOrderPackThreads workgroups per output block.
+constexpr int kOrderPackThreads = 4;
+__global__ __launch_bounds__(kOrderPackThreads) void order_pack_kernel(const int32_t* __restrict__ idx,
                                                                    const float* __restrict__ val, int N,
                                                                    const int2* __restrict__ win,
                                                                    const int* __restrict__ widest,
@@ -1971,8 +1974,9 @@ __global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t
                                                                    uint16_t* __restrict__ rel,
                                                                    float* __restrict__ wval) {
     extern __shared__ OrderScratch order_scratch[];
-    const int b = blockIdx.x;
-    const int t = threadIdx.x;
+    const int gset = blockIdx.x * kOrderPackThreads + threadIdx.x;  // lane set, counted over the whole layer
+    const int b = gset / kOrderThreads;
+    const int t = gset - b * kOrderThreads;
     const int wave0 = (t >> 2) * 64;  // first lane of this thread's wave inside the block
     const int set = t & 3;
     const int c_lo = win[b].x;
@@ -1986,7 +1990,7 @@ __global__ __launch_bounds__(kOrderThreads) void order_pack_kernel(const int32_t
     const uint16_t* tab = slot_tab + (size_t)(pair ? (b & ~1) : b) * kCap;
     auto slot_of = [&](uint32_t r) -> uint32_t { return balanced ? tab[r] : col_slot(r); };
     order_group(
-        order_scratch[t], kNnz,
+        order_scratch[threadIdx.x], kNnz,
         [&](int l, int k) -> unsigned {
             return (neuron(l) < N) ? (slot_of((uint32_t)(column(l, k) - c_lo) & (kCap - 1)) & 15u) : 255u;
         },
