@@ -523,12 +523,10 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         const bool row2_ok = wide_pair && !d.multi && N % spdnn::kUnit4 == 0 && d.r2_codes != nullptr;
         bool row2 = row2_ok;
         for (int32_t u = 0; row2 && u < nblk / 4; ++u) {
-            int lo = 1 << 30, hi = 0;
-            for (int i = 0; i < 4; ++i) {
-                lo = std::min(lo, hw[(size_t)l * nblk + 4 * u + i].x);
-                hi = std::max(hi, hw[(size_t)l * nblk + 4 * u + i].x + hw[(size_t)l * nblk + 4 * u + i].y);
-            }
-            row2 = hi - lo <= spdnn::kRow2Cols;
+            int x = 0, y = 0;  // the unit's window: the union of its blocks' cyclic windows
+            for (int i = 0; i < 4; ++i)
+                spdnn::win_union(x, y, hw[(size_t)l * nblk + 4 * u + i].x, hw[(size_t)l * nblk + 4 * u + i].y, N, x, y);
+            row2 = y <= spdnn::kRow2Cols;
         }
         // Windows too wide for the tile: the gathered footprint (Section III-A-2's preload list at 4-column
         // granularity) may still fit it -- every unit's connections within 4096 groups of four columns.
@@ -900,9 +898,9 @@ int spdnn_scan_windows(int32_t N, int32_t L, const int32_t* const* idx, int32_t 
             // layers that run two neurons per lane give blocks 2u and 2u+1 their common window
             if (N % (2 * spdnn::kBlk) == 0)
                 for (int32_t b = 0; b + 1 < nblk; b += 2) {
-                    const int lo = std::min(hw[b].x, hw[b + 1].x);
-                    const int hi = std::max(hw[b].x + hw[b].y, hw[b + 1].x + hw[b + 1].y);
-                    widest = std::max(widest, hi - lo);
+                    int x, y;  // windows are cyclic
+                    spdnn::win_union(hw[b].x, hw[b].y, hw[b + 1].x, hw[b + 1].y, N, x, y);
+                    widest = std::max(widest, y);
                 }
         }
         int herr = 0;

@@ -625,7 +625,7 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         const int left = ncols - s * kCap;  // columns in this stage (a multiple of 4, may exceed kCap)
         if (wave_col >= left) return;
         const int row0 = (g0 + gi) * kRows;
-        const size_t coff = (size_t)c_lo + (size_t)s * kCap + (size_t)min(4 * tid, left - 4);
+        const size_t coff = (size_t)win_col(c_lo, s * kCap + min(4 * tid, left - 4), N);  // windows are cyclic
         stage_load(st, Yin, N, c4, row0, A, cat_last, coff);
     };
     auto store_tile = [&](int P, int t) {
@@ -768,7 +768,7 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     const uint32_t qp = w.qsel[(size_t)b * kBlk + tid];
     const int cat_last = cat[A - 1];
     // byte offset of my four columns in a row; lanes past the window re-read its last columns
-    const uint32_t ld_off = 4u * (uint32_t)(c_lo + min(4 * tid, ncols - 4));
+    const uint32_t ld_off = 4u * (uint32_t)win_col(c_lo, min(4 * tid, ncols - 4), N);  // windows are cyclic
     const char* ld_row[kRows] = {nullptr, nullptr, nullptr, nullptr};  // bases of the 4 rows of the tile to load (scalar)
 
     auto fetch_rows = [&](int t) {
@@ -926,7 +926,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
         const int left = ncols - s * kCap;
         if (wave_col >= left) return;
         const int row0 = g * kRows;
-        const size_t coff = (size_t)c_lo + (size_t)s * kCap + (size_t)min(4 * tid, left - 4);
+        const size_t coff = (size_t)win_col(c_lo, s * kCap + min(4 * tid, left - 4), N);  // windows are cyclic
         stage_load(st, Yin, N, c4, row0, A, cat_last, coff);
     };
     auto store_tile = [&](int P, int t) {
@@ -965,13 +965,13 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
         const int nlive = min(kRows, A - row0);
         if (nspill > 0) {  // connections that did not fit a stage: gathered from global memory
             const int4 cg = *reinterpret_cast<const int4*>(cat + (size_t)g * kRows);
-            const float* p0 = Yin + (size_t)cg.x * N + c_lo;
-            const float* p1 = Yin + (size_t)(nlive > 1 ? cg.y : cat_last) * N + c_lo;
-            const float* p2 = Yin + (size_t)(nlive > 2 ? cg.z : cat_last) * N + c_lo;
-            const float* p3 = Yin + (size_t)(nlive > 3 ? cg.w : cat_last) * N + c_lo;
+            const float* p0 = Yin + (size_t)cg.x * N;
+            const float* p1 = Yin + (size_t)(nlive > 1 ? cg.y : cat_last) * N;
+            const float* p2 = Yin + (size_t)(nlive > 2 ? cg.z : cat_last) * N;
+            const float* p3 = Yin + (size_t)(nlive > 3 ? cg.w : cat_last) * N;
             for (int e = 0; e < nspill; ++e) {
                 const size_t se = ((size_t)b * kSpill + e) * kBlk + tid;
-                const int col = w.spill_col[se];
+                const int col = win_col(c_lo, w.spill_col[se], N);  // windows are cyclic
                 const float v = w.spill_val[se];
                 a[0] = __builtin_fmaf(p0[col], v, a[0]);
                 a[1] = __builtin_fmaf(p1[col], v, a[1]);
@@ -1120,7 +1120,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
         const int left = ncols - s * kCap;
         if (wave_col >= left) return;
         const int row0 = g * kRows;
-        const size_t coff = (size_t)c_lo + (size_t)s * kCap + (size_t)min(4 * tid, left - 4);
+        const size_t coff = (size_t)win_col(c_lo, s * kCap + min(4 * tid, left - 4), N);  // windows are cyclic
         stage_load(st, Yin, N, c4, row0, A, cat_last, coff);
     };
     auto store_tile = [&](int P, int t) {
@@ -1165,13 +1165,13 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
         const int row0 = g * kRows;
         if (nspill > 0) {
             const int4 cg = *reinterpret_cast<const int4*>(cat + (size_t)g * kRows);
-            const float* p0 = Yin + (size_t)cg.x * N + c_lo;
-            const float* p1 = Yin + (size_t)(nlive > 1 ? cg.y : cat_last) * N + c_lo;
-            const float* p2 = Yin + (size_t)(nlive > 2 ? cg.z : cat_last) * N + c_lo;
-            const float* p3 = Yin + (size_t)(nlive > 3 ? cg.w : cat_last) * N + c_lo;
+            const float* p0 = Yin + (size_t)cg.x * N;
+            const float* p1 = Yin + (size_t)(nlive > 1 ? cg.y : cat_last) * N;
+            const float* p2 = Yin + (size_t)(nlive > 2 ? cg.z : cat_last) * N;
+            const float* p3 = Yin + (size_t)(nlive > 3 ? cg.w : cat_last) * N;
             for (int e = 0; e < nspill; ++e) {
                 const size_t se = ((size_t)blk * kSpill + e) * kBlk + tid;
-                const int col = w.spill_col[se];
+                const int col = win_col(c_lo, w.spill_col[se], N);  // windows are cyclic
                 const float v = w.spill_val[se];
                 a[0] = __builtin_fmaf(p0[col], v, a[0]);
                 a[1] = __builtin_fmaf(p1[col], v, a[1]);
@@ -1383,7 +1383,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
         const int left = ncols - s * kCap;  // <= 0 for the idle fourth step of a 3-stage layer
         if (wave_col >= left) return;
         const int row0 = (g0 + (t >> LNS)) * kRows;
-        const uint32_t col = s == nstage - 1 ? col_last : col_full + (uint32_t)(s * kCap);
+        uint32_t col = s == nstage - 1 ? col_last : col_full + (uint32_t)(s * kCap);
+        if (col >= (uint32_t)N) col -= (uint32_t)N;  // windows are cyclic
         const float* r0 = Yin + (size_t)c4.x * N;  // row bases are the same for the whole workgroup
         const float* r1 = Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N;
         const float* r2 = Yin + (size_t)(row0 + 2 < A ? c4.z : cat_last) * N;
@@ -1648,15 +1649,18 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
                                                             int* __restrict__ widest,
                                                             const float* __restrict__ val = nullptr,
                                                             int* __restrict__ nonuniform = nullptr) {
-    __shared__ int s_lo, s_hi;
+    // The window is cyclic (see win_rel): two candidate cuts of the circle are tried, the row end and the
+    // row's middle (columns shifted by h), and the narrower window wins.
+    __shared__ int s_lo, s_hi, s_lo2, s_hi2;
     const int tid = threadIdx.x;
     const int j = blockIdx.x * kBlk + tid;
+    const int h = (N / 2) & ~3;
     if (tid == 0) {
-        s_lo = N;
-        s_hi = -1;
+        s_lo = s_lo2 = N;
+        s_hi = s_hi2 = -1;
     }
     __syncthreads();
-    int lo = N, hi = -1;
+    int lo = N, hi = -1, lo2 = N, hi2 = -1;
     if (j < N) {
         for (int k = 0; k < kNnz; ++k) {
             const int c = idx[(size_t)j * kNnz + k];
@@ -1665,6 +1669,9 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
             } else {
                 lo = min(lo, c);
                 hi = max(hi, c);
+                const int c2 = c + h >= N ? c + h - N : c + h;
+                lo2 = min(lo2, c2);
+                hi2 = max(hi2, c2);
             }
         }
         if (val) {  // does the whole layer use one weight (bit for bit)?
@@ -1676,12 +1683,20 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
     }
     atomicMin(&s_lo, lo);
     atomicMax(&s_hi, hi);
+    atomicMin(&s_lo2, lo2);
+    atomicMax(&s_hi2, hi2);
     __syncthreads();
     if (tid == 0) {
         int c_lo = 0, ncols = 4;
         if (s_hi >= s_lo) {
             c_lo = s_lo & ~3;
             ncols = ((s_hi + 1 - c_lo) + 3) & ~3;
+            const int c_lo2 = s_lo2 & ~3;
+            const int ncols2 = ((s_hi2 + 1 - c_lo2) + 3) & ~3;
+            if (ncols2 < ncols) {  // narrower when cut at the row's middle: back to unshifted columns
+                ncols = ncols2;
+                c_lo = c_lo2 - h < 0 ? c_lo2 - h + N : c_lo2 - h;
+            }
         }
         win[blockIdx.x] = make_int2(c_lo, ncols);
         atomicMax(widest, ncols);  // the layer's widest window (zero before the launch)
@@ -1798,8 +1813,9 @@ __global__ __launch_bounds__(64) void pair_merge_kernel(int2* __restrict__ win, 
     if (candidate) {
         for (int u = t; u < nblk / 2; u += 64) {
             const int2 a = win[2 * u], c = win[2 * u + 1];
-            const int lo = min(a.x, c.x), hi = max(a.x + a.y, c.x + c.y);
-            atomicMax(&s_max, hi - lo);
+            int ux, uy;
+            win_union(a.x, a.y, c.x, c.y, N, ux, uy);
+            atomicMax(&s_max, uy);
         }
     }
     __syncthreads();
@@ -1813,8 +1829,9 @@ __global__ __launch_bounds__(64) void pair_merge_kernel(int2* __restrict__ win, 
     if (ok) {
         for (int u = t; u < nblk / 2; u += 64) {
             const int2 a = win[2 * u], c = win[2 * u + 1];
-            const int lo = min(a.x, c.x), hi = max(a.x + a.y, c.x + c.y);
-            win[2 * u] = win[2 * u + 1] = make_int2(lo, hi - lo);
+            int ux, uy;
+            win_union(a.x, a.y, c.x, c.y, N, ux, uy);
+            win[2 * u] = win[2 * u + 1] = make_int2(ux, uy);
         }
         if (t == 0) atomicMax(widest, s_max);
     }
@@ -1872,7 +1889,7 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
         const int j = b * kBlk + (e >> 5);
         if (j >= N) return -1;
         const int c = idx[(size_t)j * kNnz + (e & 31)];
-        return (c < 0 || c >= N) ? 0 : c - c_lo;  // out-of-range columns were reported; keep them harmless
+        return (c < 0 || c >= N) ? 0 : win_rel(c, c_lo, N);  // out-of-range columns were reported; keep them harmless
     };
     for (int e = lane; e < UB * kNnz * kBlk; e += kBalanceThreads) {
         const int r = rel_of(e);
@@ -1992,14 +2009,14 @@ __global__ __launch_bounds__(kOrderPackThreads) void order_pack_kernel(const int
     order_group(
         order_scratch[threadIdx.x], kNnz,
         [&](int l, int k) -> unsigned {
-            return (neuron(l) < N) ? (slot_of((uint32_t)(column(l, k) - c_lo) & (kCap - 1)) & 15u) : 255u;
+            return (neuron(l) < N) ? (slot_of((uint32_t)win_rel(column(l, k), c_lo, N) & (kCap - 1)) & 15u) : 255u;
         },
         [&](int l, int step, int k) {
             const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
             const size_t src = (size_t)neuron(l) * kNnz + k;
             const int c = idx[src];
             const bool ok = c >= 0 && c < N;
-            const uint32_t r = ok ? (uint32_t)(c - c_lo) : 0u;  // stage number | slot inside the stage
+            const uint32_t r = ok ? (uint32_t)win_rel(c, c_lo, N) : 0u;  // stage number | slot inside the stage
             rel[e] = (uint16_t)((r & ~(uint32_t)(kCap - 1)) | slot_of(r & (kCap - 1)));
             wval[e] = ok ? val[src] : 0.0f;
         });
@@ -2047,7 +2064,7 @@ __global__ __launch_bounds__(kOrderThreads) void wide_pack_kernel(const int32_t*
     auto neuron = [&](int l) -> int { return b * kBlk + wave0 + lane_of_group(set, l); };
     auto rel_of = [&](int l, int k) -> int {  // column relative to the window; bad columns were reported
         const int c = idx[(size_t)neuron(l) * kNnz + k];
-        return (c < 0 || c >= N) ? 0 : c - c_lo;
+        return (c < 0 || c >= N) ? 0 : win_rel(c, c_lo, N);
     };
     // phase 1: counts, spills
     for (int l = 0; l < kGroup; ++l) {
@@ -2121,7 +2138,7 @@ __global__ __launch_bounds__(kOrderThreads) void wide_pack_kernel(const int32_t*
                 const size_t src = (size_t)neuron(l) * kNnz + k;
                 const int c = idx[src];
                 const bool ok = c >= 0 && c < N;
-                const uint32_t slot = col_slot((uint32_t)(ok ? c - c_lo : 0) & (kCap - 1));
+                const uint32_t slot = col_slot((uint32_t)(ok ? win_rel(c, c_lo, N) : 0) & (kCap - 1));
                 pk[entry(step, wave0 + lane_of_group(set, l))] =
                     make_uint2(slot, __builtin_bit_cast(uint32_t, ok ? val[src] : 0.0f));
                 quads_of_step[step] |= (uint16_t)(1u << (slot & 15u));

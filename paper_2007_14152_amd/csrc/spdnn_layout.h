@@ -62,6 +62,46 @@ SPDNN_HD inline uint32_t store_group(uint32_t c) {  // of stage-local column c
     return (((t >> 6) << 2) | set_of_lane(t & 63u)) << 2 | (c & 3u);
 }
 
+// Column windows are cyclic: the window {c_lo, ncols} of a block of output neurons covers the columns
+// (c_lo + i) mod N, i < ncols (c_lo, ncols and N multiples of 4).  The strided, modular patterns that the
+// challenge networks are built from wrap around the row end; their footprint is narrow only on the circle.
+SPDNN_HD inline int win_rel(int c, int c_lo, int N) {  // position of column c inside the window starting at c_lo
+    const int r = c - c_lo;
+    return r < 0 ? r + N : r;
+}
+SPDNN_HD inline int win_col(int c_lo, int rel, int N) {  // column at position rel (< N) of that window
+    const int c = c_lo + rel;
+    return c >= N ? c - N : c;
+}
+// Smallest cyclic window holding the windows {ax, ay} and {cx, cy} (a length of 0 = empty).
+SPDNN_HD inline void win_union(int ax, int ay, int cx, int cy, int N, int& ox, int& oy) {
+    if (cy == 0) {
+        ox = ax;
+        oy = ay;
+        return;
+    }
+    if (ay == 0) {
+        ox = cx;
+        oy = cy;
+        return;
+    }
+    const int d = win_rel(cx, ax, N);       // c starts d columns after a ...
+    const int e = d == 0 ? 0 : N - d;       // ... which is the same as a starting e columns after c
+    const int span_a = ay > d + cy ? ay : d + cy;
+    const int span_c = cy > e + ay ? cy : e + ay;
+    if (span_a <= span_c) {
+        ox = ax;
+        oy = span_a;
+    } else {
+        ox = cx;
+        oy = span_c;
+    }
+    if (oy >= N) {
+        ox = 0;
+        oy = N;
+    }
+}
+
 // Tile of the two-rows-per-entry kernel (fused_row2_kernel): an entry is 8 bytes, the two rows'
 // values of one column, at byte 8 * row2_pos(c) for stage-local column c.  Staging lane t owns columns
 // 4t..4t+3 and writes them with 8-byte stores, one per column; a ds_write_b64 / ds_read_b64 is served

@@ -40,16 +40,15 @@ struct Row2Weights {
                          // last group repeat it.  Tile column 4g + a is then row column map[g] + a.
 };
 
-// Column window of unit u: the union of its four blocks' windows (c_lo a multiple of 4).
-__device__ __forceinline__ int2 row2_window(const int2* __restrict__ win, int u) {
-    int lo = 1 << 30, hi = 0;
+// Column window of unit u: the union of its four blocks' (cyclic) windows; c_lo a multiple of 4.
+__device__ __forceinline__ int2 row2_window(const int2* __restrict__ win, int u, int N) {
+    int x = 0, y = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int2 w = win[4 * u + i];
-        lo = min(lo, w.x);
-        hi = max(hi, w.x + w.y);
+        win_union(x, y, w.x, w.y, N, x, y);
     }
-    return make_int2(lo, hi - lo);
+    return make_int2(x, y);
 }
 
 // 16 connections of one neuron: acc[r] = fma(tile[col_k][r], w, acc[r]), k = 0..15 in that order.
@@ -183,7 +182,7 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     if (!my_work(nunit, G, Q, count_ptr, wi, kRows2)) return;
     const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const bool gathered = w.map != nullptr;  // the tile is a gathered list of 4-column groups, not a window
-    const int2 win = gathered ? make_int2(0, kRow2Cols) : row2_window(w.win, u);
+    const int2 win = gathered ? make_int2(0, kRow2Cols) : row2_window(w.win, u, N);
     const int c_lo = win.x;
     const int ncols = win.y;  // <= kRow2Cols, a multiple of 4
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds4;
@@ -216,23 +215,23 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     const uint32_t st_addr = lds_base + 8u * (((4u * tid) & ~127u) | (tid & 31u));  // entry of column 4t; +256 per column
     const int cat_last = cat[A - 1];
     const int T = g1 - g0;
-    // Byte offset of my four columns inside a segment: 16 * tid, except that in a narrower last segment
-    // the lanes past the window re-read its last columns.  The segment's own offset is scalar.  With a
-    // gathered footprint the offsets come from the unit's list instead (and the segment offset is zero).
+    // Byte offset, from the start of a row, of my four columns in every segment.  In a narrower last segment
+    // the lanes past the window re-read its last columns; the window is cyclic (it may run over the row end);
+    // with a gathered footprint the offsets come from the unit's list.
     const int last_cols = ncols - (nseg - 1) * kRow2Seg;  // columns of the last segment (a multiple of 4, >= 4)
     uint32_t off[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-        off[s] = s == nseg - 1 ? 4u * (uint32_t)min(4 * tid, last_cols - 4) : 16u * (uint32_t)tid;
+        const int rel = s * kRow2Seg + (s == nseg - 1 ? min(4 * tid, last_cols - 4) : 4 * tid);
+        off[s] = 4u * (uint32_t)win_col(c_lo, min(rel, ncols - 4), N);
         if (gathered) off[s] = 4u * (uint32_t)w.map[(size_t)u * (kRow2Cols / 4) + s * kBlk + tid];
     }
-    const size_t seg_bytes = gathered ? 0 : (size_t)kRow2Seg * 4;
     const char* ld_row[kRows2] = {nullptr, nullptr};  // row bases of the tile being loaded, at the window's first column
     auto tile_rows = [&](int t) {
         const int2 c2 = *reinterpret_cast<const int2*>(cat + (size_t)(g0 + t) * kRows2);
         const int row0 = (g0 + t) * kRows2;
-        ld_row[0] = reinterpret_cast<const char*>(Yin + (size_t)c2.x * N + c_lo);
-        ld_row[1] = reinterpret_cast<const char*>(Yin + (size_t)(row0 + 1 < A ? c2.y : cat_last) * N + c_lo);
+        ld_row[0] = reinterpret_cast<const char*>(Yin + (size_t)c2.x * N);
+        ld_row[1] = reinterpret_cast<const char*>(Yin + (size_t)(row0 + 1 < A ? c2.y : cat_last) * N);
     };
     // One 16-byte load per lane: scalar base + 32-bit lane offset.  Written as an instruction so that the
     // addresses stay out of the vector registers; the compiler therefore does not know that the result
@@ -240,8 +239,7 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     auto load_piece = [&](int i) {  // piece i = row i & 1 of segment i >> 1; i is a constant wherever this is called
         const int s = i >> 1, r = i & 1;
         if (s < nseg) {
-            const char* base = ld_row[r] + (size_t)s * seg_bytes;
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(st[s][r]) : "v"(off[s]), "s"(base) : "memory");
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(st[s][r]) : "v"(off[s]), "s"(ld_row[r]) : "memory");
         }
     };
     auto wait_tile = [&]() {  // every load (and store) issued so far has completed; the staged values may be touched
@@ -399,12 +397,12 @@ __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32
     const int in_unit = g - u * groups_per_unit;
     const int s = in_unit / (kBlk / kGroup32);
     const int lane0 = (in_unit - s * (kBlk / kGroup32)) * kGroup32;
-    const int c_lo = rank ? 0 : row2_window(win, u).x;
+    const int c_lo = rank ? 0 : row2_window(win, u, N).x;
     auto pos_of = [&](int l, int k) -> uint32_t {  // out-of-range columns were reported; keep them harmless
         int c = idx[((size_t)u * kUnit4 + s * kBlk + lane0 + l) * kNnz + k];
         if (c < 0 || c >= N) c = c_lo;
         // tile column: inside the window, or in the gathered list group rank[c >> 2], column c & 3 of it
-        const uint32_t tc = rank ? 4u * rank[(size_t)u * (N / 4) + (c >> 2)] + (uint32_t)(c & 3) : (uint32_t)(c - c_lo);
+        const uint32_t tc = rank ? 4u * rank[(size_t)u * (N / 4) + (c >> 2)] + (uint32_t)(c & 3) : (uint32_t)win_rel(c, c_lo, N);
         return row2_pos(tc & (kRow2Cols - 1));
     };
     order_group32(

@@ -545,7 +545,7 @@ def test_scattered_windows():
     ref = oracle.infer(idx, val, bias, Y0)
     assert 0 < ref.n_active < batch
     m = sp.Model(idx, val, bias)
-    assert m.widest_window > N - 64
+    assert m.widest_window > N - 512
     n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
     m.close()
     common, _ = check_against_oracle(ref, n, rows, Y, what="scattered windows")
@@ -572,6 +572,42 @@ def test_scattered_windows_gathered_footprint(N, w, batch):
     n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
     m.close()
     common, _ = check_against_oracle(ref, n, rows, Y, what="scattered windows, gathered footprint")
+    assert common > 0
+
+
+@pytest.mark.parametrize("N,strides,uniform,kinds", [
+    (1024, (1, 32), True, "SINGLE"),            # one block: the whole row is its window
+    (8192, (1, 32), True, "PAIR"),              # the last unit's window runs over the row end
+    (8192, (32, 1), False, "SINGLE"),           # the same with two weight values: one neuron per lane
+    (8192, (160,), False, "STAGED"),            # two stages, cyclic
+    (16384, (256, 1, 32), True, "ROW2 PAIR PAIR"),  # two-row tiles whose window wraps
+    (16384, (256,), False, "WIDE"),             # three stages, one neuron per lane
+    (10240, (256,), True, "WIDE_PAIR4"),        # three stages, two neurons per lane, step lists in registers
+    (32768, (700,), True, "WIDE_PAIR"),         # six stages, two neurons per lane
+    (65536, (1500,), False, "WIDE"),            # twelve stages of eight steps
+])
+def test_strided_layers_wrap_around_the_row_end(N, strides, uniform, kinds):
+    """Strided, modular patterns (neuron j reads (j + k*S) mod N): the footprint of the last blocks runs
+    over the row end, so their windows are narrow only as arcs of the circle of columns.  Every kernel
+    family with such cyclic windows, against the oracle."""
+    import paper_2007_14152_amd as sp
+    rng = np.random.default_rng(N + len(strides))
+    L, batch = len(strides), 11
+    idx = [synth.gen_layer_strided(N, s_) for s_ in strides]
+    if uniform:
+        val = [synth.gen_values(N) for _ in range(L)]
+    else:
+        val = [rng.uniform(0.03, 0.1, size=(N, 32)).astype(np.float32) for _ in range(L)]
+    bias = synth.gen_bias(N, -0.3)
+    Y0 = synth.gen_y0(batch, N, 5, density="mixed")
+    ref = oracle.infer(idx, val, bias, Y0)
+    assert 0 < ref.n_active <= batch
+    m = sp.Model(idx, val, bias)
+    want = [getattr(sp, "SPDNN_KERNEL_" + k) for k in kinds.split()]
+    assert [m.layer_kernel(l) for l in range(L)] == (want if len(want) == L else want * L)
+    n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+    m.close()
+    common, _ = check_against_oracle(ref, n, rows, Y, what="strided N=%d %s" % (N, strides))
     assert common > 0
 
 

@@ -103,3 +103,36 @@ def test_two_row_tile_layout(lay):
         for half in range(0, 4096, 32):           # lanes half .. half+31 store their column a together
             assert sorted((pos[4 * t[half:half + 32] + a] % 32).tolist()) == list(range(32))
     assert np.all(pos % 32 == (np.arange(16384) >> 2) % 32)
+
+
+def test_cyclic_windows(lay):
+    """Windows are arcs of the circle of N columns: win_rel / win_col are inverse to each other, and
+    win_union returns the shortest arc that holds both arguments (brute force on a small circle)."""
+    N = 48
+    for c_lo in range(0, N, 4):
+        for c in range(N):
+            r = lay.spdnn_win_rel_host(c, c_lo, N)
+            assert 0 <= r < N and lay.spdnn_win_col_host(c_lo, r, N) == c
+    rng = np.random.default_rng(3)
+    out = (ctypes.c_int * 2)()
+
+    def members(x, y):
+        return {(x + i) % N for i in range(y)}
+
+    for _ in range(400):
+        ax, cx = (int(v) for v in rng.integers(0, N, 2))
+        ay, cy = (int(v) for v in rng.integers(0, N // 2, 2))
+        lay.spdnn_win_union_host(ax, ay, cx, cy, N, out)
+        ux, uy = out[0], out[1]
+        need = members(ax, ay) | members(cx, cy)
+        assert need <= members(ux, uy) and uy <= N
+        # no shorter arc holds both: try every start
+        best = min((y for x in range(N) for y in range(N + 1) if need <= members(x, y)), default=0)
+        if ay and cy:
+            # both arcs must be covered whole, in one piece each: the shortest such arc starts at one of the two starts
+            cand = []
+            for x, first, second in ((ax, (ax, ay), (cx, cy)), (cx, (cx, cy), (ax, ay))):
+                d = (second[0] - first[0]) % N
+                cand.append(max(first[1], d + second[1]))
+            assert uy == min(min(cand), N)
+        assert uy >= best
