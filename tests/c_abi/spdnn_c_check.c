@@ -1,6 +1,9 @@
 /* The C ABI used from plain C (gcc, C99): builds a small model with spdnn_create, runs
  * spdnn_infer and checks the result against a closed form of Eq. 1 (Section II-A-1).
  *
+ * The same inference is then repeated through spdnn_infer_static (no work arena) and spdnn_infer_host
+ * (inputs in host memory, in batches of two rows).
+ *
  * Model: N neurons, L layers, neuron j connected to columns (j + 3k) mod N, k = 0..31, all
  * weights 1/16, bias -0.25.  A row of constant c then maps to the constant
  * min(max(2c - 0.25, 0), 32) whatever the pattern (32 weights of 1/16 sum to 2, and all the
@@ -110,6 +113,44 @@ int main(void) {
                         (double)want_val[r]);
                 return 1;
             }
+    }
+    /* the same inference without a work arena (static scratch) and with the inputs left in host memory,
+     * two rows at a time: same rows, same values */
+    {
+        int32_t n2 = -1, rows2[BATCH];
+        int which;
+        size_t hbytes = 0;
+        void* harena = NULL;
+        CHECK_SP(spdnn_host_work_bytes(N, 2, &hbytes));
+        CHECK_HIP(hipMalloc(&harena, hbytes));
+        for (which = 0; which < 2; ++which) {
+            CHECK_HIP(hipMemset(rows_dev, 0xff, sizeof(int32_t) * BATCH));
+            CHECK_HIP(hipMemset(yf_dev, 0xff, sizeof(float) * BATCH * N));
+            if (which == 0)
+                CHECK_SP(spdnn_infer_static(net, (const float*)y0_dev, BATCH, &n2, (int32_t*)rows_dev, (float*)yf_dev));
+            else
+                CHECK_SP(spdnn_infer_host(net, y0, BATCH, 2, harena, hbytes, &n2, (int32_t*)rows_dev, (float*)yf_dev));
+            if (n2 != want_n) {
+                fprintf(stderr, "entry point %d: n_active = %d, expected %d\n", which, (int)n2, want_n);
+                return 1;
+            }
+            CHECK_HIP(hipMemcpy(rows2, rows_dev, sizeof(int32_t) * (size_t)want_n, hipMemcpyDeviceToHost));
+            CHECK_HIP(hipMemcpy(yf, yf_dev, sizeof(float) * (size_t)want_n * N, hipMemcpyDeviceToHost));
+            for (r = 0; r < want_n; ++r) {
+                if (rows2[r] != want_rows[r]) {
+                    fprintf(stderr, "entry point %d: active row %d is %d, expected %d\n", which, r, (int)rows2[r],
+                            (int)want_rows[r]);
+                    return 1;
+                }
+                for (j = 0; j < N; ++j)
+                    if (fabsf(yf[r * N + j] - want_val[r]) > 1e-5f * want_val[r]) {
+                        fprintf(stderr, "entry point %d: row %d neuron %d: %g, expected %g\n", which, (int)rows2[r], j,
+                                (double)yf[r * N + j], (double)want_val[r]);
+                        return 1;
+                    }
+            }
+        }
+        hipFree(harena);
     }
     int32_t kind = -1, passes = -1;
     CHECK_SP(spdnn_layer_kernel(net, 0, &kind));
