@@ -22,7 +22,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-NO_SCRATCH_KERNELS = ["fused_row2_kernel"]
+NO_SCRATCH_KERNELS = ["fused_row2_kernel", "fused_pair_kernel"]
 
 
 def _resource_usage(text):

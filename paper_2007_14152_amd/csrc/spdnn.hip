@@ -163,10 +163,11 @@ size_t ooc_device_bytes_for(int32_t N, int32_t L, int nstage_cap) {
 
 struct WorkView {
     float* Y[2];
-    int* cat[2];
-    int* gid[2];
-    uint8_t* flags[2];  // one byte per row; layer l raises flags[l & 1]
-    int* count[2];      // layer l reads count[l & 1]
+    int* cat[2];        // layer l writes and reads cat[l & 1]: slots, in layer l-1's buffer, of the rows active on entry
+    int* gid[2];        // gid[l & 1]: their original row numbers (derived from gid[(l + 1) & 1], layer l-1's)
+    uint8_t* flags[3];  // one byte per row; layer l raises flags[l % 3], reads flags[(l + 2) % 3] (layer l-1's) and
+                        // clears flags[(l + 1) % 3] for layer l+1
+    int* count[2];      // count[l & 1]: rows active on entry to layer l, written by layer l's kernel
 };
 size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
     size_t o = 0;
@@ -185,7 +186,7 @@ size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
         o += lb;
     }
     const size_t fb = up((size_t)batch + 16);  // flags are read 16 bytes at a time
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 3; ++i) {
         if (v) v->flags[i] = reinterpret_cast<uint8_t*>(base + o);
         o += fb;
     }
@@ -687,8 +688,9 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
 
     for (int32_t l = 1; l <= L; ++l) h->host_counts[l] = -1;  // "not reported yet"
     h->host_counts[0] = batch;
-    spdnn::init_lists_kernel<<<(batch + 255) / 256, 256, 0, s>>>(wv.cat[0], wv.gid[0], wv.flags[0], wv.flags[1], wv.count[0],
-                                                                 batch, row_offset);
+    // "layer -1": every row of the batch is flagged alive, under its own number
+    spdnn::init_lists_kernel<<<(batch + 255) / 256, 256, 0, s>>>(wv.gid[1], wv.flags[2], wv.flags[0], wv.count[1], batch,
+                                                                 row_offset);
     int32_t bound = batch;  // upper bound of the rows active at the layer being launched
     int32_t run = 0;        // layers launched
     // Out-of-core weights (Section III-B-1): pass p runs from device slot p & 1.  The copy stream fills
@@ -717,6 +719,17 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
         for (int32_t p = h->first_pass[l]; p < h->first_pass[l + 1]; ++p) {
             const LayerDesc& d = h->layers[p];
             if (h->ooc_host) HIP_TRY(hipStreamWaitEvent(s, h->ooc_ready[p & 1], 0));
+            // The layer's first kernel compacts the list of active rows on its way in (the flags layer l-1
+            // raised -> slots and row numbers); later passes of the same layer find the lists in place.
+            spdnn::RowLists rl;
+            rl.flags_prev = p == h->first_pass[l] ? wv.flags[(l + 2) % 3] : nullptr;
+            rl.count_prev = wv.count[(l + 1) & 1];
+            rl.gid_prev = wv.gid[(l + 1) & 1];
+            rl.cat = wv.cat[l & 1];
+            rl.gid = wv.gid[l & 1];
+            rl.count = wv.count[l & 1];
+            rl.host_count = h->host_counts + l;
+            rl.flags_clear = wv.flags[(l + 1) % 3];
             // launch shape: one workgroup per CU; the rows are cut into Q chunks per output block
             const int32_t rows_per_group = d.mode == kRow2 ? spdnn::kRows2 : spdnn::kRows;
             const int32_t ngroups = (bound + rows_per_group - 1) / rows_per_group;
@@ -740,37 +753,37 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
             const size_t lds = spdnn::tile_pair_bytes((d.lds_cols + 255) / 256 * 256);  // whole waves of 256 columns
             if (d.mode == kRow2)
                 spdnn::fused_row2_kernel<<<grid, spdnn::kBlk, spdnn::kRow2LdsBytes, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.r2, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, Yout, wv.flags[l % 3], rl, d.r2, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.multi && d.mode == kStaged)
                 spdnn::fused_layer_kernel<true, true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, G, Q, d.pass);
+                    Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q, d.pass);
             else if (d.multi)
                 spdnn::fused_layer_kernel<false, true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, G, Q, d.pass);
+                    Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q, d.pass);
             else if (d.mode == kPair)
                 spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWidePair && d.pair4 && d.ww.nstage == 2)  // + the all-zero entries and the spill table
                 spdnn::fused_wide_pair4_kernel<2, 32><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, Yout, wv.flags[l % 3], rl, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWidePair && d.pair4)
                 spdnn::fused_wide_pair4_kernel<4, 16><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, Yout, wv.flags[l % 3], rl, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWidePair)
                 spdnn::fused_wide_pair_kernel<<<grid, spdnn::kBlk, lds + spdnn::kPadLds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
+                    Yin, Yout, wv.flags[l % 3], rl, d.ww, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWide && d.ww.nstage > 8)
                 spdnn::fused_wide_kernel<8><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q);
+                    Yin, Yout, wv.flags[l % 3], rl, d.ww, h->bias_dev, N, ncb, G, Q);
             else if (d.mode == kWide)
                 spdnn::fused_wide_kernel<16><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.ww, h->bias_dev, N, ncb, G, Q);
+                    Yin, Yout, wv.flags[l % 3], rl, d.ww, h->bias_dev, N, ncb, G, Q);
             else if (d.mode == kStaged)
                 spdnn::fused_layer_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, G, Q);
+                    Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q);
             else
                 spdnn::fused_layer_kernel<false><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, wv.cat[l & 1], Yout, wv.flags[l & 1], wv.count[l & 1], d.w, h->bias_dev, N, h->nblk, G, Q);
+                    Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q);
             if (h->ooc_host) {  // the slot is free once this kernel is done: refill it with pass p + 2
                 HIP_TRY(hipEventRecord(h->ooc_freed[p & 1], s));
                 if (p + 2 < P) {
@@ -780,18 +793,16 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
             }
         }
         if (h->profiling) HIP_TRY(hipEventRecord(h->t1[l], s));
-        spdnn::compact_kernel<<<spdnn::kCompactWGs, 1024, 0, s>>>(wv.flags[l & 1], wv.flags[(l + 1) & 1], wv.count[l & 1],
-                                                  wv.count[(l + 1) & 1], wv.gid[l & 1], wv.gid[(l + 1) & 1],
-                                                  wv.cat[(l + 1) & 1], h->host_counts + l + 1);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(h->lag_ev[l % kLag], s));
         run = l + 1;
-        // Feedback with bounded lag: the survivor count of layer l+1-kLag bounds all later ones.  The
-        // compaction kernel stores it to pinned host memory, which is polled here; the layer's event is
-        // looked at only so that a failed launch ends the wait.
-        if (l + 1 >= kLag) {
-            const int32_t lr = l + 1 - kLag;
-            volatile int* slot = h->host_counts + lr + 1;
+        // Feedback with bounded lag: the number of rows active on entry to layer l+2-kLag bounds all later
+        // ones.  That layer's kernel stores it to pinned host memory as it starts, which is polled here
+        // (so at most kLag-1 kernels are queued behind the running one); the layer's event is looked at
+        // only so that a failed launch ends the wait.
+        if (l + 2 >= kLag) {
+            const int32_t lr = l + 2 - kLag;
+            volatile int* slot = h->host_counts + lr;
             int32_t c = *slot;
             for (uint32_t spin = 1; c < 0; ++spin) {
                 if ((spin & 1023u) == 0) {
@@ -810,14 +821,19 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
             if (bound == 0) break;
         }
     }
+    // the rows that survive the last layer launched: the same compaction, as a kernel of its own
+    spdnn::compact_kernel<<<spdnn::kCompactWGs, 1024, 0, s>>>(wv.flags[(run + 2) % 3], wv.flags[(run + 1) % 3],
+                                                              wv.count[(run + 1) & 1], wv.count[run & 1], wv.gid[(run + 1) & 1],
+                                                              wv.gid[run & 1], wv.cat[run & 1], h->host_counts + run);
+    HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(s));
     const int32_t n = h->host_counts[run];
     if (n < 0) return fail(SPDNN_EHIP, "layer %d finished without reporting its active rows", run - 1);
     *n_active_host = n;
     if (n > 0) {
         const int32_t lf = run - 1;  // == L-1 here: rows survive only if every layer ran
-        const int* cat_f = wv.cat[(lf + 1) & 1];
-        const int* gid_f = wv.gid[(lf + 1) & 1];
+        const int* cat_f = wv.cat[run & 1];
+        const int* gid_f = wv.gid[run & 1];
         HIP_TRY(hipMemcpyAsync(active_rows_dev, gid_f, sizeof(int) * (size_t)n, hipMemcpyDeviceToDevice, s));
         if (Y_final_dev) {
             const int n4 = N / 4;

@@ -381,31 +381,211 @@ __device__ __forceinline__ void fma_block8ps(float (&acc)[4], uint32_t p0, uint3
         : "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "memory");
 }
 
-// Workgroup -> (column block, row groups).  A launch has ncb column blocks (output blocks,
-// or 2048-neuron units) times Q row chunks.  Consecutive workgroup ids go to consecutive
-// XCDs (8 of them, each with its own L2); the G column blocks that read the same rows
-// through overlapping windows get ids that are equal modulo 8, so they share one L2.
-// *count_ptr = number of active rows A; a workgroup takes the row groups [g0, g1) of
-// ceil(A / rows_per_group).  Returns false for a workgroup with nothing to do.
+// Number of set bytes among flags[0 .. n), counted by the whole workgroup.  red: 17 ints of LDS.
+// Four 16-byte loads per thread are in flight at a time (the count sits on every workgroup's way in).
+__device__ __forceinline__ int count_flags(const uint8_t* __restrict__ flags, int n, int* red) {
+    const int tid = threadIdx.x;
+    int c = 0;
+    for (int i0 = tid * 16; i0 < n; i0 += 4 * kBlk * 16) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * kBlk * 16;
+            v[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (i + 16 <= n) v[u] = *reinterpret_cast<const uint4*>(flags + i);
+            else
+                for (int k = i; k < n; ++k) c += flags[k];  // the ragged end: one thread, at most 15 bytes
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)  // bytes are 0 or 1: the population count of a word is its number of flags
+            c += __popc(v[u].x) + __popc(v[u].y) + __popc(v[u].z) + __popc(v[u].w);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
+    __syncthreads();  // red may still be read from a call before
+    if ((tid & 63) == 0) red[tid >> 6] = c;
+    __syncthreads();
+    int t = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) t += red[w];
+    return t;
+}
+
+// How a layer's kernel gets its list of active rows (a2, the host loop of Listing 1 between two layers,
+// folded into the layer that needs its result, so that a layer is one launch).  The previous layer
+// left one flag byte per row it wrote ("has a positive output"); every workgroup counts them for
+// itself, works out which row groups of the compacted list are its own, and writes that slice of the
+// list -- the slots of its rows in the buffer the previous layer wrote, and their original row numbers
+// -- before it reads it back.  Workgroups with the same rows (other column blocks) write the same
+// values to the same places; nothing a workgroup reads was written by another workgroup of the launch.
+struct RowLists {
+    const uint8_t* flags_prev;  // [*count_prev] flags of the rows the previous layer wrote; NULL: the lists below are
+                                // complete already (later passes of a layer of several passes)
+    const int* count_prev;      // rows the previous layer wrote
+    const int* gid_prev;        // [*count_prev] their original row numbers
+    int* cat;                   // out: slot (in the previous layer's buffer) of the i-th active row; not written when
+                                // no row died (then it is i)
+    int* gid;                   // out: its original row number
+    int* count;                 // out (workgroup 0): number of active rows A
+    int* host_count;            // out (workgroup 0): the same, in pinned host memory
+    uint8_t* flags_clear;       // the buffer the next layer will raise its flags in: this layer clears its rows of it
+};
+
+// Entries of the list are read from the same address by every lane, but from memory the kernel itself
+// wrote a moment ago, so they arrive in vector registers: back to scalar ones (row bases are scalar
+// operands of the tile loads).
+__device__ __forceinline__ int4 uniform4(int4 v) {
+    return make_int4(__builtin_amdgcn_readfirstlane(v.x), __builtin_amdgcn_readfirstlane(v.y),
+                     __builtin_amdgcn_readfirstlane(v.z), __builtin_amdgcn_readfirstlane(v.w));
+}
+__device__ __forceinline__ int2 uniform2(int2 v) {
+    return make_int2(__builtin_amdgcn_readfirstlane(v.x), __builtin_amdgcn_readfirstlane(v.y));
+}
+
+// 64 consecutive entries of the workgroup's slice of the list, entry k in lane k of one register; a tile's
+// entries are picked out with v_readlane.  The tile loop therefore meets a load from the list, and the
+// wait for it (which also waits for every tile load in flight), once per 64 entries, not once per tile.
+// Entries past the slice's end repeat its last entry: a valid row to re-read, for the ragged last group.
+struct ListWindow {
+    const int* cat;
+    int first, end;  // the slice [first, end) of the list, end > first
+    int lo;          // entries [lo, lo + 64) are held
+    int v;
+    bool identity;   // the list is 0, 1, 2, ...: nothing is read
+    __device__ __forceinline__ ListWindow(const int* cat_, int first_, int end_, bool identity_)
+        : cat(cat_), first(first_), end(end_), lo(first_), identity(identity_) {
+        fill();
+    }
+    __device__ __forceinline__ void fill() {
+        const int e = min(lo + (int)(threadIdx.x & 63), end - 1);
+        v = identity ? e : cat[e];
+    }
+    __device__ __forceinline__ void seek(int e) {  // e: the same in every lane
+        const int want = first + ((e - first) & ~63);
+        if (want != lo) {
+            lo = want;
+            fill();
+        }
+    }
+    __device__ __forceinline__ int4 get4(int e) {  // entries e .. e+3, e - first a multiple of 4
+        seek(e);
+        const int k = e - lo;
+        return make_int4(__builtin_amdgcn_readlane(v, k), __builtin_amdgcn_readlane(v, k + 1),
+                         __builtin_amdgcn_readlane(v, k + 2), __builtin_amdgcn_readlane(v, k + 3));
+    }
+    __device__ __forceinline__ int2 get2(int e) {
+        seek(e);
+        const int k = e - lo;
+        return make_int2(__builtin_amdgcn_readlane(v, k), __builtin_amdgcn_readlane(v, k + 1));
+    }
+    __device__ __forceinline__ int last() const { return identity ? end - 1 : __builtin_amdgcn_readfirstlane(cat[end - 1]); }
+};
+
+// Workgroup -> (column block, row groups): a launch has ncb column blocks times Q chunks of row groups, the G
+// column blocks that read the same rows get workgroup ids that are equal modulo 8 (one XCD, one L2).  The
+// lists are derived on the way.  red: 17 ints, scan: 17 ints of LDS.
 struct WorkItem {
     int cb, A, g0, g1;
+    bool identity;  // no row died in the previous layer: entry i of the list is i, and the list was not written
 };
-__device__ __forceinline__ bool my_work(int ncb, int G, int Q, const int* __restrict__ count_ptr, WorkItem& w,
-                                        int rows_per_group = kRows) {
+__device__ __forceinline__ bool derive_work(const RowLists& rl, int ncb, int G, int Q, WorkItem& w, int rows_per_group,
+                                            int* red, int* scan) {
+    const int tid = threadIdx.x;
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;
     const int unit = (slot / G) * 8 + xcd;
     const int sub = slot - (slot / G) * G;
     const int ngrp = ncb / G;
-    if (unit >= ngrp * Q) return false;
+    const bool has_unit = unit < ngrp * Q;
+    if (!has_unit && blockIdx.x != 0) return false;
+    if (!rl.flags_prev) {  // lists and count are in place
+        if (!has_unit) return false;
+        const int q = unit / ngrp;
+        w.cb = (unit - q * ngrp) * G + sub;
+        w.A = __builtin_amdgcn_readfirstlane(*rl.count);
+        const int ngroups = (w.A + rows_per_group - 1) / rows_per_group;
+        const int per = (ngroups + Q - 1) / Q;
+        w.g0 = q * per;
+        w.g1 = min(ngroups, w.g0 + per);
+        w.identity = w.A == __builtin_amdgcn_readfirstlane(*rl.count_prev);  // as the layer's first pass found it
+        return w.g0 < w.g1;
+    }
+    // the same in every lane: said out loud, so that everything derived from them stays in scalar registers
+    const int Aprev = __builtin_amdgcn_readfirstlane(*rl.count_prev);
+    const int A = __builtin_amdgcn_readfirstlane(count_flags(rl.flags_prev, Aprev, red));
+    if (blockIdx.x == 0 && tid == 0) {
+        *rl.count = A;
+        // the host reads nothing else that this kernel writes before the stream is drained: no release (which
+        // would write back the L2), just a store that goes through to host memory
+        __hip_atomic_store(rl.host_count, A, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    if (!has_unit) return false;
     const int q = unit / ngrp;
     w.cb = (unit - q * ngrp) * G + sub;
-    w.A = *count_ptr;
-    const int ngroups = (w.A + rows_per_group - 1) / rows_per_group;
+    w.A = A;
+    const int ngroups = (A + rows_per_group - 1) / rows_per_group;
     const int per = (ngroups + Q - 1) / Q;
     w.g0 = q * per;
     w.g1 = min(ngroups, w.g0 + per);
-    return w.g0 < w.g1;
+    if (w.g0 >= w.g1) return false;
+    // my slice of the list: ranks [r0, r1) among the set flags (the list's last entry too, which the ragged
+    // last group re-reads: it is in the last slice, and only the workgroups of that slice use it)
+    const int r0 = w.g0 * rows_per_group;
+    const int r1 = min(A, w.g1 * rows_per_group);
+    for (int r = r0 + tid; r < r1; r += kBlk) rl.flags_clear[r] = 0;
+    w.identity = A == Aprev;
+    if (w.identity) {  // nobody died: the slots are 0, 1, 2, ... (not written: ListWindow counts them up itself)
+        for (int r = r0 + tid; r < r1; r += kBlk) rl.gid[r] = rl.gid_prev[r];
+    } else {
+        // walk the flags in chunks of 16 per thread; an exclusive scan over the workgroup's counts gives the ranks
+        const int lane = tid & 63, wave = tid >> 6;
+        int base = 0;  // set flags before the chunk
+        for (int c0 = 0; c0 < Aprev && base < r1; c0 += kBlk * 16) {
+            const int i = c0 + tid * 16;
+            uint32_t f[4] = {0, 0, 0, 0};
+            if (i + 16 <= Aprev) {
+                const uint4 v = *reinterpret_cast<const uint4*>(rl.flags_prev + i);
+                f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+            } else {
+                for (int k = i; k < Aprev; ++k) f[(k - i) >> 2] |= (uint32_t)rl.flags_prev[k] << (8 * ((k - i) & 3));
+            }
+            const int mine = __popc(f[0]) + __popc(f[1]) + __popc(f[2]) + __popc(f[3]);
+            int incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int up = __shfl_up(incl, d, 64);
+                if (lane >= d) incl += up;
+            }
+            __syncthreads();  // scan[] may still be read from the chunk before
+            if (lane == 63) scan[wave] = incl;
+            __syncthreads();
+            if (tid == 0) {
+                int run = 0;
+                for (int k = 0; k < 16; ++k) {
+                    const int t = scan[k];
+                    scan[k] = run;
+                    run += t;
+                }
+                scan[16] = run;
+            }
+            __syncthreads();
+            int rank = base + scan[wave] + incl - mine;
+            if (mine && rank < r1 && rank + mine > r0) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k)
+                    if ((f[k >> 2] >> (8 * (k & 3))) & 1u) {
+                        if (rank >= r0 && rank < r1) {
+                            rl.cat[rank] = i + k;
+                            rl.gid[rank] = rl.gid_prev[i + k];
+                        }
+                        ++rank;
+                    }
+            }
+            base += scan[16];
+        }
+    }
+    if (!w.identity) __syncthreads();  // the slice is written (workgroup-scope release / acquire): it may be read now
+    return true;
 }
 
 // Tile staging shared by the fused kernels.  A lane owns 4 neighbouring columns of the
@@ -538,25 +718,29 @@ __device__ __forceinline__ unsigned finish_rows_pass(float (&a)[kRows], const fl
 // a1: fused SpMM + bias + clipped ReLU for one layer (Eq. 1), plus the per-row
 // "has a positive output" flag that Listings 1 and 2 keep in active[].
 //
-// Yin is read through cat[] (slot of every active row in the buffer written by
-// the previous layer); row i of the active list is written to slot i of Yout.
-// *count_ptr = number of active rows A.  The grid is nblk * G-aligned units
-// (see unit mapping below); a workgroup handles row groups
-// [q*per, (q+1)*per) of ceil(A/4).
+// Yin is read through the list of active rows that the kernel derives first (RowLists:
+// slot of every active row in the buffer written by the previous layer); row i of the
+// list is written to slot i of Yout.  A launch has ncb column blocks (output blocks, or
+// units of 2048 / 4096 neurons) times Q row chunks; consecutive workgroup ids go to
+// consecutive XCDs (8 of them, each with its own L2), and the G column blocks that read
+// the same rows through overlapping windows get ids that are equal modulo 8, so they
+// share one L2.  A workgroup handles row groups [q*per, (q+1)*per) of ceil(A/4).
 //
 // PASSES: the launch is one of several passes over a layer whose neurons have more
 // than 32 connections; `pass` says what the epilogue does (finish_rows_pass).
 // ---------------------------------------------------------------------------
 template <bool MULTI, bool PASSES = false>
 __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
-    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, LayerWeights w,
+    const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
+    RowLists rl, LayerWeights w,
     const float* __restrict__ bias, int N, int nblk, int G, int Q, int pass = kPassFinal) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
 
     WorkItem wi;  // my output block and row groups
-    if (!my_work(nblk, G, Q, count_ptr, wi)) return;
+    __shared__ int rl_red[17], rl_scan[17];
+    if (!derive_work(rl, nblk, G, Q, wi, kRows, rl_red, rl_scan)) return;
+    const int* cat = rl.cat;      // my slice of it was written just now
     const int b = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
 
     const int j = b * kBlk + tid;
@@ -611,13 +795,14 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         st_addr = lds_base + tile_offset(store_group(4 * tid) << 4);
         qp = w.qsel[(size_t)b * kBlk + tid];
     }
-    const int cat_last = cat[A - 1];
+    ListWindow rows_of(cat, g0 * kRows, min(A, g1 * kRows), wi.identity);
+    const int cat_last = rows_of.last();  // used by the last, ragged group only: then the list's last entry
     int4 c4 = make_int4(0, 0, 0, 0);  // slots (in Yin) of the 4 rows of the tile to load next
 
     // cat[] is padded so that the 16-byte read of the last, ragged group stays inside it
     auto fetch_rows = [&](int t) {
         const int gi = MULTI ? t / nstage : t;
-        c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + gi) * kRows);
+        c4 = rows_of.get4((g0 + gi) * kRows);
     };
     auto load_tile = [&](int t) {
         const int gi = MULTI ? t / nstage : t;
@@ -633,7 +818,10 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         const int s = MULTI ? t - gi * nstage : 0;
         const int left = ncols - s * kCap;
         if (wave_col >= left) return;
-        stage_store(st, st_addr + P * kBufSkew, qp);
+        // the four store addresses are worked out per tile from two registers, not kept in four across the loop
+        uint32_t q = qp, a = st_addr;
+        if (!MULTI) asm volatile("" : "+v"(q), "+v"(a));
+        stage_store(st, a + P * kBufSkew, q);
     };
 
     float acc[kRows] = {0.f, 0.f, 0.f, 0.f};
@@ -695,10 +883,12 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         constexpr int P = decltype(Ptag)::value;
         const int gi = MULTI ? t / nstage : t;
         const int s = MULTI ? t - gi * nstage : 0;
-        if (t + 2 < T) fetch_rows(t + 2);
         compute(Ptag, s, std::integral_constant<int, 0>{});
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
-        if (t + 2 < T) load_tile(t + 2);
+        if (t + 2 < T) {  // the row numbers come out of a register (ListWindow): asked for only now, behind the wait for tile t+1
+            fetch_rows(t + 2);
+            load_tile(t + 2);
+        }
         compute(Ptag, s, std::integral_constant<int, 16>{});
         if (s == nstage - 1) epilogue(g0 + gi);
         __syncthreads();
@@ -733,13 +923,15 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
 // per output.  Same pipeline as fused_layer_kernel<false>; nunit = number of units.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
-    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, LayerWeights w,
+    const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
+    RowLists rl, LayerWeights w,
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
     WorkItem wi;
-    if (!my_work(nunit, G, Q, count_ptr, wi)) return;
+    __shared__ int rl_red[17], rl_scan[17];
+    if (!derive_work(rl, nunit, G, Q, wi, kRows, rl_red, rl_scan)) return;
+    const int* cat = rl.cat;      // my slice of it was written just now
     const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const int b = 2 * u;  // first of the unit's two output blocks
 
@@ -766,13 +958,14 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     const bool staging = wave_col < ncols;  // waves whose columns lie past the window stage nothing
     const uint32_t st_addr = lds_base + tile_offset(store_group(4 * tid) << 4);
     const uint32_t qp = w.qsel[(size_t)b * kBlk + tid];
-    const int cat_last = cat[A - 1];
+    ListWindow rows_of(cat, g0 * kRows, min(A, g1 * kRows), wi.identity);
+    const int cat_last = rows_of.last();  // used by the last, ragged group only: then the list's last entry
     // byte offset of my four columns in a row; lanes past the window re-read its last columns
     const uint32_t ld_off = 4u * (uint32_t)win_col(c_lo, min(4 * tid, ncols - 4), N);  // windows are cyclic
     const char* ld_row[kRows] = {nullptr, nullptr, nullptr, nullptr};  // bases of the 4 rows of the tile to load (scalar)
 
     auto fetch_rows = [&](int t) {
-        const int4 c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + t) * kRows);
+        const int4 c4 = rows_of.get4((g0 + t) * kRows);
         const int row0 = (g0 + t) * kRows;
         ld_row[0] = reinterpret_cast<const char*>(Yin + (size_t)c4.x * N);
         ld_row[1] = reinterpret_cast<const char*>(Yin + (size_t)(row0 + 1 < A ? c4.y : cat_last) * N);
@@ -791,7 +984,11 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
         asm volatile("" : "+v"(st[0]), "+v"(st[1]), "+v"(st[2]), "+v"(st[3]));
     };
     auto store_tile = [&](int P) {
-        if (staging) stage_store(st, st_addr + P * kBufSkew, qp);
+        // The four store addresses are worked out per tile, not ahead of the loop: two registers (st_addr, qp)
+        // stay live instead of four, for eight cheap instructions per tile.
+        uint32_t q = qp, a = st_addr;
+        asm volatile("" : "+v"(q), "+v"(a));
+        if (staging) stage_store(st, a + P * kBufSkew, q);
     };
 
     float accA[kRows] = {0.f, 0.f, 0.f, 0.f}, accB[kRows] = {0.f, 0.f, 0.f, 0.f};
@@ -878,8 +1075,8 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
 // ---------------------------------------------------------------------------
 template <int S>
 __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
-    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
+    const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
+    RowLists rl, WideWeights w,
     const float* __restrict__ bias, int N, int nblk, int G, int Q) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
@@ -887,7 +1084,9 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
     const int wave = tid >> 6;
 
     WorkItem wi;
-    if (!my_work(nblk, G, Q, count_ptr, wi)) return;
+    __shared__ int rl_red[17], rl_scan[17];
+    if (!derive_work(rl, nblk, G, Q, wi, kRows, rl_red, rl_scan)) return;
+    const int* cat = rl.cat;      // my slice of it was written just now
     const int b = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
 
     const int j = b * kBlk + tid;
@@ -906,7 +1105,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
     f32x4 st[kRows];
     const int wave_col = (tid & ~63) * 4;
     const uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));
-    const int cat_last = cat[A - 1];
+    ListWindow rows_of(cat, g0 * kRows, min(A, g1 * kRows), wi.identity);
+    const int cat_last = rows_of.last();  // used by the last, ragged group only: then the list's last entry
     int4 c4 = make_int4(0, 0, 0, 0);
 
     auto group_of = [&](int t, int& s) -> int {
@@ -918,7 +1118,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
     auto fetch_rows = [&](int t) {
         int s;
         const int g = group_of(t, s);
-        c4 = *reinterpret_cast<const int4*>(cat + (size_t)g * kRows);
+        c4 = rows_of.get4(g * kRows);
     };
     auto load_tile = [&](int t) {
         int s;
@@ -964,7 +1164,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
         const int row0 = g * kRows;
         const int nlive = min(kRows, A - row0);
         if (nspill > 0) {  // connections that did not fit a stage: gathered from global memory
-            const int4 cg = *reinterpret_cast<const int4*>(cat + (size_t)g * kRows);
+            const int4 cg = wi.identity ? make_int4(row0, row0 + 1, row0 + 2, row0 + 3)
+                                        : uniform4(*reinterpret_cast<const int4*>(cat + (size_t)g * kRows));
             const float* p0 = Yin + (size_t)cg.x * N;
             const float* p1 = Yin + (size_t)(nlive > 1 ? cg.y : cat_last) * N;
             const float* p2 = Yin + (size_t)(nlive > 2 ? cg.z : cat_last) * N;
@@ -1002,7 +1203,6 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
     // buffer and the loads of the tile after it, then the other 8 connections.
     auto step = [&](int t, auto Ptag, float (&a)[kRows]) {
         constexpr int P = decltype(Ptag)::value;
-        if (t + 2 < T) fetch_rows(t + 2);
         if (nb > 0) {
             uint32_t o8[8];
             float v8[8];
@@ -1014,7 +1214,10 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
             fma_block8<P>(a, o8, v8);
         }
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
-        if (t + 2 < T) load_tile(t + 2);
+        if (t + 2 < T) {  // the row numbers come out of a register (ListWindow): asked for only now, behind the wait for tile t+1
+            fetch_rows(t + 2);
+            load_tile(t + 2);
+        }
         if (S > 8 && nb > 1) {
             uint32_t o8[8];
             float v8[8];
@@ -1065,8 +1268,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_kernel(
 // fused_wide_kernel.  S = 16 steps per stage only (3 to 8 stages).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
-    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
+    const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
+    RowLists rl, WideWeights w,
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
     constexpr int S = 16;
     extern __shared__ float4 lds4[];
@@ -1075,7 +1278,9 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     const int wave = tid >> 6;
 
     WorkItem wi;
-    if (!my_work(nunit, G, Q, count_ptr, wi)) return;
+    __shared__ int rl_red[17], rl_scan[17];
+    if (!derive_work(rl, nunit, G, Q, wi, kRows, rl_red, rl_scan)) return;
+    const int* cat = rl.cat;      // my slice of it was written just now
     const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const int b = 2 * u;  // first of the unit's two output blocks (same window for both)
 
@@ -1100,7 +1305,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     f32x4 st[kRows];
     const int wave_col = (tid & ~63) * 4;
     const uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));
-    const int cat_last = cat[A - 1];
+    ListWindow rows_of(cat, g0 * kRows, min(A, g1 * kRows), wi.identity);
+    const int cat_last = rows_of.last();  // used by the last, ragged group only: then the list's last entry
     int4 c4 = make_int4(0, 0, 0, 0);
 
     auto group_of = [&](int t, int& s) -> int {
@@ -1112,7 +1318,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     auto fetch_rows = [&](int t) {
         int s;
         const int g = group_of(t, s);
-        c4 = *reinterpret_cast<const int4*>(cat + (size_t)g * kRows);
+        c4 = rows_of.get4(g * kRows);
     };
     auto load_tile = [&](int t) {
         int s;
@@ -1164,7 +1370,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     auto finish = [&](float (&a)[kRows], float bj, int j, int blk, int nspill, int g, int nlive) -> unsigned {
         const int row0 = g * kRows;
         if (nspill > 0) {
-            const int4 cg = *reinterpret_cast<const int4*>(cat + (size_t)g * kRows);
+            const int4 cg = wi.identity ? make_int4(row0, row0 + 1, row0 + 2, row0 + 3)
+                                        : uniform4(*reinterpret_cast<const int4*>(cat + (size_t)g * kRows));
             const float* p0 = Yin + (size_t)cg.x * N;
             const float* p1 = Yin + (size_t)(nlive > 1 ? cg.y : cat_last) * N;
             const float* p2 = Yin + (size_t)(nlive > 2 ? cg.z : cat_last) * N;
@@ -1207,10 +1414,12 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
     // buffer and the loads of the tile after it, then A's other 8 and B's 16.
     auto step = [&](int t, auto Ptag, float (&aA)[kRows], float (&aB)[kRows]) {
         constexpr int P = decltype(Ptag)::value;
-        if (t + 2 < T) fetch_rows(t + 2);
         if (nbA > 0) block(Ptag, aA, owA);
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
-        if (t + 2 < T) load_tile(t + 2);
+        if (t + 2 < T) {  // the row numbers come out of a register (ListWindow): asked for only now, behind the wait for tile t+1
+            fetch_rows(t + 2);
+            load_tile(t + 2);
+        }
         if (nbA > 1) block(Ptag, aA, owA + 8);
         if (nbB > 0) block(Ptag, aB, owB);
         if (nbB > 1) block(Ptag, aB, owB + 8);
@@ -1263,8 +1472,8 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair_kernel(
 // ---------------------------------------------------------------------------
 template <int NS, int S>
 __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
-    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, WideWeights w,
+    const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
+    RowLists rl, WideWeights w,
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
     static_assert(NS * S == 64 && (NS == 2 || NS == 4), "64 steps per neuron");
     constexpr int LNS = NS == 4 ? 2 : 1;  // log2(NS)
@@ -1274,7 +1483,9 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     const int wave = tid >> 6;
 
     WorkItem wi;
-    if (!my_work(nunit, G, Q, count_ptr, wi)) return;
+    __shared__ int rl_red[17], rl_scan[17];
+    if (!derive_work(rl, nunit, G, Q, wi, kRows, rl_red, rl_scan)) return;
+    const int* cat = rl.cat;      // my slice of it was written just now
     const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const int b = 2 * u;
 
@@ -1371,10 +1582,11 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     f32x4 st[kRows];
     const int wave_col = (tid & ~63) * 4;
     const uint32_t st_addr = lds_base + tile_offset(col_slot(4 * tid));
-    const int cat_last = cat[A - 1];
+    ListWindow rows_of(cat, g0 * kRows, min(A, g1 * kRows), wi.identity);
+    const int cat_last = rows_of.last();  // used by the last, ragged group only: then the list's last entry
     int4 c4 = make_int4(0, 0, 0, 0);
 
-    auto fetch_rows = [&](int t) { c4 = *reinterpret_cast<const int4*>(cat + (size_t)(g0 + (t >> LNS)) * kRows); };
+    auto fetch_rows = [&](int t) { c4 = rows_of.get4((g0 + (t >> LNS)) * kRows); };
     // column (in floats) of my four staged columns: the same in every full stage, clamped in a narrower last one
     const uint32_t col_full = (uint32_t)(c_lo + 4 * tid);
     const uint32_t col_last = (uint32_t)(c_lo + (nstage - 1) * kCap + min(4 * tid, ncols - (nstage - 1) * kCap - 4));
@@ -1409,11 +1621,13 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
     auto step = [&](int t, auto Ptag, auto Stag) {
         constexpr int P = decltype(Ptag)::value;
         constexpr int s = decltype(Stag)::value;
-        if (t + 2 < T) fetch_rows(t + 2);
         constexpr int o = s * (S / 2);  // first word of this stage's steps
         if (nbA[s] > 0) fma_block8ps<P>(accA, pA[o + 0], pA[o + 1], pA[o + 2], pA[o + 3], wuni, sh4);
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
-        if (t + 2 < T) load_tile(t + 2);
+        if (t + 2 < T) {  // the row numbers come out of a register (ListWindow): asked for only now, behind the wait for tile t+1
+            fetch_rows(t + 2);
+            load_tile(t + 2);
+        }
 #pragma unroll
         for (int blk = 1; blk < S / 8; ++blk)
             if (nbA[s] > blk) fma_block8ps<P>(accA, pA[o + 4 * blk], pA[o + 4 * blk + 1], pA[o + 4 * blk + 2], pA[o + 4 * blk + 3], wuni, sh4);
@@ -1514,32 +1728,6 @@ constexpr int kCompactWGs = 16;
 constexpr int kCompactRounds = 4;
 static_assert(kCompactRounds * 16 == 64, "one wave scans the (round, wave) counts");
 
-// Number of set bytes among flags[0 .. n), counted by the whole workgroup.  red: 17 ints of LDS.
-__device__ __forceinline__ int count_flags(const uint8_t* __restrict__ flags, int n, int* red) {
-    const int tid = threadIdx.x;
-    int c = 0;
-    for (int i = tid * 16; i < n; i += kBlk * 16) {
-        if (i + 16 <= n) {  // bytes are 0 or 1: the population count of a word is its number of flags
-            const uint4 v = *reinterpret_cast<const uint4*>(flags + i);
-            c += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
-        } else {
-            for (int k = i; k < n; ++k) c += flags[k];
-        }
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
-    __syncthreads();  // red may still be read from a call before
-    if ((tid & 63) == 0) red[tid >> 6] = c;
-    __syncthreads();
-    if (tid == 0) {
-        int t = 0;
-        for (int w = 0; w < 16; ++w) t += red[w];
-        red[16] = t;
-    }
-    __syncthreads();
-    return red[16];
-}
-
 __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict__ flags_in,
                                                        uint8_t* __restrict__ flags_clear,
                                                        const int* __restrict__ count_in, int* __restrict__ count_out,
@@ -1612,19 +1800,20 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict
     }
 }
 
-// Start of an inference: identity lists, both flag buffers cleared, A = batch.  Row i of the
-// input carries the original row number row_offset + i (inputs handed over in serial batches,
-// Section III-B-2, are numbered through).
-__global__ void init_lists_kernel(int* __restrict__ cat, int* __restrict__ gid, uint8_t* __restrict__ flags0,
-                                  uint8_t* __restrict__ flags1, int* __restrict__ count, int batch, int row_offset) {
+// Start of an inference, written as the state a "layer -1" would have left: all rows of the batch
+// flagged alive, A = batch, the first layer's own flags cleared.  Row i of the input carries the
+// original row number row_offset + i (inputs handed over in serial batches, Section III-B-2, are
+// numbered through).
+__global__ void init_lists_kernel(int* __restrict__ gid_prev, uint8_t* __restrict__ flags_prev,
+                                  uint8_t* __restrict__ flags_first, int* __restrict__ count_prev, int batch,
+                                  int row_offset) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < batch) {
-        cat[i] = i;
-        gid[i] = row_offset + i;
-        flags0[i] = 0;
-        flags1[i] = 0;
+        gid_prev[i] = row_offset + i;
+        flags_prev[i] = 1;
+        flags_first[i] = 0;
     }
-    if (i == 0) *count = batch;
+    if (i == 0) *count_prev = batch;
 }
 
 // a4: surviving rows of Y_L, gathered into a dense [n][N] array (16-byte pieces).

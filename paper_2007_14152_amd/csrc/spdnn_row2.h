@@ -169,8 +169,8 @@ __device__ __forceinline__ void quartet_transpose(float& y0, float& y1, float& y
 }
 
 __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
-    const float* __restrict__ Yin, const int* __restrict__ cat, float* __restrict__ Yout,
-    uint8_t* __restrict__ flags, const int* __restrict__ count_ptr, Row2Weights w,
+    const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
+    RowLists rl, Row2Weights w,
     const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
     extern __shared__ float4 lds4[];
     typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -179,7 +179,9 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     const int lane = tid & 63;
 
     WorkItem wi;  // my unit and my groups of two rows
-    if (!my_work(nunit, G, Q, count_ptr, wi, kRows2)) return;
+    __shared__ int rl_red[17], rl_scan[17];
+    if (!derive_work(rl, nunit, G, Q, wi, kRows2, rl_red, rl_scan)) return;
+    const int* cat = rl.cat;      // my slice of it was written just now
     const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const bool gathered = w.map != nullptr;  // the tile is a gathered list of 4-column groups, not a window
     const int2 win = gathered ? make_int2(0, kRow2Cols) : row2_window(w.win, u, N);
@@ -213,7 +215,8 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     const int nseg = (ncols + kRow2Seg - 1) / kRow2Seg;
     f32x4 st[4][kRows2];
     const uint32_t st_addr = lds_base + 8u * (((4u * tid) & ~127u) | (tid & 31u));  // entry of column 4t; +256 per column
-    const int cat_last = cat[A - 1];
+    ListWindow rows_of(cat, g0 * kRows2, min(A, g1 * kRows2), wi.identity);
+    const int cat_last = rows_of.last();  // used by the last, ragged group only: then the list's last entry
     const int T = g1 - g0;
     // Byte offset, from the start of a row, of my four columns in every segment.  In a narrower last segment
     // the lanes past the window re-read its last columns; the window is cyclic (it may run over the row end);
@@ -228,7 +231,7 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     }
     const char* ld_row[kRows2] = {nullptr, nullptr};  // row bases of the tile being loaded, at the window's first column
     auto tile_rows = [&](int t) {
-        const int2 c2 = *reinterpret_cast<const int2*>(cat + (size_t)(g0 + t) * kRows2);
+        const int2 c2 = rows_of.get2((g0 + t) * kRows2);
         const int row0 = (g0 + t) * kRows2;
         ld_row[0] = reinterpret_cast<const char*>(Yin + (size_t)c2.x * N);
         ld_row[1] = reinterpret_cast<const char*>(Yin + (size_t)(row0 + 1 < A ? c2.y : cat_last) * N);
