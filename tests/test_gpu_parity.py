@@ -508,6 +508,47 @@ def test_batch_larger_than_one_compaction_chunk():
     assert common > 1000
 
 
+@pytest.mark.parametrize("N,batch,kernel", [
+    (1024, 50001, "fused_layer_kernel<false>"),   # one neuron per lane, one column block, 250 row chunks
+    (4096, 30001, "fused_pair_kernel"),           # two neurons per lane
+    (8192, 12002, "fused_row2_kernel"),           # two-row tiles: slices of the list in pairs of rows
+    (4100, 9999, None),                           # ragged last output block, window wider than one stage
+])
+def test_rows_die_in_every_layer_closed_form(N, batch, kernel):
+    """The list of active rows is derived by every layer's own kernel from the flags of the layer before
+    (Listing 1's pruning between two layers).  Row r holds the integer v_r in every column, every neuron
+    averages 32 inputs and the bias is -1, so a layer turns v into v - 1, exactly: v_r > l rows are alive
+    on entry to layer l, scattered over the whole batch, and the survivors hold v_r - L.  Checked against
+    that closed form on all rows and layers, and against the oracle on a sample."""
+    import torch
+    import paper_2007_14152_amd as sp
+    dev = "cuda:0"
+    L, vmax = 8, 12
+    rng = np.random.default_rng(N + batch)
+    v = rng.integers(1, vmax + 1, size=batch)
+    idx = [torch.from_numpy(np.sort(rng.integers(0, N, size=(N, 32)), axis=1).astype(np.int32)).to(dev) for _ in range(L)]
+    val = torch.full((N, 32), 1.0 / 32, dtype=torch.float32, device=dev)
+    bias = torch.full((N,), -1.0, dtype=torch.float32, device=dev)
+    y0 = torch.from_numpy(v.astype(np.float32)).to(dev)[:, None].expand(batch, N).contiguous()
+    m = sp.Model(idx, [val] * L, bias, device=dev)
+    assert kernel is None or sp.KERNEL_NAMES[m.layer_kernel(0)] == kernel
+    m.set_profiling(True)
+    n, rows, Y = m.infer(y0)
+    run, rows_in, _ = m.profile()
+    assert run == L
+    assert [int(x) for x in rows_in[:L]] == [int((v > l).sum()) for l in range(L)]
+    alive = np.nonzero(v > L)[0]
+    assert n == len(alive) and np.array_equal(rows.cpu().numpy(), alive)
+    want = torch.from_numpy((v[alive] - L).astype(np.float32)).to(dev)
+    assert bool((Y == want[:, None]).all())
+    # the oracle on a sample, first and last rows included
+    ids = np.unique(np.concatenate([[0, batch - 1], rng.choice(batch, 24, replace=False)]))
+    ref = oracle.infer([i.cpu().numpy() for i in idx], [val.cpu().numpy()] * L, bias.cpu().numpy(),
+                       np.repeat(v[ids].astype(np.float32)[:, None], N, axis=1))
+    assert np.array_equal(ids[ref.active_rows], np.intersect1d(ids, alive))
+    m.close()
+
+
 @pytest.mark.parametrize("uniform", [True, False])
 def test_largest_n_with_columns_anywhere(uniform):
     """N = 65536 (the largest the 16-bit column offsets allow) with columns drawn from the whole
