@@ -120,7 +120,11 @@ def parity_check(model, y0, ids, ref, final_rows):
     model.set_profiling(False)
     apl = ref.active_per_layer
     ok_layers = all(abs(int(rows_in[l]) - int(apl[l])) <= len(fragile) for l in range(run))
-    ok_layers = ok_layers and all(int(apl[l]) <= len(fragile) for l in range(run, len(apl)))
+    # apl[l] = rows on entry to layer l, l < L; apl[L] = rows that survive the last layer.  Layers that were
+    # not launched had nothing to do; the survivors are the run's result.
+    L = len(apl) - 1
+    ok_layers = ok_layers and all(int(apl[l]) <= len(fragile) for l in range(run, L))
+    ok_layers = ok_layers and abs(int(n_s) - int(apl[L])) <= len(fragile)
     ok_set = not ((set(ids[rows_s.cpu().numpy()].tolist()) ^ want) - fragile)
     return bool(ok_final and ok_layers and ok_set), {
         "rows_compared": int(len(ids)), "fragile_rows_excused": len(fragile), "final_set_matches": bool(ok_final),

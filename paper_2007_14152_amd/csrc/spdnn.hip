@@ -529,21 +529,57 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
                 spdnn::win_union(x, y, hw[(size_t)l * nblk + 4 * u + i].x, hw[(size_t)l * nblk + 4 * u + i].y, N, x, y);
             row2 = y <= spdnn::kRow2Cols;
         }
-        // Windows too wide for the tile: the gathered footprint (Section III-A-2's preload list at 4-column
-        // granularity) may still fit it -- every unit's connections within 4096 groups of four columns.
+        // Windows too wide for the tile, or much wider than the unit itself: the gathered footprint (Section
+        // III-A-2's preload list at 4-column granularity) may fit it -- every unit's connections within 4096
+        // groups of four columns -- and units of interleaved segments (unit_neuron) may need far fewer columns
+        // than units of 4096 neighbours: in a strided pattern the neurons j, j + stride, j + 2 stride, ... read
+        // the same columns.  Every segment length from 4096 down to 64 is tried and the one whose largest unit
+        // needs the fewest groups wins (the longer segment on a tie).
         // The rank table is set-up scratch: this stream's column -> slot table, which such a layer does not use.
         const int32_t* gather_map = nullptr;
         const uint16_t* gather_rank = nullptr;
-        if (row2_ok && !row2 && (size_t)(nblk / 4) * (N / 4) <= slot_tab_elems) {
+        int seg_log2 = spdnn::kSegLog2Max, seg_stride = N;
+        int widest_unit = 0;  // columns of the widest unit's window, units of 4096 neighbours
+        for (int32_t u = 0; row2_ok && u < nblk / 4; ++u) {
+            int x = 0, y = 0;
+            for (int i = 0; i < 4; ++i)
+                spdnn::win_union(x, y, hw[(size_t)l * nblk + 4 * u + i].x, hw[(size_t)l * nblk + 4 * u + i].y, N, x, y);
+            widest_unit = std::max(widest_unit, y);
+        }
+        if (row2_ok && widest_unit > spdnn::kUnit4 && (size_t)(nblk / 4) * (N / 4) <= slot_tab_elems) {
             const int32_t nunit = nblk / 4;
-            spdnn::row2_gather_kernel<<<nunit, spdnn::kBlk, 0, stream>>>(di, N, d.r2_map, slot_tab, d.r2_ngroups);
-            HIP_TRY(hipGetLastError());
             std::vector<int> ngr((size_t)nunit);
-            HIP_TRY(hipMemcpyAsync(ngr.data(), d.r2_ngroups, sizeof(int) * (size_t)nunit, hipMemcpyDeviceToHost, stream));
-            HIP_TRY(hipStreamSynchronize(stream));
-            row2 = true;
-            for (int32_t u = 0; u < nunit; ++u) row2 = row2 && ngr[u] <= spdnn::kRow2Cols / 4;
-            if (row2) {
+            auto gather = [&](int a, int& most) -> int {  // the footprints with segments of 1 << a neurons
+                spdnn::row2_gather_kernel<<<nunit, spdnn::kBlk, 0, stream>>>(di, N, a, (N / spdnn::kUnit4) << a, d.r2_map, slot_tab,
+                                                                           d.r2_ngroups);
+                HIP_TRY(hipGetLastError());
+                HIP_TRY(hipMemcpyAsync(ngr.data(), d.r2_ngroups, sizeof(int) * (size_t)nunit, hipMemcpyDeviceToHost, stream));
+                HIP_TRY(hipStreamSynchronize(stream));
+                most = *std::max_element(ngr.begin(), ngr.end());
+                return SPDNN_OK;
+            };
+            int best_a = -1, best = spdnn::kRow2Cols / 4 + 1, last_a = -1;
+            for (int a = spdnn::kSegLog2Max; a >= spdnn::kSegLog2Min; --a) {
+                int most = 0;
+                const int rc = gather(a, most);
+                if (rc != SPDNN_OK) return rc;
+                last_a = a;
+                if (most < best) {
+                    best = most;
+                    best_a = a;
+                }
+            }
+            // worth it if the window does not fit the tile at all, or if the tile shrinks to half the window or less
+            const bool take = best_a >= 0 && (!row2 || 4 * best <= widest_unit / 2);
+            if (take) {
+                if (best_a != last_a) {
+                    int most = 0;
+                    const int rc = gather(best_a, most);
+                    if (rc != SPDNN_OK) return rc;
+                }
+                row2 = true;
+                seg_log2 = best_a;
+                seg_stride = (N / spdnn::kUnit4) << best_a;
                 gather_map = d.r2_map;
                 gather_rank = slot_tab;
             }
@@ -551,10 +587,11 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         if (row2) {
             // the windows read back above are the blocks' own; pair_merge_kernel has widened them on the device to
             // common windows of block pairs, whose unions per unit are the same
-            d.r2 = spdnn::Row2Weights{reinterpret_cast<const uint4*>(d.r2_codes), win_dev[l], gather_map};
+            d.r2 = spdnn::Row2Weights{reinterpret_cast<const uint4*>(d.r2_codes), win_dev[l], gather_map, seg_log2, seg_stride};
             const int groups = N / spdnn::kGroup32;
             spdnn::row2_pack_kernel<<<(groups + spdnn::kRow2PackThreads - 1) / spdnn::kRow2PackThreads,
-                                      spdnn::kRow2PackThreads, 0, stream>>>(di, N, win_dev[l], gather_rank, d.r2_codes);
+                                      spdnn::kRow2PackThreads, 0, stream>>>(di, N, win_dev[l], gather_rank, seg_log2, seg_stride,
+                                                                            d.r2_codes);
             HIP_TRY(hipGetLastError());
             d.mode = kRow2;
             d.lds_cols = spdnn::kRow2Cols;

@@ -110,4 +110,16 @@ SPDNN_HD inline void win_union(int ax, int ay, int cx, int cy, int N, int& ox, i
 // row2_pos(c) mod 32 = (c >> 2) mod 32.
 SPDNN_HD inline uint32_t row2_pos(uint32_t c) { return (c & ~127u) | ((c & 3u) << 5) | ((c >> 2) & 31u); }
 
+// Which output neurons a 4096-neuron unit of fused_row2_kernel owns.  A unit is 4096 >> seg_log2 segments of
+// (1 << seg_log2) neighbouring neurons, one segment every seg_stride neurons: unit u takes the neurons
+// k * seg_stride + (u << seg_log2) + i, i < (1 << seg_log2), k < (4096 >> seg_log2), and local index
+// p = (k << seg_log2) + i counts them in ascending order.  seg_log2 = 12 is the plain unit of 4096 neighbours;
+// with smaller segments the units interleave, so that the neurons of a strided pattern which read the same
+// few columns (j, j + stride, j + 2 stride, ... all read j + k stride) land in one unit.  Needs
+// seg_stride << (12 - seg_log2) == N; segments are at least 64 neurons, so a wave's outputs stay contiguous.
+constexpr int kSegLog2Min = 6, kSegLog2Max = 12;
+SPDNN_HD inline int unit_neuron(int u, int p, int seg_log2, int seg_stride) {
+    return (p >> seg_log2) * seg_stride + (u << seg_log2) + (p & ((1 << seg_log2) - 1));
+}
+
 }  // namespace spdnn

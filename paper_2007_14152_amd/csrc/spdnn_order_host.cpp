@@ -75,6 +75,7 @@ uint32_t spdnn_rank_in_set_host(uint32_t lane) { return spdnn::rank_in_set(lane)
 uint32_t spdnn_col_slot_host(uint32_t c) { return spdnn::col_slot(c); }
 uint32_t spdnn_store_group_host(uint32_t c) { return spdnn::store_group(c); }
 uint32_t spdnn_row2_pos_host(uint32_t c) { return spdnn::row2_pos(c); }
+int spdnn_unit_neuron_host(int u, int p, int seg_log2, int seg_stride) { return spdnn::unit_neuron(u, p, seg_log2, seg_stride); }
 void spdnn_win_union_host(int ax, int ay, int cx, int cy, int N, int* out) { spdnn::win_union(ax, ay, cx, cy, N, out[0], out[1]); }
 int spdnn_win_rel_host(int c, int c_lo, int N) { return spdnn::win_rel(c, c_lo, N); }
 int spdnn_win_col_host(int c_lo, int rel, int N) { return spdnn::win_col(c_lo, rel, N); }

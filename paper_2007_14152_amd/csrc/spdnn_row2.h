@@ -36,8 +36,10 @@ struct Row2Weights {
     const int2* win;     // [nblk] per 1024-neuron block {c_lo, ncols}; a unit's window is the union of its four
     const int32_t* map;  // NULL: the tile is the unit's contiguous window.  Else the gathered footprint (the preload
                          // list of Section III-A-2, at 4-column granularity): [nunit][4096] first column of the
-                         // group of four columns that tile slot g holds, ascending; entries past the unit's
-                         // last group repeat it.  Tile column 4g + a is then row column map[g] + a.
+                         // group of four columns that tile slot g holds (row2_gather_kernel says in which order);
+                         // slots without a group repeat the unit's last.  Tile column 4g + a is row column map[g] + a.
+    int seg_log2;        // the unit's neurons: 4096 >> seg_log2 segments of 1 << seg_log2 neighbours, one every
+    int seg_stride;      // seg_stride neurons (unit_neuron); 12 = one run of 4096 (then seg_stride is not used)
 };
 
 // Column window of unit u: the union of its four blocks' (cyclic) windows; c_lo a multiple of 4.
@@ -282,11 +284,13 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     using lds_f1 = __attribute__((address_space(3))) float;
     const uint32_t bias_addr = lds_base + kRow2TileBytes + 4u * tid;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) *reinterpret_cast<lds_f1*>(bias_addr + s * (4 * kBlk)) = bias[u * kUnit4 + s * kBlk + tid];
-    // Output: after the transpose lane 4q+i holds row (i & 1) of neurons 4q..4q+3 of slot 2h + (i >> 1).
-    // Byte offset of that 16-byte piece from the start of the row group's first output row, for h = 0:
-    const uint32_t out_off = 4u * ((uint32_t)(lane & 1) * (uint32_t)N + (uint32_t)(u * kUnit4 + (tid & ~3)) +
-                                   (uint32_t)((lane >> 1) & 1) * kBlk);
+    for (int s = 0; s < 4; ++s)
+        *reinterpret_cast<lds_f1*>(bias_addr + s * (4 * kBlk)) = bias[unit_neuron(u, s * kBlk + tid, w.seg_log2, w.seg_stride)];
+    // Output: after the transpose lane 4q+i holds row (i & 1) of the unit's neurons p .. p+3 (four neighbours: a
+    // segment is a multiple of 4 long), p = (2h + (i >> 1)) * 1024 + 4q.  p for h = 0; the byte offset of the
+    // 16-byte piece from the start of the row group's first output row is worked out per tile (one register here).
+    const uint32_t out_p = (uint32_t)(((lane >> 1) & 1) * kBlk + (tid & ~3));
+    const uint32_t out_row_off = 4u * (uint32_t)(lane & 1) * (uint32_t)N;
 
     load_tile(0);
     wait_tile();
@@ -322,8 +326,10 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
             pos |= (__builtin_amdgcn_ballot_w64(y0 > 0.0f || y2 > 0.0f) != 0ull ? 1u : 0u) |
                    (__builtin_amdgcn_ballot_w64(y1 > 0.0f || y3 > 0.0f) != 0ull ? 2u : 0u);
             quartet_transpose(y0, y1, y2, y3, lane);
-            if ((lane & 1) < nlive)
-                *reinterpret_cast<float4*>(out_row + (out_off + (uint32_t)h * (2u * kBlk * 4u))) = make_float4(y0, y1, y2, y3);
+            if ((lane & 1) < nlive) {
+                const uint32_t nrn = (uint32_t)unit_neuron(u, (int)out_p + h * (2 * kBlk), w.seg_log2, w.seg_stride);
+                *reinterpret_cast<float4*>(out_row + (out_row_off + 4u * nrn)) = make_float4(y0, y1, y2, y3);
+            }
         }
         if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;  // lane r raises row r's flag
         __syncthreads();  // every wave is done reading tile t
@@ -335,24 +341,33 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     }
 }
 
-// a0 for the gathered footprint: per unit of 4096 neurons, the groups of four columns (column >> 2) that
-// any of its connections touches, in ascending order.  One workgroup per unit: a bitmap of the row's
-// N / 4 groups in LDS, a prefix count over it, and out come
-//   map[u][g]   first column of the unit's g-th group (entries past the last group repeat it),
-//   rank[u][c4] position g of group c4 in that list (meaningful for the groups that are used),
+// a0 for the gathered footprint: per unit of 4096 neurons (unit_neuron), the groups of four columns
+// (column >> 2) that any of its connections touches.  One workgroup per unit: a bitmap of the row's N / 4
+// groups in LDS, a prefix count over it, and out come
+//   map[u][g]   first column of the group that tile slot g holds,
+//   rank[u][c4] tile slot of group c4 (meaningful for the groups that are used),
 //   ngroups[u]  number of groups; the tile holds kRow2Cols / 4 of them.
-__global__ __launch_bounds__(kBlk) void row2_gather_kernel(const int32_t* __restrict__ idx, int N,
-                                                           int32_t* __restrict__ map, uint16_t* __restrict__ rank,
-                                                           int* __restrict__ ngroups) {
+// The i-th group in ascending order goes to slot gather_slot(i): inside every block of 32 slots (one round of
+// the 32 bank pairs) the order is rotated by the block's number.  In a strided pattern a neuron's 32 columns
+// sit at the same place of 32 different blocks; unrotated they would all lie in one bank pair, and the four
+// neighbouring neurons that share a group of four columns would collide in every step whatever the order of
+// their connections.  Slots that hold no group repeat the unit's last group (a harmless load).
+__device__ __forceinline__ int gather_slot(int i) { return (i & ~31) | ((i + (i >> 5)) & 31); }
+__global__ __launch_bounds__(kBlk) void row2_gather_kernel(const int32_t* __restrict__ idx, int N, int seg_log2,
+                                                           int seg_stride, int32_t* __restrict__ map,
+                                                           uint16_t* __restrict__ rank, int* __restrict__ ngroups) {
     __shared__ uint32_t bits[65536 / 4 / 32];  // one bit per group of four columns
     __shared__ uint32_t before[65536 / 4 / 32 + 1];
+    __shared__ int last_col;
     const int u = blockIdx.x;
     const int tid = threadIdx.x;
     const int words = (N / 4 + 31) / 32;
+    constexpr int kSlots = kRow2Cols / 4;
     for (int i = tid; i < words; i += kBlk) bits[i] = 0;
+    if (tid == 0) last_col = 0;
     __syncthreads();
     for (int e = tid; e < kUnit4 * kNnz; e += kBlk) {
-        const int c = idx[(size_t)u * kUnit4 * kNnz + e];
+        const int c = idx[(size_t)unit_neuron(u, e / kNnz, seg_log2, seg_stride) * kNnz + (e % kNnz)];
         if (c >= 0 && c < N) atomicOr(&bits[c >> 7], 1u << ((c >> 2) & 31));  // bad columns were reported
     }
     __syncthreads();
@@ -367,18 +382,22 @@ __global__ __launch_bounds__(kBlk) void row2_gather_kernel(const int32_t* __rest
     }
     __syncthreads();
     const int total = (int)before[words];
+    const int held = min(total, kSlots);  // a unit with more groups does not fit; the host looks at ngroups
     for (int c4 = tid; c4 < N / 4; c4 += kBlk) {
         const uint32_t wbits = bits[c4 >> 5];
-        const int g = (int)before[c4 >> 5] + __popc(wbits & ((1u << (c4 & 31)) - 1u));
-        rank[(size_t)u * (N / 4) + c4] = (uint16_t)min(g, kRow2Cols / 4 - 1);
-        if (((wbits >> (c4 & 31)) & 1u) && g < kRow2Cols / 4) {
-            map[(size_t)u * (kRow2Cols / 4) + g] = 4 * c4;
-            if (g == total - 1)  // the last group fills the rest of the list
-                for (int k = g + 1; k < kRow2Cols / 4; ++k) map[(size_t)u * (kRow2Cols / 4) + k] = 4 * c4;
-        }
+        const int i = (int)before[c4 >> 5] + __popc(wbits & ((1u << (c4 & 31)) - 1u));
+        if (((wbits >> (c4 & 31)) & 1u) && i == held - 1) last_col = 4 * c4;
     }
-    if (total == 0)
-        for (int k = tid; k < kRow2Cols / 4; k += kBlk) map[(size_t)u * (kRow2Cols / 4) + k] = 0;
+    __syncthreads();
+    for (int k = tid; k < kSlots; k += kBlk) map[(size_t)u * kSlots + k] = last_col;
+    __syncthreads();
+    for (int c4 = tid; c4 < N / 4; c4 += kBlk) {
+        const uint32_t wbits = bits[c4 >> 5];
+        const int i = (int)before[c4 >> 5] + __popc(wbits & ((1u << (c4 & 31)) - 1u));
+        const int g = gather_slot(min(i, kSlots - 1));
+        rank[(size_t)u * (N / 4) + c4] = (uint16_t)g;
+        if (((wbits >> (c4 & 31)) & 1u) && i < kSlots) map[(size_t)u * kSlots + g] = 4 * c4;
+    }
 }
 
 // a0 for fused_row2_kernel: one thread per group of 32 neighbouring neurons of one neuron slot
@@ -391,6 +410,7 @@ constexpr int kRow2PackThreads = 1;
 __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32_t* __restrict__ idx, int N,
                                                                      const int2* __restrict__ win,
                                                                      const uint16_t* __restrict__ rank,  // NULL: contiguous windows
+                                                                     int seg_log2, int seg_stride,
                                                                      uint16_t* __restrict__ codes) {
     __shared__ Order32Scratch scratch[kRow2PackThreads];
     const int g = blockIdx.x * kRow2PackThreads + threadIdx.x;  // group: unit, slot, 32 lanes
@@ -402,7 +422,7 @@ __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32
     const int lane0 = (in_unit - s * (kBlk / kGroup32)) * kGroup32;
     const int c_lo = rank ? 0 : row2_window(win, u, N).x;
     auto pos_of = [&](int l, int k) -> uint32_t {  // out-of-range columns were reported; keep them harmless
-        int c = idx[((size_t)u * kUnit4 + s * kBlk + lane0 + l) * kNnz + k];
+        int c = idx[(size_t)unit_neuron(u, s * kBlk + lane0 + l, seg_log2, seg_stride) * kNnz + k];
         if (c < 0 || c >= N) c = c_lo;
         // tile column: inside the window, or in the gathered list group rank[c >> 2], column c & 3 of it
         const uint32_t tc = rank ? 4u * rank[(size_t)u * (N / 4) + (c >> 2)] + (uint32_t)(c & 3) : (uint32_t)win_rel(c, c_lo, N);

@@ -626,6 +626,9 @@ def test_scattered_windows_gathered_footprint(N, w, batch):
     (10240, (256,), True, "WIDE_PAIR4"),        # three stages, two neurons per lane, step lists in registers
     (32768, (700,), True, "WIDE_PAIR"),         # six stages, two neurons per lane
     (65536, (1500,), False, "WIDE"),            # twelve stages of eight steps
+    (65536, (1024, 2048, 32), True, "ROW2 ROW2 PAIR"),  # units of interleaved segments: 64 x 64 and 32 x 128 neurons
+    (16384, (512,), True, "ROW2"),              # the window fits the tile, the interleaved unit needs a quarter of it
+    (12288, (384,), True, "ROW2"),              # three units, segments every 384 neurons
 ])
 def test_strided_layers_wrap_around_the_row_end(N, strides, uniform, kinds):
     """Strided, modular patterns (neuron j reads (j + k*S) mod N): the footprint of the last blocks runs

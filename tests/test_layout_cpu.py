@@ -105,6 +105,38 @@ def test_two_row_tile_layout(lay):
     assert np.all(pos % 32 == (np.arange(16384) >> 2) % 32)
 
 
+def test_units_of_interleaved_segments(lay):
+    """unit_neuron: for every segment length the units partition the N neurons, a unit's local index
+    counts its neurons in ascending order, four neighbouring local indices are four neighbouring
+    neurons (one 16-byte store), and in a strided pattern of the matching period a unit's neurons
+    read as many columns as it has neurons."""
+    f = lay.spdnn_unit_neuron_host
+    f.argtypes = [ctypes.c_int] * 4
+    f.restype = ctypes.c_int
+    for N in (4096, 12288, 65536):
+        nunit = N // 4096
+        for a in range(6, 13):
+            stride = nunit << a
+            nr = np.array([[f(u, p, a, stride) for p in range(0, 4096, 1 if N == 4096 else 4)] for u in range(nunit)])
+            if N == 4096:
+                assert np.array_equal(nr[0], np.arange(4096))   # one unit: the identity, whatever the segments
+            step = 1 if N == 4096 else 4
+            full = (nr[:, :, None] + np.arange(step)[None, None, :]).reshape(nunit, -1)  # neighbours of every 4th index
+            assert sorted(full.ravel().tolist()) == list(range(N))
+            assert np.all(np.diff(full, axis=1) > 0)
+            if step == 4:
+                for u in range(nunit):
+                    assert all(f(u, p + 1, a, stride) == f(u, p, a, stride) + 1 for p in range(0, 4096, 4))
+    # N = 65536, neuron j reads j + k * 1024 (mod N): segments of 64 neurons every 1024
+    N, S, a = 65536, 1024, 6
+    p = np.arange(4096)
+    for u in (0, 5, 15):
+        nrn = (p >> a) * S + (u << a) + (p & 63)
+        assert np.array_equal(nrn[::97], [f(u, int(q), a, S) for q in p[::97]])
+        cols = (nrn[:, None] + np.arange(32)[None, :] * 1024) % N
+        assert len(np.unique(cols)) == 4096
+
+
 def test_cyclic_windows(lay):
     """Windows are arcs of the circle of N columns: win_rel / win_col are inverse to each other, and
     win_union returns the shortest arc that holds both arguments (brute force on a small circle)."""
