@@ -73,8 +73,9 @@ struct LayerDesc {
     int lds_cols;  // columns the LDS tile must hold for this layer
     float wuni;    // kPair, kWidePair: the layer's weight
     bool pair4;    // kWidePair: 3 or 4 stages -> slot lists resident in registers
-    int pass;      // what this pass's epilogue does (spdnn::kPassAdd | spdnn::kPassFinal)
-    bool multi;    // one of several passes over a layer with more than 32 connections per neuron
+    bool multi;    // one of several launches of a layer with more than 32 connections per neuron: each computes the
+                   // outputs of a slice of the neurons, several lanes per neuron (spdnn::VirtInfo)
+    spdnn::VirtInfo virt;
 };
 
 }  // namespace
@@ -84,7 +85,7 @@ struct spdnn_model {
     hipStream_t stream = nullptr;
     int num_cu = 256;
     const float* bias_dev = nullptr;
-    std::vector<LayerDesc> layers;     // one per pass; a layer is one pass unless some neuron has more than 32 connections
+    std::vector<LayerDesc> layers;     // one per pass (launch); a layer is one pass unless some neuron has more than 32 connections
     std::vector<int32_t> first_pass;   // L+1 entries: layer l is passes first_pass[l] .. first_pass[l+1]-1
     int* host_counts = nullptr;  // pinned, L+1 entries: rows active on entry to layer l
     hipEvent_t lag_ev[kLag] = {};
@@ -113,7 +114,8 @@ bool valid_n(int32_t N) { return N >= 32 && N <= 65536 && (N % 4) == 0; }
 size_t layer_bytes(int32_t nblk) {
     const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
     return up((size_t)nblk * sizeof(int2)) + up(e * sizeof(uint16_t)) + up(e * sizeof(float)) +
-           up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t));
+           up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t)) +
+           up((size_t)nblk * spdnn::kBlk * sizeof(uint16_t)) + up((size_t)nblk * 16);  // several lanes per neuron: slots, steps per wave
 }
 int stages_of(int32_t window) { return (window + spdnn::kCap - 1) / spdnn::kCap; }
 // extra bytes per layer for the wide format with up to `nstage` stages (0 if not needed)
@@ -144,7 +146,8 @@ size_t wide_bytes(int32_t nblk, int nstage) {
 }
 size_t staging_bytes(int32_t N, int32_t L) {
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
-    return up((size_t)N * spdnn::kNnz * sizeof(int32_t)) + up((size_t)N * spdnn::kNnz * sizeof(float)) +
+    const size_t lanes = (size_t)nblk * spdnn::kBlk;  // rows of the staging arrays: the lanes of a launch
+    return up(lanes * spdnn::kNnz * sizeof(int32_t)) + up(lanes * spdnn::kNnz * sizeof(float)) + up(lanes) +
            kSetupStreams * up((size_t)nblk * spdnn::kCap * sizeof(uint16_t)) +  // column -> LDS slot tables of the layers being set up
            up(sizeof(int) * (size_t)nblk) +                     // general layers: smallest column of every block
            up(sizeof(int) * (size_t)(5 * L + 1));  // error flag; per layer: wide failure, widest window, weights differ, pair info[2]
@@ -197,10 +200,12 @@ size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
     return o;
 }
 
-template <bool MULTI, bool PASSES>
+constexpr int kVirtLds = spdnn::kBlk * 16;  // the slots of the lanes' sums (spdnn::VirtInfo)
+template <bool MULTI, bool VIRT>
 hipError_t allow_big_lds() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_layer_kernel<MULTI, PASSES>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)spdnn::tile_pair_bytes(spdnn::kCap));
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_layer_kernel<MULTI, VIRT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)spdnn::tile_pair_bytes(spdnn::kCap) + (VIRT ? kVirtLds : 0));
 }
 
 
@@ -262,7 +267,14 @@ int scan_csr(int32_t N, int32_t L, const int32_t* const* ptr, void* scratch_dev,
     passes_of->assign((size_t)L, 1);
     for (int32_t l = 0; l < L; ++l) {
         if (h[2 * l + 1]) return fail(SPDNN_EINVAL, "ptr[%d] is negative somewhere or decreases", l);
-        (*passes_of)[l] = std::max(1, (h[2 * l] + spdnn::kNnz - 1) / spdnn::kNnz);
+        // parts of 32 connections per neuron, rounded up to a power of two (lanes per neuron)
+        const int parts = std::max(1, (h[2 * l] + spdnn::kNnz - 1) / spdnn::kNnz);
+        int p2 = 1;
+        while (p2 < parts) p2 *= 2;
+        if (p2 > spdnn::kBlk / 4)
+            return fail(SPDNN_EINVAL, "layer %d has a neuron of %d connections; at most %d are supported", l, h[2 * l],
+                        spdnn::kNnz * spdnn::kBlk / 4);
+        (*passes_of)[l] = p2;
     }
     if (idx && widest_window) {  // after the ptr arrays are known to be sound
         std::vector<int2> hw(nblk);
@@ -406,6 +418,10 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         o += up(e * sizeof(float));
         uint32_t* qsel = reinterpret_cast<uint32_t*>(base + o);
         o += up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t));
+        m->layers[l].virt.slot = reinterpret_cast<const uint16_t*>(base + o);
+        o += up((size_t)nblk * spdnn::kBlk * sizeof(uint16_t));
+        m->layers[l].virt.nb8 = reinterpret_cast<const uint8_t*>(base + o);
+        o += up((size_t)nblk * 16);
         m->layers[l].w = spdnn::LayerWeights{rel, wv, win, qsel};
         win_dev[l] = win;
         spdnn::WideWeights ww{};
@@ -442,10 +458,13 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         m->layers[l].ww = ww;
     }
     o = blocks_at + (size_t)(ooc ? 2 : P) * blk_bytes;
+    const size_t lanes = (size_t)nblk * spdnn::kBlk;
     int32_t* st_idx = reinterpret_cast<int32_t*>(base + o);
-    o += up((size_t)N * spdnn::kNnz * sizeof(int32_t));
+    o += up(lanes * spdnn::kNnz * sizeof(int32_t));
     float* st_val = reinterpret_cast<float*>(base + o);
-    o += up((size_t)N * spdnn::kNnz * sizeof(float));
+    o += up(lanes * spdnn::kNnz * sizeof(float));
+    uint8_t* st_len = reinterpret_cast<uint8_t*>(base + o);  // several lanes per neuron: connections of every lane
+    o += up(lanes);
     uint16_t* slot_tabs = reinterpret_cast<uint16_t*>(base + o);  // one table per set-up stream
     const size_t slot_tab_elems = up((size_t)nblk * spdnn::kCap * sizeof(uint16_t)) / sizeof(uint16_t);
     o += kSetupStreams * up((size_t)nblk * spdnn::kCap * sizeof(uint16_t));
@@ -488,8 +507,23 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         const float* dv = val[ll];
         LayerDesc& d = m->layers[l];
         d.multi = passes_of[ll] > 1;
-        d.pass = (round_of[l] > 0 ? spdnn::kPassAdd : 0) | (round_of[l] == passes_of[ll] - 1 ? spdnn::kPassFinal : 0);
-        if (ptr) {  // general layer: connections 32r .. 32r+31 of every neuron, padded with zero weights
+        int nrows = -1;                 // rows of di / dv if not N
+        const uint8_t* lens = nullptr;  // connections per row if not 32
+        if (ptr && d.multi) {
+            // More than 32 connections somewhere: P lanes per neuron, R = 1024 / P neurons per workgroup.  Launch r of
+            // the layer's P computes the neurons of the virtual blocks r * nblk .. (r + 1) * nblk - 1; its lanes
+            // are set up like the neurons of a fixed-32 layer.
+            const int R = spdnn::kBlk / passes_of[ll];
+            d.virt.R = R;
+            d.virt.vb0 = round_of[l] * nblk;
+            spdnn::csr_virtual_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(ptr[ll], idx[ll], val[ll], N, R, d.virt.vb0, st_idx, st_val,
+                                                                        st_len, const_cast<uint16_t*>(d.virt.slot));
+            HIP_TRY(hipGetLastError());
+            di = st_idx;
+            dv = st_val;
+            nrows = nblk * spdnn::kBlk;
+            lens = st_len;
+        } else if (ptr) {  // general layer of at most 32 connections per neuron, padded with zero weights
             const int r = round_of[l];
             spdnn::csr_block_min_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(ptr[ll], idx[ll], N, r, blockmin);
             spdnn::csr_round_kernel<<<(unsigned)((raw + 255) / 256), 256, 0, stream>>>(ptr[ll], idx[ll], val[ll], N, r,
@@ -506,7 +540,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         int* widest_dev = err_dev + 1 + P + l;
         int* pair_dev = err_dev + 1 + 3 * P + 2 * l;
         spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev, widest_dev, dv,
-                                                                       err_dev + 1 + 2 * P + l);
+                                                                       err_dev + 1 + 2 * P + l, nrows);
         // a layer of several passes runs the one-neuron-per-lane kernels, whose epilogue knows about passes
         if (!d.multi)
             spdnn::pair_merge_kernel<<<1, 64, 0, stream>>>(win_dev[l], nblk, N, dv, err_dev + 1 + 2 * P + l, widest_dev,
@@ -607,10 +641,10 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
                 di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
         else
             spdnn::balance_kernel<1><<<nblk, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<1>), stream>>>(
-                di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel));
+                di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel), nrows);
         spdnn::order_pack_kernel<<<nblk * (spdnn::kOrderThreads / spdnn::kOrderPackThreads), spdnn::kOrderPackThreads, order_lds, stream>>>(
             di, dv, N, win_dev[l], widest_dev, slot_tab, pair, const_cast<uint16_t*>(d.w.rel),
-            const_cast<float*>(d.w.val));
+            const_cast<float*>(d.w.val), nrows, lens, lens ? const_cast<uint8_t*>(d.virt.nb8) : nullptr);
         HIP_TRY(hipGetLastError());
         int widest = 4;
         for (int32_t b = 0; b < nblk; ++b) widest = std::max(widest, hw[(size_t)l * nblk + b].y);
@@ -791,12 +825,16 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
             if (d.mode == kRow2)
                 spdnn::fused_row2_kernel<<<grid, spdnn::kBlk, spdnn::kRow2LdsBytes, s>>>(
                     Yin, Yout, wv.flags[l % 3], rl, d.r2, h->bias_dev, N, ncb, G, Q, d.wuni);
-            else if (d.multi && d.mode == kStaged)
-                spdnn::fused_layer_kernel<true, true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q, d.pass);
-            else if (d.multi)
-                spdnn::fused_layer_kernel<false, true><<<grid, spdnn::kBlk, lds, s>>>(
-                    Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q, d.pass);
+            else if (d.multi) {  // several lanes per neuron: the lanes' sums meet in LDS behind the tile pair
+                spdnn::VirtInfo vi = d.virt;
+                vi.part_off = (uint32_t)lds;
+                if (d.mode == kStaged)
+                    spdnn::fused_layer_kernel<true, true><<<grid, spdnn::kBlk, lds + kVirtLds, s>>>(
+                        Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q, vi);
+                else
+                    spdnn::fused_layer_kernel<false, true><<<grid, spdnn::kBlk, lds + kVirtLds, s>>>(
+                        Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q, vi);
+            }
             else if (d.mode == kPair)
                 spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
                     Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);

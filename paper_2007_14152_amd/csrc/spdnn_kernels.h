@@ -655,64 +655,22 @@ __device__ __forceinline__ unsigned finish_rows(float (&a)[kRows], float bj, flo
     return pos;
 }
 
-// The same epilogue for a layer that is evaluated in several passes of 32 connections
-// per neuron (neurons with more than 32 connections): every pass but the first adds
-// the partial sums that the pass before left in Yout, every pass but the last stores
-// the raw sums, and the last one adds the bias, clips and reports the rows with a
-// positive output.  Transposes first, so that partial sums, bias and result all move
-// as 16-byte accesses of 4 neighbouring neurons.
-constexpr int kPassAdd = 1;    // add the partial sums found in Yout
-constexpr int kPassFinal = 2;  // bias, clip, row flags
-__device__ __forceinline__ unsigned finish_rows_pass(float (&a)[kRows], const float* __restrict__ bias,
-                                                     float* __restrict__ Yout, int N, int j, bool jok, int row0,
-                                                     int nlive, int lane, int pass) {
-    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
-    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
-    const bool b0 = lane & 1, b1 = lane & 2;
-    float y0 = a[0], y1 = a[1], y2 = a[2], y3 = a[3];
-    a[0] = a[1] = a[2] = a[3] = 0.0f;
-    {
-        const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
-        const float r0 = xor2(s0), r1 = xor2(s1);
-        y0 = b1 ? r0 : y0;
-        y1 = b1 ? r1 : y1;
-        y2 = b1 ? y2 : r0;
-        y3 = b1 ? y3 : r1;
-    }
-    {
-        const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
-        const float r0 = xor1(s0), r1 = xor1(s1);
-        y0 = b0 ? r0 : y0;
-        y1 = b0 ? y1 : r0;
-        y2 = b0 ? r1 : y2;
-        y3 = b0 ? y3 : r1;
-    }
-    // now: row (lane & 3) of neurons (j & ~3) .. (j & ~3) + 3
-    const int r = lane & 3;
-    const bool ok = jok && r < nlive;  // N is a multiple of 4: a quartet of neurons exists as a whole or not at all
-    float4* dst = reinterpret_cast<float4*>(Yout + (size_t)(row0 + (ok ? r : 0)) * N + (jok ? (j & ~3) : 0));
-    if ((pass & kPassAdd) && ok) {
-        const float4 p = *dst;
-        y0 += p.x;
-        y1 += p.y;
-        y2 += p.z;
-        y3 += p.w;
-    }
-    unsigned pos = 0;
-    if (pass & kPassFinal) {
-        const float4 bq = jok ? *reinterpret_cast<const float4*>(bias + (j & ~3)) : make_float4(0.f, 0.f, 0.f, 0.f);
-        y0 = fminf(fmaxf(y0 + bq.x, 0.0f), kClip);
-        y1 = fminf(fmaxf(y1 + bq.y, 0.0f), kClip);
-        y2 = fminf(fmaxf(y2 + bq.z, 0.0f), kClip);
-        y3 = fminf(fmaxf(y3 + bq.w, 0.0f), kClip);
-        const bool any = ok && (y0 > 0.0f || y1 > 0.0f || y2 > 0.0f || y3 > 0.0f);
-        const unsigned long long m = __builtin_amdgcn_ballot_w64(any);  // lane 4q+r speaks for row r
-        pos = ((m & 0x1111111111111111ull) ? 1u : 0u) | ((m & 0x2222222222222222ull) ? 2u : 0u) |
-              ((m & 0x4444444444444444ull) ? 4u : 0u) | ((m & 0x8888888888888888ull) ? 8u : 0u);
-    }
-    if (ok) *dst = make_float4(y0, y1, y2, y3);
-    return pos;
-}
+// A layer whose neurons have more than 32 connections (general layers, Section II-A-1) runs with several
+// lanes per neuron: a neuron of K connections is cut into parts of 32, P = 2^ceil(log2(ceil(Kmax/32))) parts for
+// every neuron of the layer, so a workgroup's 1024 lanes serve R = 1024 / P neurons.  Inside a workgroup the
+// 1024 (neuron, part) pairs are given to the lanes in the order of their lengths, longest first, so that a
+// wave's 64 lanes have about equally many connections and a wave runs only the blocks of 8 steps its longest
+// lane needs -- the zero padding of Section III-A-3 at the granularity of a wave.  After the last step every
+// lane leaves its four sums (one per row of the tile) in its slot of a 16-KB LDS array, slot = part * R +
+// neuron, and after a barrier the first R lanes add up their neuron's P slots in part order, add the bias, clip
+// and store (finish_rows).  No partial sum leaves the CU.
+struct VirtInfo {
+    const uint16_t* slot;  // [nblk][kBlk] the lane's slot: part * R + neuron (neuron counted inside the workgroup)
+    const uint8_t* nb8;    // [nblk][16] blocks of 8 steps wave w of the workgroup runs (0..4)
+    int R;                 // neurons per workgroup, 1024 / P: a power of two, 4 <= R <= 512
+    int vb0;               // workgroup b of this launch owns the neurons (vb0 + b) * R .. + R - 1
+    uint32_t part_off;     // byte offset of the slots inside the dynamic LDS (behind the tile pair)
+};
 
 // ---------------------------------------------------------------------------
 // a1: fused SpMM + bias + clipped ReLU for one layer (Eq. 1), plus the per-row
@@ -726,14 +684,13 @@ __device__ __forceinline__ unsigned finish_rows_pass(float (&a)[kRows], const fl
 // the same rows through overlapping windows get ids that are equal modulo 8, so they
 // share one L2.  A workgroup handles row groups [q*per, (q+1)*per) of ceil(A/4).
 //
-// PASSES: the launch is one of several passes over a layer whose neurons have more
-// than 32 connections; `pass` says what the epilogue does (finish_rows_pass).
+// VIRT: several lanes per neuron (VirtInfo); the launch computes the outputs of nblk * R neurons.
 // ---------------------------------------------------------------------------
-template <bool MULTI, bool PASSES = false>
+template <bool MULTI, bool VIRT = false>
 __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
     RowLists rl, LayerWeights w,
-    const float* __restrict__ bias, int N, int nblk, int G, int Q, int pass = kPassFinal) {
+    const float* __restrict__ bias, int N, int nblk, int G, int Q, VirtInfo vi = VirtInfo{}) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
 
@@ -742,9 +699,11 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     if (!derive_work(rl, nblk, G, Q, wi, kRows, rl_red, rl_scan)) return;
     const int* cat = rl.cat;      // my slice of it was written just now
     const int b = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
+    if (VIRT && (vi.vb0 + b) * vi.R >= N) return;  // a workgroup past the last neuron
 
-    const int j = b * kBlk + tid;
-    const bool jok = j < N;
+    // the neuron whose result this lane finishes and stores (VIRT: lanes R and up finish none)
+    const int j = VIRT ? (vi.vb0 + b) * vi.R + tid : b * kBlk + tid;
+    const bool jok = j < N && (!VIRT || tid < vi.R);
     const int2 win = w.win[b];
     const int c_lo = win.x;
     const int ncols = win.y;
@@ -779,6 +738,10 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         __syncthreads();
     }
     const float bj = jok ? bias[j] : 0.0f;
+    // VIRT: where my sums go, and how many blocks of 8 steps my wave runs
+    const uint32_t part_base = lds_base + (VIRT ? vi.part_off : 0u);
+    const uint32_t part_addr = part_base + 16u * (VIRT ? (uint32_t)vi.slot[(size_t)b * kBlk + tid] : 0u);
+    const int nb = VIRT ? __builtin_amdgcn_readfirstlane((int)vi.nb8[b * 16 + (tid >> 6)]) : kNnz / 8;
 
     const int T = (g1 - g0) * nstage;  // pipeline steps: (row group, stage) pairs
     // Staging: lane t owns columns 4t..4t+3 of the stage: one 16-byte load per row,
@@ -857,7 +820,7 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
                     v[i] = (x & (15u << (4 * (k & 7)))) == 0u ? v[i] : 0.0f;
                 }
             }
-            fma_block8<P>(acc, o, v);
+            if (!VIRT || (k0 >> 3) < nb) fma_block8<P>(acc, o, v);  // VIRT: the blocks my wave's longest lane needs
             // keep each block's masked weights next to their block: hoisted, they would
             // need 32 more registers
             if (MULTI) __builtin_amdgcn_sched_barrier(0);
@@ -869,8 +832,27 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     auto epilogue = [&](int g) {
         const int row0 = g * kRows;
         const int nlive = min(kRows, A - row0);  // rows of this group that exist (>= 1)
-        const unsigned pos = PASSES ? finish_rows_pass(acc, bias, Yout, N, j, jok, row0, nlive, lane, pass)
-                                    : finish_rows(acc, bj, Yout, N, j, jok, row0, nlive, lane);
+        if (VIRT) {
+            // my part's four sums go to my slot; the neuron's lane adds the parts up in part order
+            using lds_f4 = __attribute__((address_space(3))) f32x4;
+            *reinterpret_cast<lds_f4*>(part_addr) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+            __syncthreads();
+            acc[0] = acc[1] = acc[2] = acc[3] = 0.0f;
+            if ((tid & ~63) < vi.R) {  // waves that hold finishing lanes (whole waves: finish_rows talks across lanes)
+                if (tid < vi.R)
+                    for (int p = 0; p < kBlk / vi.R; ++p) {
+                        const f32x4 v = *reinterpret_cast<const lds_f4*>(part_base + 16u * (uint32_t)(p * vi.R + tid));
+                        acc[0] += v.x;
+                        acc[1] += v.y;
+                        acc[2] += v.z;
+                        acc[3] += v.w;
+                    }
+                const unsigned pos = finish_rows(acc, bj, Yout, N, j, jok, row0, nlive, lane);
+                if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;
+            }
+            return;  // the barrier at the end of the step keeps the next tile's sums out of the slots until here
+        }
+        const unsigned pos = finish_rows(acc, bj, Yout, N, j, jok, row0, nlive, lane);
         if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;  // lane r raises row r's flag
     };
 
@@ -1837,7 +1819,8 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
                                                             int2* __restrict__ win, int* __restrict__ err,
                                                             int* __restrict__ widest,
                                                             const float* __restrict__ val = nullptr,
-                                                            int* __restrict__ nonuniform = nullptr) {
+                                                            int* __restrict__ nonuniform = nullptr,
+                                                            int nrows = -1) {  // rows of idx, if not N (VirtInfo layers)
     // The window is cyclic (see win_rel): two candidate cuts of the circle are tried, the row end and the
     // row's middle (columns shifted by h), and the narrower window wins.
     __shared__ int s_lo, s_hi, s_lo2, s_hi2;
@@ -1850,7 +1833,7 @@ __global__ __launch_bounds__(kBlk) void block_window_kernel(const int32_t* __res
     }
     __syncthreads();
     int lo = N, hi = -1, lo2 = N, hi2 = -1;
-    if (j < N) {
+    if (j < (nrows < 0 ? N : nrows)) {
         for (int k = 0; k < kNnz; ++k) {
             const int c = idx[(size_t)j * kNnz + k];
             if (c < 0 || c >= N) {
@@ -1984,6 +1967,52 @@ __global__ void csr_round_kernel(const int32_t* __restrict__ ptr, const int32_t*
     }
 }
 
+// A general layer with several lanes per neuron (VirtInfo), as a fixed-32 layer of lanes: workgroup blockIdx.x of
+// the launch is virtual block vb0 + blockIdx.x, i.e. the neurons (vb0 + blockIdx.x) * R .. + R - 1 in P = 1024 / R
+// parts each.  Pair q = part * R + neuron has the connections 32 * part .. of its neuron (0 to 32 of them); the
+// pairs are ranked by length, longest first, equal lengths in the order of q, and the pair of rank i becomes
+// lane i: out_idx / out_val [.][32] hold its connections, padded with weight 0 on the block's smallest
+// column, len its length and slot its q.
+__global__ __launch_bounds__(kBlk) void csr_virtual_kernel(const int32_t* __restrict__ ptr,
+                                                           const int32_t* __restrict__ idx,
+                                                           const float* __restrict__ val, int N, int R, int vb0,
+                                                           int32_t* __restrict__ out_idx, float* __restrict__ out_val,
+                                                           uint8_t* __restrict__ len, uint16_t* __restrict__ slot) {
+    __shared__ uint8_t len_s[kBlk];
+    __shared__ int s_lo;
+    const int q = threadIdx.x;
+    const int part = q / R;
+    const int j = (vb0 + (int)blockIdx.x) * R + (q - part * R);
+    if (q == 0) s_lo = N;
+    __syncthreads();
+    int first = 0, mine = 0;
+    if (j < N) {
+        first = ptr[j] + part * kNnz;
+        mine = max(0, min(kNnz, ptr[j + 1] - first));
+    }
+    int lo = N;
+    for (int k = 0; k < mine; ++k) {
+        const int c = idx[first + k];
+        if (c >= 0) lo = min(lo, c);
+    }
+    atomicMin(&s_lo, lo);
+    len_s[q] = (uint8_t)mine;
+    __syncthreads();
+    const int pad = s_lo < N ? s_lo : 0;
+    int rank = 0;
+    for (int o = 0; o < kBlk; ++o) {
+        const int other = len_s[o];
+        rank += (other > mine || (other == mine && o < q)) ? 1 : 0;
+    }
+    const size_t lane = (size_t)blockIdx.x * kBlk + rank;
+    len[lane] = (uint8_t)mine;
+    slot[lane] = (uint16_t)q;
+    for (int k = 0; k < kNnz; ++k) {
+        out_idx[lane * kNnz + k] = k < mine ? idx[first + k] : pad;
+        out_val[lane * kNnz + k] = k < mine ? val[first + k] : 0.0f;
+    }
+}
+
 // Can the layer run two output neurons per lane?  Yes if all its weights are equal, N
 // is a multiple of 2048 and either the windows of output blocks 2u and 2u+1 together
 // span at most kCap columns for every u (info[0] = 1: fused_pair_kernel) or every block
@@ -2063,7 +2092,8 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
                                                                   const int2* __restrict__ win,
                                                                   const int* __restrict__ widest,
                                                                   uint16_t* __restrict__ slot_tab,
-                                                                  uint32_t* __restrict__ qsel) {
+                                                                  uint32_t* __restrict__ qsel,
+                                                                  int nrows = -1) {  // rows of idx, if not N
     extern __shared__ char balance_scratch[];
     BalanceScratch<UB>& B = *reinterpret_cast<BalanceScratch<UB>*>(balance_scratch);
     if (*widest > kCap) return;
@@ -2076,7 +2106,7 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
     // stage-local column of connection e = (neuron << 5 | k) of this unit, or -1
     auto rel_of = [&](int e) -> int {
         const int j = b * kBlk + (e >> 5);
-        if (j >= N) return -1;
+        if (j >= (nrows < 0 ? N : nrows)) return -1;
         const int c = idx[(size_t)j * kNnz + (e & 31)];
         return (c < 0 || c >= N) ? 0 : win_rel(c, c_lo, N);  // out-of-range columns were reported; keep them harmless
     };
@@ -2178,14 +2208,23 @@ __global__ __launch_bounds__(kOrderPackThreads) void order_pack_kernel(const int
                                                                    const uint16_t* __restrict__ slot_tab,
                                                                    int pair,  // the layer's tile layout is per two blocks
                                                                    uint16_t* __restrict__ rel,
-                                                                   float* __restrict__ wval) {
+                                                                   float* __restrict__ wval,
+                                                                   // VirtInfo layers: idx / val have nrows rows (all of them
+                                                                   // lanes that exist), row i holds len[i] connections, and
+                                                                   // a set's connections are placed in the first steps only,
+                                                                   // as many (in eights) as its longest lane needs;
+                                                                   // nb8[block][wave] = blocks of 8 steps the wave then runs
+                                                                   int nrows = -1, const uint8_t* __restrict__ len = nullptr,
+                                                                   uint8_t* __restrict__ nb8 = nullptr) {
     extern __shared__ OrderScratch order_scratch[];
+    __shared__ int wave_steps;
     const int gset = blockIdx.x * kOrderPackThreads + threadIdx.x;  // lane set, counted over the whole layer
     const int b = gset / kOrderThreads;
     const int t = gset - b * kOrderThreads;
     const int wave0 = (t >> 2) * 64;  // first lane of this thread's wave inside the block
     const int set = t & 3;
     const int c_lo = win[b].x;
+    const int rows = nrows < 0 ? N : nrows;
     auto neuron = [&](int l) -> int { return b * kBlk + wave0 + lane_of_group(set, l); };
     auto column = [&](int l, int k) -> int {  // out-of-range columns were reported; keep them harmless
         const int c = idx[(size_t)neuron(l) * kNnz + k];
@@ -2195,10 +2234,29 @@ __global__ __launch_bounds__(kOrderPackThreads) void order_pack_kernel(const int
     const bool balanced = *widest <= kCap;
     const uint16_t* tab = slot_tab + (size_t)(pair ? (b & ~1) : b) * kCap;
     auto slot_of = [&](uint32_t r) -> uint32_t { return balanced ? tab[r] : col_slot(r); };
+    int nsteps = kNnz;
+    if (len) {  // steps this set needs; everything else is weight 0 on the window's first column
+        int longest = 0;
+        for (int l = 0; l < kGroup; ++l) longest = max(longest, (int)len[neuron(l)]);
+        nsteps = (longest + 7) & ~7;
+        for (int l = 0; l < kGroup; ++l)
+            for (int step = 0; step < kNnz; ++step) {
+                const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
+                rel[e] = (uint16_t)slot_of(0);
+                wval[e] = 0.0f;
+            }
+        // the four threads of a workgroup are the four sets of one wave (kOrderPackThreads == 4)
+        if (threadIdx.x == 0) wave_steps = 0;
+        __syncthreads();
+        atomicMax(&wave_steps, nsteps);
+        __syncthreads();
+        if (threadIdx.x == 0 && nb8) nb8[b * 16 + (t >> 2)] = (uint8_t)(wave_steps / 8);
+    }
     order_group(
-        order_scratch[threadIdx.x], kNnz,
+        order_scratch[threadIdx.x], nsteps,
         [&](int l, int k) -> unsigned {
-            return (neuron(l) < N) ? (slot_of((uint32_t)win_rel(column(l, k), c_lo, N) & (kCap - 1)) & 15u) : 255u;
+            if (neuron(l) >= rows || (len && k >= (int)len[neuron(l)])) return 255u;
+            return slot_of((uint32_t)win_rel(column(l, k), c_lo, N) & (kCap - 1)) & 15u;
         },
         [&](int l, int step, int k) {
             const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
@@ -2210,7 +2268,7 @@ __global__ __launch_bounds__(kOrderPackThreads) void order_pack_kernel(const int
             wval[e] = ok ? val[src] : 0.0f;
         });
     for (int l = 0; l < kGroup; ++l) {
-        if (neuron(l) < N) continue;
+        if (neuron(l) < rows) continue;
         for (int step = 0; step < kNnz; ++step) {  // lanes past the last neuron: weight 0 on column c_lo
             const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
             rel[e] = (uint16_t)slot_of(0);

@@ -237,7 +237,7 @@ def _draw_small(bk, nkey, base, width):
     return chosen + base[:, None]
 
 
-def gen_layer(N, l, seed, window=None, device=None):
+def gen_layer(N, l, seed, window=None, device=None, window_layer=None):
     """Input columns of every output neuron of layer l: int32 [N, 32], each row
     32 distinct columns, ascending.
 
@@ -248,7 +248,8 @@ def gen_layer(N, l, seed, window=None, device=None):
     instead (see _draw_small).
     """
     bk = _backend(device)
-    base, width = window_bases(N, l, seed, window, device)
+    # window_layer: take the windows of that layer (gen_layer_general: every draw of a neuron in the neuron's window)
+    base, width = window_bases(N, l if window_layer is None else window_layer, seed, window, device)
     if width < NNZ:
         raise ValueError("need at least 32 columns to draw 32 distinct ones")
     kl = _mix_py(_mix_py(seed ^ _STREAM_W) ^ l)
@@ -334,8 +335,8 @@ def gen_layer_general(N, l, seed, kmin, kmax, window=None, uniform_weight=False)
 
     Recipe: neuron j has d_j = kmin + (hash mod (kmax-kmin+1)) connections.  Its
     columns are the first d_j of the concatenation of ceil(kmax/32) independent
-    32-column draws of gen_layer (each ascending; a column may repeat across
-    draws -- repeated connections add up).  Weights: m / (d_j * 2**23) with m a
+    32-column draws of gen_layer, all from the neuron's window in layer l (each
+    ascending; a column may repeat across draws -- repeated connections add up).  Weights: m / (d_j * 2**23) with m a
     hashed integer in [2**23, 3 * 2**23), so a neuron's weights sum to about 2, as
     the 32 weights of 1/16 of the challenge networks do; uniform_weight=True gives
     every connection 1/16 instead.
@@ -344,7 +345,7 @@ def gen_layer_general(N, l, seed, kmin, kmax, window=None, uniform_weight=False)
         raise ValueError("need 0 <= kmin <= kmax")
     bk = _NP()
     draws = max(1, -(-kmax // NNZ))
-    cols = np.concatenate([gen_layer(N, l + 100003 * t, seed, window) for t in range(draws)], axis=1)  # [N, 32*draws]
+    cols = np.concatenate([gen_layer(N, l + 100003 * t, seed, window, window_layer=l) for t in range(draws)], axis=1)  # [N, 32*draws]
     kg = _mix_py(_mix_py(seed ^ _STREAM_G) ^ l)
     j = bk.arange(N)
     nkey = _mix(bk, j ^ bk.const(kg))

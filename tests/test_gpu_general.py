@@ -13,6 +13,12 @@ from parity_util import check_against_oracle
 pytestmark = pytest.mark.gpu
 
 
+def lanes_per_neuron(ptr):
+    """Parts of 32 connections of the layer's longest neuron, rounded up to a power of two."""
+    parts = max(1, -(-int(np.diff(ptr).max()) // 32))
+    return 1 << (parts - 1).bit_length()
+
+
 def rand_general(rng, N, L, kmin, kmax, lo=0.0, hi=0.12, empty_frac=0.05, width=None):
     """Random general layers; width = columns of neuron j lie in a window of that many
     columns around j (None: anywhere)."""
@@ -72,14 +78,17 @@ def test_short_neurons_one_pass(N, L, batch, kmax):
 
 
 @pytest.mark.parametrize("N,L,batch,kmax,width", [
-    (96, 3, 37, 70, None),      # up to 3 passes
-    (2052, 3, 33, 100, None),   # three output blocks, 4 passes
-    (5000, 2, 9, 64, None),     # two LDS stages, exactly 2 passes
+    (96, 3, 37, 70, None),      # up to 3 parts of 32: 4 lanes per neuron
+    (2052, 3, 33, 100, None),   # 4 lanes per neuron, 256 neurons per workgroup: 9 of them, the last launch all empty
+    (5000, 2, 9, 64, None),     # two LDS stages, exactly 2 lanes per neuron
     (9000, 2, 10, 45, 1500),    # narrow windows, one stage
-    (20000, 2, 6, 40, None),    # 5 stages: the staged kernel walks them in every pass
+    (20000, 2, 6, 40, None),    # 5 stages: the staged kernel walks them
+    (1024, 2, 19, 300, None),   # 16 lanes per neuron, 64 neurons per workgroup
+    (64, 2, 11, 2100, None),    # 128 lanes per neuron: 8 neurons per workgroup, finishing lanes fill an eighth of a wave
 ])
 def test_long_neurons_several_passes(N, L, batch, kmax, width):
-    """More than 32 connections: ceil(K/32) passes that accumulate in the output buffer."""
+    """More than 32 connections: a neuron is spread over P = 2^ceil(log2(ceil(K/32))) lanes, whose sums meet in LDS;
+    the layer runs as P launches, each computing a slice of the neurons (reported as passes)."""
     import paper_2007_14152_amd as sp
     rng = np.random.default_rng(N * 3 + kmax)
     ptr, idx, val, bias = rand_general(rng, N, L, 0, kmax, hi=4.0 / kmax, width=width)
@@ -87,7 +96,7 @@ def test_long_neurons_several_passes(N, L, batch, kmax, width):
     Y0[1] = 0
     ref = oracle.infer(idx, val, bias, Y0, ptr=ptr)
     m = sp.Model.from_csr(ptr, idx, val, bias)
-    want = [max(1, -(-int(np.diff(p).max()) // 32)) for p in ptr]
+    want = [lanes_per_neuron(p) for p in ptr]
     assert [m.layer_passes(l) for l in range(L)] == want and max(want) > 1
     assert m.layer_kernel(0) in (sp.SPDNN_KERNEL_SINGLE, sp.SPDNN_KERNEL_STAGED)
     if width:   # the arena was sized for the patterns' window, not for the worst case
@@ -117,7 +126,7 @@ def test_layers_of_different_kinds_in_one_model():
     Y0 = rng.uniform(0, 1, size=(batch, N)).astype(np.float32)
     ref = oracle.infer(idx, val, bias, Y0, ptr=ptr)
     m = sp.Model.from_csr(ptr, idx, val, bias)
-    assert [m.layer_passes(l) for l in range(3)] == [1, 3, 1]
+    assert [m.layer_passes(l) for l in range(3)] == [1, 4, 1]
     assert m.layer_kernel(2) == sp.SPDNN_KERNEL_PAIR
     n, rows, Y = gpu_infer_general(ptr, idx, val, bias, Y0, model=m)
     m.close()
@@ -220,7 +229,7 @@ def test_general_errors_and_edges():
                                                 torch.cuda.current_stream().cuda_stream,
                                                 idx_ptrs=[a.data_ptr() for a in ti])
     assert widest == N   # columns anywhere: every block spans the whole row
-    assert passes.tolist() == [max(1, -(-int(np.diff(p).max()) // 32)) for p in ptr] and total == int(passes.sum())
+    assert passes.tolist() == [lanes_per_neuron(p) for p in ptr] and total == int(passes.sum())
     need = sp.spdnn_weights_bytes_for_window(N, total, 4)
     arena = torch.empty(need, dtype=torch.uint8, device=dev)
     with pytest.raises(sp.SpdnnError) as e:
