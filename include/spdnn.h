@@ -105,10 +105,14 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx,
  *
  *     Y_{l+1}[r][j] = min(max( sum_k Y_l[r][idx_l[k]] * val_l[k] + bias[j], 0), 32)
  *
- * over the neuron's entries k.  A layer whose longest neuron has K connections runs as
- * max(1, ceil(K/32)) passes of the fused kernel over 32 connections per neuron, shorter
- * neurons padded with zero weights (the padding of Section III-A-3); the passes of a layer
- * accumulate in the output buffer and the last one applies bias and ReLU.
+ * over the neuron's entries k.  A layer whose longest neuron has K <= 32 connections runs as
+ * one launch of the fused kernel, shorter neurons padded with zero weights.  With K > 32 a
+ * neuron is spread over P lanes of 32 connections each, P = ceil(K/32) rounded up to a power
+ * of two (K <= 8192); the lanes of a workgroup are ordered by length, a wave runs only the
+ * steps its longest lane needs (the padding of Section III-A-3, per wave), and the lanes' sums
+ * are added inside the workgroup before bias and ReLU.  Such a layer runs as P launches, each
+ * of which computes the outputs of a share of the neurons and takes one layer's room in the
+ * weights arena; P is what is called the layer's passes here.
  *
  * spdnn_csr_passes: passes[l] (host, may be NULL) = passes of layer l, *total = their sum,
  * which is the "L" to size the weights arena with (spdnn_weights_bytes(N, *total, ...)); if
@@ -118,7 +122,8 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx,
  *                non-decreasing.
  *   idx        : as for spdnn_create_csr; may be NULL if widest_window is NULL.
  *   scratch_dev: device memory, 8-byte aligned, >= 8*L + 8*ceil(N/1024) bytes, contents scratch.
- * Blocks until done.  SPDNN_EINVAL if a ptr array decreases or is negative. */
+ * Blocks until done.  SPDNN_EINVAL if a ptr array decreases or is negative, or if a neuron has
+ * more than 8192 connections. */
 int spdnn_csr_passes(int32_t N, int32_t L, const int32_t* const* ptr, const int32_t* const* idx,
                      void* scratch_dev, size_t scratch_bytes, void* hip_stream, int32_t* passes,
                      int32_t* total, int32_t* widest_window);
@@ -250,8 +255,8 @@ int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows
 #define SPDNN_KERNEL_ROW2 6
 int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind);
 
-/* Number of fused-kernel passes layer l takes: 1, or ceil(K/32) for a general layer whose
- * longest neuron has K > 32 connections. */
+/* Number of fused-kernel launches (passes) layer l takes: 1, or for a general layer whose
+ * longest neuron has K > 32 connections ceil(K/32) rounded up to a power of two. */
 int spdnn_layer_passes(spdnn_t h, int32_t l, int32_t* passes);
 
 #ifdef __cplusplus

@@ -811,6 +811,12 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
             // column block reads whole rows: as many of them as possible share an XCD, so that a row is
             // fetched from memory once, not once per XCD.
             int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1) : h->G;
+            if (d.multi)  // R = 1024 / P neurons per workgroup: P times as many workgroups read the same window
+                for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
+                    if (g <= h->G * (spdnn::kBlk / d.virt.R) && ncb % g == 0) {
+                        G = g;
+                        break;
+                    }
             if (d.mode == kWide || d.mode == kWidePair || d.mode == kRow2)
                 for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
                     if (ncb % g == 0) {
