@@ -548,6 +548,19 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         HIP_TRY(hipGetLastError());
         // the windows decide the layer's kernel and its set-up; they are small, so read them back now
         int pair_info[2] = {0, 0};
+        // Layers that may run on two-row tiles: how many groups of four columns a 4096-neuron unit touches, for
+        // every segment length of unit_neuron, asked for now so that it comes back with the windows (the list
+        // area serves as the kernel's output).
+        constexpr int kCand = spdnn::kSegLog2Max - spdnn::kSegLog2Min + 1;
+        const bool r2_room = !d.multi && N % spdnn::kUnit4 == 0 && d.r2_codes != nullptr &&
+                             (size_t)(nblk / 4) * (N / 4) <= slot_tab_elems;
+        std::vector<int> ngr;
+        if (r2_room) {
+            ngr.resize((size_t)(nblk / 4) * kCand);
+            spdnn::row2_footprint_kernel<<<dim3(nblk / 4, kCand), spdnn::kBlk, 0, stream>>>(di, N, reinterpret_cast<int*>(d.r2_map));
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(hipMemcpyAsync(ngr.data(), d.r2_map, sizeof(int) * ngr.size(), hipMemcpyDeviceToHost, stream));
+        }
         HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipMemcpyAsync(pair_info, pair_dev, sizeof(pair_info), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
@@ -580,37 +593,22 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
                 spdnn::win_union(x, y, hw[(size_t)l * nblk + 4 * u + i].x, hw[(size_t)l * nblk + 4 * u + i].y, N, x, y);
             widest_unit = std::max(widest_unit, y);
         }
-        if (row2_ok && widest_unit > spdnn::kUnit4 && (size_t)(nblk / 4) * (N / 4) <= slot_tab_elems) {
+        if (row2_ok && r2_room && widest_unit > spdnn::kUnit4) {
             const int32_t nunit = nblk / 4;
-            std::vector<int> ngr((size_t)nunit);
-            auto gather = [&](int a, int& most) -> int {  // the footprints with segments of 1 << a neurons
-                spdnn::row2_gather_kernel<<<nunit, spdnn::kBlk, 0, stream>>>(di, N, a, (N / spdnn::kUnit4) << a, d.r2_map, slot_tab,
-                                                                           d.r2_ngroups);
-                HIP_TRY(hipGetLastError());
-                HIP_TRY(hipMemcpyAsync(ngr.data(), d.r2_ngroups, sizeof(int) * (size_t)nunit, hipMemcpyDeviceToHost, stream));
-                HIP_TRY(hipStreamSynchronize(stream));
-                most = *std::max_element(ngr.begin(), ngr.end());
-                return SPDNN_OK;
-            };
-            int best_a = -1, best = spdnn::kRow2Cols / 4 + 1, last_a = -1;
-            for (int a = spdnn::kSegLog2Max; a >= spdnn::kSegLog2Min; --a) {
-                int most = 0;
-                const int rc = gather(a, most);
-                if (rc != SPDNN_OK) return rc;
-                last_a = a;
+            int best_a = -1, best = spdnn::kRow2Cols / 4 + 1;
+            for (int y = 0; y < kCand; ++y) {
+                const int most = *std::max_element(ngr.begin() + (size_t)y * nunit, ngr.begin() + (size_t)(y + 1) * nunit);
                 if (most < best) {
                     best = most;
-                    best_a = a;
+                    best_a = spdnn::kSegLog2Max - y;
                 }
             }
             // worth it if the window does not fit the tile at all, or if the tile shrinks to half the window or less
             const bool take = best_a >= 0 && (!row2 || 4 * best <= widest_unit / 2);
             if (take) {
-                if (best_a != last_a) {
-                    int most = 0;
-                    const int rc = gather(best_a, most);
-                    if (rc != SPDNN_OK) return rc;
-                }
+                spdnn::row2_gather_kernel<<<nunit, spdnn::kBlk, 0, stream>>>(di, N, best_a, (N / spdnn::kUnit4) << best_a, d.r2_map,
+                                                                           slot_tab, d.r2_ngroups);
+                HIP_TRY(hipGetLastError());
                 row2 = true;
                 seg_log2 = best_a;
                 seg_stride = (N / spdnn::kUnit4) << best_a;

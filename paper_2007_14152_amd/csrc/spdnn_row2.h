@@ -400,6 +400,31 @@ __global__ __launch_bounds__(kBlk) void row2_gather_kernel(const int32_t* __rest
     }
 }
 
+// The sizes alone, for every segment length at once: workgroup (u, y) counts the groups of four columns that
+// unit u touches with segments of 1 << (kSegLog2Max - y) neurons; out[y * gridDim.x + u].
+__global__ __launch_bounds__(kBlk) void row2_footprint_kernel(const int32_t* __restrict__ idx, int N, int* __restrict__ out) {
+    __shared__ uint32_t bits[65536 / 4 / 32];
+    __shared__ int total;
+    const int u = blockIdx.x;
+    const int seg_log2 = kSegLog2Max - (int)blockIdx.y;
+    const int seg_stride = (N / kUnit4) << seg_log2;
+    const int tid = threadIdx.x;
+    const int words = (N / 4 + 31) / 32;
+    for (int i = tid; i < words; i += kBlk) bits[i] = 0;
+    if (tid == 0) total = 0;
+    __syncthreads();
+    for (int e = tid; e < kUnit4 * kNnz; e += kBlk) {
+        const int c = idx[(size_t)unit_neuron(u, e / kNnz, seg_log2, seg_stride) * kNnz + (e % kNnz)];
+        if (c >= 0 && c < N) atomicOr(&bits[c >> 7], 1u << ((c >> 2) & 31));
+    }
+    __syncthreads();
+    int mine = 0;
+    for (int i = tid; i < words; i += kBlk) mine += __popc(bits[i]);
+    if (mine) atomicAdd(&total, mine);
+    __syncthreads();
+    if (tid == 0) out[blockIdx.y * gridDim.x + u] = total;
+}
+
 // a0 for fused_row2_kernel: one thread per group of 32 neighbouring neurons of one neuron slot
 // (the lanes a ds_read_b64 serves together).  Orders the group's connections so that in every
 // step the 32 lanes read 32 different bank pairs whenever possible (order_group32) and writes the
