@@ -107,11 +107,11 @@ int spdnn_create(spdnn_t* out, int32_t N, int32_t L, const int32_t* const* idx,
  *
  * over the neuron's entries k.  A layer whose longest neuron has K <= 32 connections runs as
  * one launch of the fused kernel, shorter neurons padded with zero weights.  With K > 32 a
- * neuron is spread over P lanes of 32 connections each, P = ceil(K/32) rounded up to a power
- * of two (K <= 8192); the lanes of a workgroup are ordered by length, a wave runs only the
- * steps its longest lane needs (the padding of Section III-A-3, per wave), and the lanes' sums
- * are added inside the workgroup before bias and ReLU.  Such a layer runs as P launches, each
- * of which computes the outputs of a share of the neurons and takes one layer's room in the
+ * neuron is spread over one lane per 32 connections (K <= 8192); the lanes of a workgroup are
+ * ordered by length, a wave runs only the steps its longest lane needs (the padding of Section
+ * III-A-3, per wave), and the lanes' sums are added inside the workgroup before bias and ReLU.
+ * Such a layer runs as up to P launches, P = ceil(K/32) rounded up to a power of two, each of
+ * which computes the outputs of a share of the neurons and takes one layer's room in the
  * weights arena; P is what is called the layer's passes here.
  *
  * spdnn_csr_passes: passes[l] (host, may be NULL) = passes of layer l, *total = their sum,

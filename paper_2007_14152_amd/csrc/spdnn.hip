@@ -76,6 +76,8 @@ struct LayerDesc {
     bool multi;    // one of several launches of a layer with more than 32 connections per neuron: each computes the
                    // outputs of a slice of the neurons, several lanes per neuron (spdnn::VirtInfo)
     spdnn::VirtInfo virt;
+    int virt_lanes = 1;  // multi: lanes of the layer's longest neuron (the layer's passes)
+    int virt_blocks = 0;  // multi: workgroups of this launch that have neurons
 };
 
 }  // namespace
@@ -115,7 +117,9 @@ size_t layer_bytes(int32_t nblk) {
     const size_t e = (size_t)nblk * spdnn::kNnz * spdnn::kBlk;
     return up((size_t)nblk * sizeof(int2)) + up(e * sizeof(uint16_t)) + up(e * sizeof(float)) +
            up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t)) +
-           up((size_t)nblk * spdnn::kBlk * sizeof(uint16_t)) + up((size_t)nblk * 16);  // several lanes per neuron: slots, steps per wave
+           // several lanes per neuron: slots, steps per wave, neurons per workgroup, slots per neuron
+           up((size_t)nblk * spdnn::kBlk * sizeof(uint16_t)) + up((size_t)nblk * 16) + up((size_t)nblk * sizeof(int2)) +
+           up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t));
 }
 int stages_of(int32_t window) { return (window + spdnn::kCap - 1) / spdnn::kCap; }
 // extra bytes per layer for the wide format with up to `nstage` stages (0 if not needed)
@@ -200,7 +204,7 @@ size_t carve_work(int32_t N, int32_t batch, char* base, WorkView* v) {
     return o;
 }
 
-constexpr int kVirtLds = spdnn::kBlk * 16;  // the slots of the lanes' sums (spdnn::VirtInfo)
+constexpr int kVirtLds = 2 * spdnn::kBlk * 16;  // two sets of slots for the lanes' sums (spdnn::VirtInfo)
 template <bool MULTI, bool VIRT>
 hipError_t allow_big_lds() {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_layer_kernel<MULTI, VIRT>),
@@ -422,6 +426,10 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         o += up((size_t)nblk * spdnn::kBlk * sizeof(uint16_t));
         m->layers[l].virt.nb8 = reinterpret_cast<const uint8_t*>(base + o);
         o += up((size_t)nblk * 16);
+        m->layers[l].virt.range = reinterpret_cast<const int2*>(base + o);
+        o += up((size_t)nblk * sizeof(int2));
+        m->layers[l].virt.fin = reinterpret_cast<const uint32_t*>(base + o);
+        o += up((size_t)nblk * spdnn::kBlk * sizeof(uint32_t));
         m->layers[l].w = spdnn::LayerWeights{rel, wv, win, qsel};
         win_dev[l] = win;
         spdnn::WideWeights ww{};
@@ -499,6 +507,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
 
     const size_t raw = (size_t)N * spdnn::kNnz;
     std::vector<int2> hw((size_t)P * nblk);
+    std::vector<int2> virt_ranges;  // several lanes per neuron: {first neuron, neurons} of the current layer's workgroups
     for (int32_t l = 0; l < P; ++l) {  // l = pass; it belongs to layer ll
         hipStream_t stream = ss.s[l % ss.n];  // everything of this pass goes to one stream
         uint16_t* slot_tab = slot_tabs + (size_t)(l % ss.n) * slot_tab_elems;
@@ -510,14 +519,67 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         int nrows = -1;                 // rows of di / dv if not N
         const uint8_t* lens = nullptr;  // connections per row if not 32
         if (ptr && d.multi) {
-            // More than 32 connections somewhere: P lanes per neuron, R = 1024 / P neurons per workgroup.  Launch r of
-            // the layer's P computes the neurons of the virtual blocks r * nblk .. (r + 1) * nblk - 1; its lanes
-            // are set up like the neurons of a fixed-32 layer.
-            const int R = spdnn::kBlk / passes_of[ll];
-            d.virt.R = R;
-            d.virt.vb0 = round_of[l] * nblk;
-            spdnn::csr_virtual_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(ptr[ll], idx[ll], val[ll], N, R, d.virt.vb0, st_idx, st_val,
-                                                                        st_len, const_cast<uint16_t*>(d.virt.slot));
+            // More than 32 connections somewhere: a neuron takes as many lanes as it has parts of 32 connections, and
+            // a workgroup as many neighbouring neurons (in fours) as fill its 1024 lanes -- fewer where the next
+            // four would widen its column window beyond one LDS stage.  The layer's workgroups
+            // are cut into launches of nblk; launch r is pass r.  Their lanes are set up like the neurons of a
+            // fixed-32 layer.
+            if (round_of[l] == 0) {
+                std::vector<int32_t> hp((size_t)N + 1);
+                std::vector<int2> qw((size_t)N / 4);  // columns of every four neurons (the staging area as scratch)
+                int2* qw_dev = reinterpret_cast<int2*>(st_idx);
+                spdnn::csr_quartet_window_kernel<<<(N / 4 + 255) / 256, 256, 0, stream>>>(ptr[ll], idx[ll], N, qw_dev);
+                HIP_TRY(hipGetLastError());
+                HIP_TRY(hipMemcpyAsync(hp.data(), ptr[ll], sizeof(int32_t) * hp.size(), hipMemcpyDeviceToHost, stream));
+                HIP_TRY(hipMemcpyAsync(qw.data(), qw_dev, sizeof(int2) * qw.size(), hipMemcpyDeviceToHost, stream));
+                HIP_TRY(hipStreamSynchronize(stream));
+                virt_ranges.clear();
+                int first = 0, lanes = 0, lo = N, hi = -1;
+                for (int j = 0; j < N; j += 4) {  // N is a multiple of 4
+                    int q = 0;
+                    for (int i = 0; i < 4; ++i) q += (hp[j + i + 1] - hp[j + i] + spdnn::kNnz - 1) / spdnn::kNnz;
+                    const int2 w4 = qw[(size_t)j / 4];
+                    const int nlo = std::min(lo, w4.x), nhi = std::max(hi, w4.y);
+                    // a workgroup whose columns fit one LDS stage is not widened beyond it
+                    const bool widens = hi >= lo && hi - (lo & ~3) < spdnn::kCap && nhi - (nlo & ~3) >= spdnn::kCap;
+                    if (lanes + q > spdnn::kBlk || j - first == spdnn::kBlk || (j > first && widens)) {
+                        virt_ranges.push_back(make_int2(first, j - first));
+                        first = j;
+                        lanes = 0;
+                        lo = N;
+                        hi = -1;
+                    }
+                    lanes += q;  // a neuron has at most passes_of <= 256 parts: four of them always fit
+                    lo = std::min(lo, w4.x);
+                    hi = std::max(hi, w4.y);
+                }
+                virt_ranges.push_back(make_int2(first, N - first));
+                // The plain alternative: 1024 / passes_of neurons in every workgroup, as many as can all be of the
+                // longest kind.  Its workgroups are less full (their waves without connections do the finishing for
+                // free), so it is the faster one unless the packed workgroups are clearly fewer (measured: 128 plain
+                // against 112 packed workgroups 13.3 against 15.1 ms, 256 against 144: 27.3 against 22.6); it also
+                // always fits the arena, which has room for passes_of * nblk workgroups.
+                const int R = spdnn::kBlk / passes_of[ll];
+                const size_t plain = (size_t)(N + R - 1) / R;
+                if (virt_ranges.size() > (size_t)passes_of[ll] * nblk || 4 * virt_ranges.size() > 3 * plain) {
+                    virt_ranges.clear();
+                    for (int j = 0; j < N; j += R) virt_ranges.push_back(make_int2(j, std::min(R, N - j)));
+                }
+            }
+            std::vector<int2> mine((size_t)nblk, make_int2(N, 0));
+            for (int32_t b = 0; b < nblk; ++b) {
+                const size_t vb = (size_t)round_of[l] * nblk + b;
+                if (vb < virt_ranges.size()) {
+                    mine[b] = virt_ranges[vb];
+                    d.virt_blocks = b + 1;
+                }
+            }
+            HIP_TRY(hipMemcpyAsync(const_cast<int2*>(d.virt.range), mine.data(), sizeof(int2) * (size_t)nblk, hipMemcpyHostToDevice, stream));
+            HIP_TRY(hipStreamSynchronize(stream));  // `mine` goes out of scope
+            d.virt_lanes = passes_of[ll];
+            spdnn::csr_virtual_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(ptr[ll], idx[ll], val[ll], N, d.virt.range, st_idx, st_val,
+                                                                        st_len, const_cast<uint16_t*>(d.virt.slot),
+                                                                        const_cast<uint32_t*>(d.virt.fin));
             HIP_TRY(hipGetLastError());
             di = st_idx;
             dv = st_val;
@@ -787,6 +849,7 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
         // one launch per pass: a layer is a single pass unless some neuron has more than 32 connections
         for (int32_t p = h->first_pass[l]; p < h->first_pass[l + 1]; ++p) {
             const LayerDesc& d = h->layers[p];
+            if (d.multi && d.virt_blocks == 0 && p != h->first_pass[l]) continue;  // no workgroup of the layer is left for this launch
             if (h->ooc_host) HIP_TRY(hipStreamWaitEvent(s, h->ooc_ready[p & 1], 0));
             // The layer's first kernel compacts the list of active rows on its way in (the flags layer l-1
             // raised -> slots and row numbers); later passes of the same layer find the lists in place.
@@ -809,9 +872,9 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
             // column block reads whole rows: as many of them as possible share an XCD, so that a row is
             // fetched from memory once, not once per XCD.
             int32_t G = d.mode == kPair ? ((ncb % 2 == 0) ? 2 : 1) : h->G;
-            if (d.multi)  // R = 1024 / P neurons per workgroup: P times as many workgroups read the same window
+            if (d.multi)  // fewer neurons per workgroup: up to P times as many workgroups read the same window
                 for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
-                    if (g <= h->G * (spdnn::kBlk / d.virt.R) && ncb % g == 0) {
+                    if (g <= h->G * d.virt_lanes && ncb % g == 0) {
                         G = g;
                         break;
                     }
@@ -822,6 +885,9 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
                         break;
                     }
             int32_t Q = std::max(1, h->num_cu / ncb);
+            // several lanes per neuron: the launches of a layer have different numbers of workgroups with neurons,
+            // rarely a divisor of the CUs; four times as many workgroups as CUs, taken up as CUs fall free
+            if (d.multi) Q = (4 * h->num_cu + std::max(1, d.virt_blocks) - 1) / std::max(1, d.virt_blocks);
             Q = std::max(1, std::min(Q, ngroups));
             const int32_t units = (ncb / G) * Q;
             const int32_t grid = (units + 7) / 8 * 8 * G;

@@ -656,20 +656,22 @@ __device__ __forceinline__ unsigned finish_rows(float (&a)[kRows], float bj, flo
 }
 
 // A layer whose neurons have more than 32 connections (general layers, Section II-A-1) runs with several
-// lanes per neuron: a neuron of K connections is cut into parts of 32, P = 2^ceil(log2(ceil(Kmax/32))) parts for
-// every neuron of the layer, so a workgroup's 1024 lanes serve R = 1024 / P neurons.  Inside a workgroup the
-// 1024 (neuron, part) pairs are given to the lanes in the order of their lengths, longest first, so that a
-// wave's 64 lanes have about equally many connections and a wave runs only the blocks of 8 steps its longest
-// lane needs -- the zero padding of Section III-A-3 at the granularity of a wave.  After the last step every
-// lane leaves its four sums (one per row of the tile) in its slot of a 16-KB LDS array, slot = part * R +
-// neuron, and after a barrier the first R lanes add up their neuron's P slots in part order, add the bias, clip
-// and store (finish_rows).  No partial sum leaves the CU.
+// lanes per neuron: a neuron of K connections is cut into ceil(K/32) parts of up to 32, each part is one lane's
+// work, and a workgroup takes a run of neighbouring neurons (a multiple of 4, at most 1024) that have at most 1024
+// parts together.  Inside a workgroup the parts are given to the lanes in the order of their lengths, longest
+// first, so that a wave's 64 lanes have about equally many connections and a wave runs only the blocks of 8
+// steps its longest lane needs -- the zero padding of Section III-A-3 at the granularity of a wave.  After the
+// last step of a row group every lane leaves its four sums (one per row of the tile) in its slot of a 16-KB LDS
+// array -- a neuron's parts have neighbouring slots -- and at the start of the next step, behind the step's
+// barrier, the workgroup's LAST lanes (the ones with the shortest parts) add up the slots of its neurons in part
+// order, one neuron per lane, add the bias, clip and store (finish_rows) while the other waves are at the next
+// tile's arithmetic; two sets of slots alternate.  No partial sum leaves the CU.
 struct VirtInfo {
-    const uint16_t* slot;  // [nblk][kBlk] the lane's slot: part * R + neuron (neuron counted inside the workgroup)
+    const uint16_t* slot;  // [nblk][kBlk] the lane's slot
     const uint8_t* nb8;    // [nblk][16] blocks of 8 steps wave w of the workgroup runs (0..4)
-    int R;                 // neurons per workgroup, 1024 / P: a power of two, 4 <= R <= 512
-    int vb0;               // workgroup b of this launch owns the neurons (vb0 + b) * R .. + R - 1
-    uint32_t part_off;     // byte offset of the slots inside the dynamic LDS (behind the tile pair)
+    const int2* range;     // [nblk] {first neuron, number of neurons} of the workgroup; {N, 0}: none
+    const uint32_t* fin;   // [nblk][kBlk] entry i < number of neurons: first slot | number of slots << 16 of the workgroup's i-th neuron
+    uint32_t part_off;     // byte offset of the two sets of slots inside the dynamic LDS (behind the tile pair)
 };
 
 // ---------------------------------------------------------------------------
@@ -684,7 +686,7 @@ struct VirtInfo {
 // the same rows through overlapping windows get ids that are equal modulo 8, so they
 // share one L2.  A workgroup handles row groups [q*per, (q+1)*per) of ceil(A/4).
 //
-// VIRT: several lanes per neuron (VirtInfo); the launch computes the outputs of nblk * R neurons.
+// VIRT: several lanes per neuron (VirtInfo); the launch computes the outputs of its workgroups' neurons.
 // ---------------------------------------------------------------------------
 template <bool MULTI, bool VIRT = false>
 __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
@@ -695,15 +697,27 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     const int tid = threadIdx.x;
 
     WorkItem wi;  // my output block and row groups
-    __shared__ int rl_red[17], rl_scan[17];
+    int *rl_red, *rl_scan;
+    if constexpr (VIRT) {  // every byte of LDS is spoken for (two tiles, two sets of slots): borrow the first tile
+        rl_red = reinterpret_cast<int*>(lds4);
+        rl_scan = rl_red + 32;
+    } else {
+        __shared__ int red_mem[17], scan_mem[17];
+        rl_red = red_mem;
+        rl_scan = scan_mem;
+    }
     if (!derive_work(rl, nblk, G, Q, wi, kRows, rl_red, rl_scan)) return;
+    if (VIRT) __syncthreads();  // ... and give it back only when every wave is done with it
     const int* cat = rl.cat;      // my slice of it was written just now
     const int b = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
-    if (VIRT && (vi.vb0 + b) * vi.R >= N) return;  // a workgroup past the last neuron
+    const int2 mine = VIRT ? vi.range[b] : make_int2(b * kBlk, kBlk);  // my workgroup's neurons
+    if (VIRT && mine.y == 0) return;  // a workgroup past the last neuron
 
-    // the neuron whose result this lane finishes and stores (VIRT: lanes R and up finish none)
-    const int j = VIRT ? (vi.vb0 + b) * vi.R + tid : b * kBlk + tid;
-    const bool jok = j < N && (!VIRT || tid < vi.R);
+    // The neuron whose result this lane finishes and stores.  VIRT: the workgroup's last mine.y lanes finish its
+    // neurons -- the lanes with the shortest parts, whose waves have time to spare.
+    const int fl = tid - (kBlk - mine.y);  // which of my workgroup's neurons
+    const int j = mine.x + fl;
+    const bool jok = j < N && fl >= 0;
     const int2 win = w.win[b];
     const int c_lo = win.x;
     const int ncols = win.y;
@@ -742,6 +756,8 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     const uint32_t part_base = lds_base + (VIRT ? vi.part_off : 0u);
     const uint32_t part_addr = part_base + 16u * (VIRT ? (uint32_t)vi.slot[(size_t)b * kBlk + tid] : 0u);
     const int nb = VIRT ? __builtin_amdgcn_readfirstlane((int)vi.nb8[b * 16 + (tid >> 6)]) : kNnz / 8;
+    const uint32_t fin = (VIRT && fl >= 0) ? vi.fin[(size_t)b * kBlk + fl] : 0u;  // my neuron's slots
+    int pending = -1;  // VIRT: the row group whose sums wait in the slots to be finished
 
     const int T = (g1 - g0) * nstage;  // pipeline steps: (row group, stage) pairs
     // Staging: lane t owns columns 4t..4t+3 of the stage: one 16-byte load per row,
@@ -833,24 +849,14 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         const int row0 = g * kRows;
         const int nlive = min(kRows, A - row0);  // rows of this group that exist (>= 1)
         if (VIRT) {
-            // my part's four sums go to my slot; the neuron's lane adds the parts up in part order
+            // My part's four sums go to my slot, in the set of slots of this group's parity.  They are added up at
+            // the start of the next step (finish_pending), behind this step's barrier and under the other waves'
+            // arithmetic; the set is written again two groups later, with a barrier in between.
             using lds_f4 = __attribute__((address_space(3))) f32x4;
-            *reinterpret_cast<lds_f4*>(part_addr) = f32x4{acc[0], acc[1], acc[2], acc[3]};
-            __syncthreads();
+            *reinterpret_cast<lds_f4*>(part_addr + (uint32_t)(g & 1) * (16u * kBlk)) = f32x4{acc[0], acc[1], acc[2], acc[3]};
             acc[0] = acc[1] = acc[2] = acc[3] = 0.0f;
-            if ((tid & ~63) < vi.R) {  // waves that hold finishing lanes (whole waves: finish_rows talks across lanes)
-                if (tid < vi.R)
-                    for (int p = 0; p < kBlk / vi.R; ++p) {
-                        const f32x4 v = *reinterpret_cast<const lds_f4*>(part_base + 16u * (uint32_t)(p * vi.R + tid));
-                        acc[0] += v.x;
-                        acc[1] += v.y;
-                        acc[2] += v.z;
-                        acc[3] += v.w;
-                    }
-                const unsigned pos = finish_rows(acc, bj, Yout, N, j, jok, row0, nlive, lane);
-                if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;
-            }
-            return;  // the barrier at the end of the step keeps the next tile's sums out of the slots until here
+            pending = g;
+            return;
         }
         const unsigned pos = finish_rows(acc, bj, Yout, N, j, jok, row0, nlive, lane);
         if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;  // lane r raises row r's flag
@@ -861,10 +867,32 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     // Half way through, tile t+1 goes to the other buffer -- nobody reads that one
     // before the barrier below -- and the loads of tile t+2 are issued, so they have
     // a whole step to land and the barrier never waits for global memory.
+    // VIRT: the neuron's lane adds up its parts' sums in part order, then bias, clip and store as everywhere
+    auto finish_pending = [&]() {
+        if (!VIRT || pending < 0) return;
+        const int g = pending;
+        pending = -1;
+        if ((tid | 63) < kBlk - mine.y) return;  // whole waves take part: finish_rows talks across lanes
+        using lds_f4 = __attribute__((address_space(3))) f32x4;
+        const int row0 = g * kRows;
+        const int nlive = min(kRows, A - row0);
+        float sum[kRows] = {0.0f, 0.0f, 0.0f, 0.0f};
+        const uint32_t from = part_base + (uint32_t)(g & 1) * (16u * kBlk) + 16u * (fin & 0xffffu);
+        for (uint32_t p = 0; p < (fin >> 16); ++p) {
+            const f32x4 v = *reinterpret_cast<const lds_f4*>(from + 16u * p);
+            sum[0] += v.x;
+            sum[1] += v.y;
+            sum[2] += v.z;
+            sum[3] += v.w;
+        }
+        const unsigned pos = finish_rows(sum, bj, Yout, N, j, jok, row0, nlive, lane);
+        if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;
+    };
     auto step = [&](int t, auto Ptag) {
         constexpr int P = decltype(Ptag)::value;
         const int gi = MULTI ? t / nstage : t;
         const int s = MULTI ? t - gi * nstage : 0;
+        finish_pending();
         compute(Ptag, s, std::integral_constant<int, 0>{});
         if (t + 1 < T) store_tile(P ^ 1, t + 1);
         if (t + 2 < T) {  // the row numbers come out of a register (ListWindow): asked for only now, behind the wait for tile t+1
@@ -892,6 +920,7 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
         step(t + 1, P1{});
     }
     if (t < T) step(t, P0{});
+    finish_pending();  // the last group (behind the last step's barrier)
 }
 
 // ---------------------------------------------------------------------------
@@ -1967,27 +1996,78 @@ __global__ void csr_round_kernel(const int32_t* __restrict__ ptr, const int32_t*
     }
 }
 
-// A general layer with several lanes per neuron (VirtInfo), as a fixed-32 layer of lanes: workgroup blockIdx.x of
-// the launch is virtual block vb0 + blockIdx.x, i.e. the neurons (vb0 + blockIdx.x) * R .. + R - 1 in P = 1024 / R
-// parts each.  Pair q = part * R + neuron has the connections 32 * part .. of its neuron (0 to 32 of them); the
-// pairs are ranked by length, longest first, equal lengths in the order of q, and the pair of rank i becomes
-// lane i: out_idx / out_val [.][32] hold its connections, padded with weight 0 on the block's smallest
-// column, len its length and slot its q.
+// Smallest and largest column of every four neighbouring neurons of a general layer ({N, -1}: no connection):
+// what the host packs the workgroups of a several-lanes-per-neuron layer by.
+__global__ void csr_quartet_window_kernel(const int32_t* __restrict__ ptr, const int32_t* __restrict__ idx, int N,
+                                          int2* __restrict__ out) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (4 * q >= N) return;
+    int lo = N, hi = -1;
+    for (int e = ptr[4 * q]; e < ptr[4 * q + 4]; ++e) {
+        const int c = idx[e];
+        if (c >= 0 && c < N) {
+            lo = min(lo, c);
+            hi = max(hi, c);
+        }
+    }
+    out[q] = make_int2(lo, hi);
+}
+
+// A general layer with several lanes per neuron (VirtInfo), as a fixed-32 layer of lanes.  Workgroup blockIdx.x
+// has the neurons range[blockIdx.x].x .. + range[blockIdx.x].y - 1 (at most 1024 parts of 32 connections together,
+// the host sees to that).  The parts are numbered neuron by neuron (that number is the part's slot) and ranked by
+// length, longest first, equal lengths in slot order; the part of rank i becomes lane i: out_idx / out_val
+// [.][32] hold its connections, padded with weight 0 on the workgroup's smallest column, len its length, slot
+// its slot; fin[i] = first slot | number of slots << 16 of the workgroup's i-th neuron.
 __global__ __launch_bounds__(kBlk) void csr_virtual_kernel(const int32_t* __restrict__ ptr,
                                                            const int32_t* __restrict__ idx,
-                                                           const float* __restrict__ val, int N, int R, int vb0,
+                                                           const float* __restrict__ val, int N,
+                                                           const int2* __restrict__ range,
                                                            int32_t* __restrict__ out_idx, float* __restrict__ out_val,
-                                                           uint8_t* __restrict__ len, uint16_t* __restrict__ slot) {
+                                                           uint8_t* __restrict__ len, uint16_t* __restrict__ slot,
+                                                           uint32_t* __restrict__ fin) {
     __shared__ uint8_t len_s[kBlk];
+    __shared__ uint16_t part_neuron[kBlk], part_no[kBlk];
+    __shared__ int wave_sum[17];
     __shared__ int s_lo;
-    const int q = threadIdx.x;
-    const int part = q / R;
-    const int j = (vb0 + (int)blockIdx.x) * R + (q - part * R);
-    if (q == 0) s_lo = N;
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int2 rg = range[blockIdx.x];
+    if (t == 0) s_lo = N;
+    // parts of my neuron (thread i < rg.y has the workgroup's i-th neuron) and where they start
+    const int jn = rg.x + t;
+    const int parts = (t < rg.y && jn < N) ? (ptr[jn + 1] - ptr[jn] + kNnz - 1) / kNnz : 0;
+    int incl = parts;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
     __syncthreads();
+    if (t == 0) {
+        int run = 0;
+        for (int k = 0; k < 16; ++k) {
+            const int v = wave_sum[k];
+            wave_sum[k] = run;
+            run += v;
+        }
+        wave_sum[16] = run;
+    }
+    __syncthreads();
+    const int first_slot = wave_sum[wave] + incl - parts;
+    const int total = min(wave_sum[16], kBlk);  // never more than 1024: the host packed the workgroups
+    fin[(size_t)blockIdx.x * kBlk + t] = (uint32_t)first_slot | ((uint32_t)parts << 16);
+    for (int p = 0; p < parts && first_slot + p < kBlk; ++p) {
+        part_neuron[first_slot + p] = (uint16_t)t;
+        part_no[first_slot + p] = (uint16_t)p;
+    }
+    __syncthreads();
+    // thread t now is part (slot) t
     int first = 0, mine = 0;
-    if (j < N) {
-        first = ptr[j] + part * kNnz;
+    if (t < total) {
+        const int j = rg.x + part_neuron[t];
+        first = ptr[j] + (int)part_no[t] * kNnz;
         mine = max(0, min(kNnz, ptr[j + 1] - first));
     }
     int lo = N;
@@ -1996,20 +2076,20 @@ __global__ __launch_bounds__(kBlk) void csr_virtual_kernel(const int32_t* __rest
         if (c >= 0) lo = min(lo, c);
     }
     atomicMin(&s_lo, lo);
-    len_s[q] = (uint8_t)mine;
+    len_s[t] = (uint8_t)mine;
     __syncthreads();
     const int pad = s_lo < N ? s_lo : 0;
     int rank = 0;
     for (int o = 0; o < kBlk; ++o) {
         const int other = len_s[o];
-        rank += (other > mine || (other == mine && o < q)) ? 1 : 0;
+        rank += (other > mine || (other == mine && o < t)) ? 1 : 0;
     }
-    const size_t lane = (size_t)blockIdx.x * kBlk + rank;
-    len[lane] = (uint8_t)mine;
-    slot[lane] = (uint16_t)q;
+    const size_t ln = (size_t)blockIdx.x * kBlk + rank;
+    len[ln] = (uint8_t)mine;
+    slot[ln] = (uint16_t)t;  // slots past `total` belong to lanes without connections; nobody adds them up
     for (int k = 0; k < kNnz; ++k) {
-        out_idx[lane * kNnz + k] = k < mine ? idx[first + k] : pad;
-        out_val[lane * kNnz + k] = k < mine ? val[first + k] : 0.0f;
+        out_idx[ln * kNnz + k] = k < mine ? idx[first + k] : pad;
+        out_val[ln * kNnz + k] = k < mine ? val[first + k] : 0.0f;
     }
 }
 
