@@ -173,6 +173,32 @@ def test_generated_general_layers_sustained(N, batch, layers, kmin, kmax):
     assert Y.max() == 32.0
 
 
+@pytest.mark.parametrize("kmin,kmax,packed", [(0, 100, True), (33, 64, False)])
+def test_long_neurons_with_windows_stay_in_one_stage(kmin, kmax, packed):
+    """Neurons of blocks of 2048 draw their columns from windows of 2048 columns that lie anywhere in the row
+    (the locality of cfg 4).  The workgroups of a layer with several lanes per neuron are runs of neighbouring
+    neurons; whether they are packed by what their neurons need (0..100 connections) or all alike (33..64), none
+    may reach over a window boundary, or its tile would no longer fit one LDS stage."""
+    import paper_2007_14152_amd as sp
+    N, batch, window, seed = 16384, 9, 2048, 31
+    gen = [synth.gen_layer_general(N, l, seed, kmin, kmax, window) for l in range(2)]
+    ptr, idx, val = [g[0] for g in gen], [g[1] for g in gen], [g[2] for g in gen]
+    bias = synth.gen_bias(N, -0.3)
+    Y0 = synth.gen_y0(batch, N, seed, density="mixed")
+    ref = oracle.infer(idx, val, bias, Y0, ptr=ptr)
+    m = sp.Model.from_csr(ptr, idx, val, bias)
+    assert [m.layer_passes(l) for l in range(2)] == [lanes_per_neuron(p) for p in ptr]
+    assert [m.layer_kernel(l) for l in range(2)] == [sp.SPDNN_KERNEL_SINGLE] * 2
+    assert m.widest_window <= window
+    # what the set-up decides by: workgroups packed by parts against 1024 / P neurons each
+    parts = [-(-np.diff(p) // 32) for p in ptr]
+    assert all((pp.sum() / 1024 * 4 <= 3 * (N // (1024 // lanes_per_neuron(p)))) == packed for pp, p in zip(parts, ptr))
+    n, rows, Y = gpu_infer_general(ptr, idx, val, bias, Y0, model=m)
+    m.close()
+    common, _ = check_against_oracle(ref, n, rows, Y, what="windows, %d..%d connections" % (kmin, kmax))
+    assert common > 0
+
+
 def test_mixed_sign_weights_long_neurons():
     """Weights of both signs over up to 90 connections: held to the float bound for any
     summation order, (K + 2) * eps * sum|y*w|, against the oracle in double."""
