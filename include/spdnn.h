@@ -255,6 +255,15 @@ int spdnn_get_profile(spdnn_t h, int32_t cap, int32_t* layers_run, int32_t* rows
 #define SPDNN_KERNEL_ROW2 6
 int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind);
 
+/* Whether spdnn_infer on `batch` rows runs all layers of the model in ONE launch (*yes = 1) or one launch
+ * per layer (0).  One launch is taken for models of at most 1024 neurons per layer (one workgroup then
+ * computes every neuron of its rows, so Listing 1's loop over the layers -- kernel, pruning, buffer swap
+ * -- can run inside the workgroup) whose layers all fit one LDS stage, when a workgroup's share of the
+ * rows is small (at most 128): the case in which the gaps between dependent kernels outweigh the
+ * kernels.  With profiling on, such a launch's duration is shared out among the layers in proportion
+ * to the rows they had (spdnn_get_profile). */
+int spdnn_one_launch(spdnn_t h, int32_t batch, int32_t* yes);
+
 /* Number of fused-kernel launches (passes) layer l takes: 1, or for a general layer whose
  * longest neuron has K > 32 connections ceil(K/32) rounded up to a power of two. */
 int spdnn_layer_passes(spdnn_t h, int32_t l, int32_t* passes);

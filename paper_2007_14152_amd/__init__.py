@@ -33,7 +33,8 @@ EXPORTS = ("spdnn_weights_bytes", "spdnn_work_bytes", "spdnn_create", "spdnn_inf
            "spdnn_last_error", "spdnn_set_profiling", "spdnn_get_profile", "spdnn_infer_static",
            "spdnn_host_work_bytes", "spdnn_infer_host",
            "spdnn_weights_bytes_for_window", "spdnn_scan_windows", "spdnn_layer_kernel",
-           "spdnn_csr_passes", "spdnn_create_csr", "spdnn_layer_passes", "spdnn_ooc_bytes", "spdnn_create_ooc")
+           "spdnn_csr_passes", "spdnn_create_csr", "spdnn_layer_passes", "spdnn_ooc_bytes", "spdnn_create_ooc",
+           "spdnn_one_launch")
 KERNEL_NAMES = {0: "fused_layer_kernel<false>", 1: "fused_layer_kernel<true>", 2: "fused_wide_kernel",
                 3: "fused_pair_kernel", 4: "fused_wide_pair_kernel", 5: "fused_wide_pair4_kernel", 6: "fused_row2_kernel"}
 
@@ -70,6 +71,7 @@ def lib():
         L.spdnn_scan_windows.argtypes = [i32, i32, ctypes.POINTER(vp), i32, vp, sz, vp, ctypes.POINTER(i32)]
         L.spdnn_layer_kernel.argtypes = [vp, i32, ctypes.POINTER(i32)]
         L.spdnn_layer_passes.argtypes = [vp, i32, ctypes.POINTER(i32)]
+        L.spdnn_one_launch.argtypes = [vp, i32, ctypes.POINTER(i32)]
         L.spdnn_ooc_bytes.argtypes = [i32, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.spdnn_create_ooc.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
                                        i32, vp, sz, vp, sz, vp]
@@ -217,6 +219,13 @@ def spdnn_layer_passes(h, l: int) -> int:
     k = ctypes.c_int32(-1)
     _check(lib().spdnn_layer_passes(ctypes.c_void_p(h), l, ctypes.byref(k)))
     return k.value
+
+
+def spdnn_one_launch(h, batch: int) -> bool:
+    """Does spdnn_infer run all layers of the model in one launch on `batch` rows?"""
+    k = ctypes.c_int32(-1)
+    _check(lib().spdnn_one_launch(ctypes.c_void_p(h), batch, ctypes.byref(k)))
+    return bool(k.value)
 
 
 SPDNN_STATIC_SCRATCH_BYTES = 64 << 20
@@ -401,6 +410,9 @@ class Model:
 
     def layer_passes(self, l):
         return spdnn_layer_passes(self.h, l)
+
+    def one_launch(self, batch):
+        return spdnn_one_launch(self.h, batch)
 
     def close(self):
         if getattr(self, "h", None):

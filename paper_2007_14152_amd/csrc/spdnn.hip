@@ -90,6 +90,10 @@ struct spdnn_model {
     std::vector<LayerDesc> layers;     // one per pass (launch); a layer is one pass unless some neuron has more than 32 connections
     std::vector<int32_t> first_pass;   // L+1 entries: layer l is passes first_pass[l] .. first_pass[l+1]-1
     int* host_counts = nullptr;  // pinned, L+1 entries: rows active on entry to layer l
+    // all layers in one launch (fused_chain_kernel): possible if every layer is a single-stage layer of one output block
+    const spdnn::LayerWeights* chain_layers = nullptr;  // device copy of the layers' descriptors (NULL: not possible)
+    int* chain_rows = nullptr;                          // device, L + 1 counters
+    int chain_lds_cols = 0;
     hipEvent_t lag_ev[kLag] = {};
     // out-of-core weights: pass p's block lives in host memory and is copied into device slot p & 1
     const char* ooc_host = nullptr;
@@ -160,12 +164,15 @@ size_t block_bytes(int32_t N, int nstage_cap) {  // one pass's re-laid weights
     const int32_t nblk = (N + spdnn::kBlk - 1) / spdnn::kBlk;
     return layer_bytes(nblk) + wide_bytes(nblk, nstage_cap);
 }
+size_t chain_bytes(int32_t L) {  // all layers in one launch: the layers' descriptors and the rows-per-layer counters
+    return up((size_t)L * sizeof(spdnn::LayerWeights)) + up(((size_t)L + 1) * sizeof(int));
+}
 size_t arena_bytes_for(int32_t N, int32_t L, int nstage_cap) {
-    return up((size_t)N * sizeof(float)) + (size_t)L * block_bytes(N, nstage_cap) + staging_bytes(N, L);
+    return up((size_t)N * sizeof(float)) + (size_t)L * block_bytes(N, nstage_cap) + staging_bytes(N, L) + chain_bytes(L);
 }
 // out-of-core: the device holds the bias, two blocks and the staging area; the host holds all blocks
 size_t ooc_device_bytes_for(int32_t N, int32_t L, int nstage_cap) {
-    return up((size_t)N * sizeof(float)) + 2 * block_bytes(N, nstage_cap) + staging_bytes(N, L);
+    return up((size_t)N * sizeof(float)) + 2 * block_bytes(N, nstage_cap) + staging_bytes(N, L) + chain_bytes(L);
 }
 
 struct WorkView {
@@ -244,6 +251,8 @@ int allow_large_lds() {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_kernel<8>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_chain_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)spdnn::tile_pair_bytes(spdnn::kBlk)));
     return SPDNN_OK;
 }
 
@@ -385,7 +394,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     }
     constexpr size_t order_lds = spdnn::kOrderPackThreads * sizeof(spdnn::OrderScratch);
     constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
-    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 1),
+    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 2),  // [L + 1]: see infer_impl
                           hipHostMallocDefault));
     for (int i = 0; i < kLag; ++i) HIP_TRY(hipEventCreateWithFlags(&m->lag_ev[i], hipEventDisableTiming));
 
@@ -482,6 +491,10 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     // [1 + 2P + p] pass p has more than one weight value; [1 + 3P + 2p] {two neurons per lane possible, weight bits}
     int* err_dev = reinterpret_cast<int*>(base + o);
     HIP_TRY(hipMemsetAsync(err_dev, 0, sizeof(int) * (size_t)(5 * P + 1), stream));
+    o += up(sizeof(int) * (size_t)(5 * P + 1));
+    spdnn::LayerWeights* chain_layers_dev = reinterpret_cast<spdnn::LayerWeights*>(base + o);
+    o += up((size_t)P * sizeof(spdnn::LayerWeights));
+    int* chain_rows_dev = reinterpret_cast<int*>(base + o);
 
     // Layers that are already on the device and need no staging are set up on several streams in turn.
     struct SetupStreams {
@@ -746,6 +759,21 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     if (herr[0]) return fail(SPDNN_EINVAL, "a column index is outside [0, N)");
     for (int32_t l = 0; l < P; ++l)
         if ((m->layers[l].mode == kWide || m->layers[l].mode == kWidePair) && herr[1 + l]) m->layers[l].mode = kStaged;
+    // One output block and nothing but single-stage layers of one launch each: the whole network can run in one
+    // launch (fused_chain_kernel), which takes the layers' descriptors from device memory.
+    bool chain = nblk == 1 && !ooc && P == L;
+    for (int32_t l = 0; chain && l < P; ++l) chain = m->layers[l].mode == kSingle && !m->layers[l].multi;
+    if (chain) {
+        std::vector<spdnn::LayerWeights> lw((size_t)L);
+        for (int32_t l = 0; l < L; ++l) {
+            lw[l] = m->layers[l].w;
+            m->chain_lds_cols = std::max(m->chain_lds_cols, m->layers[l].lds_cols);
+        }
+        HIP_TRY(hipMemcpyAsync(chain_layers_dev, lw.data(), sizeof(spdnn::LayerWeights) * (size_t)L, hipMemcpyHostToDevice, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        m->chain_layers = chain_layers_dev;
+        m->chain_rows = chain_rows_dev;
+    }
     guard.m = nullptr;
     *out = m;
     return SPDNN_OK;
@@ -802,6 +830,15 @@ int static_scratch(void** out) {
     return SPDNN_OK;
 }
 
+// All layers in one launch (fused_chain_kernel)?  Yes if the model allows it and a workgroup's share of the rows is
+// small enough; *q = the launch's row chunks.
+bool one_launch_shape(spdnn_t h, int32_t batch, int32_t* q) {
+    const int32_t groups = (batch + spdnn::kRows - 1) / spdnn::kRows;
+    const int32_t chunks = std::max(1, std::min(h->num_cu, groups));
+    if (q) *q = chunks;
+    return batch > 0 && h->chain_layers != nullptr && (groups + chunks - 1) / chunks * spdnn::kRows <= spdnn::kChainRows;
+}
+
 // All L layers on `batch` rows whose first row has the original number row_offset; wv = the carved
 // work memory.  Returns with the model's stream drained, also when a HIP call fails half way.
 int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv, int32_t row_offset,
@@ -819,11 +856,39 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
 
     for (int32_t l = 1; l <= L; ++l) h->host_counts[l] = -1;  // "not reported yet"
     h->host_counts[0] = batch;
+    int32_t chain_q = 1;
+    const bool chain = one_launch_shape(h, batch, &chain_q);
     // "layer -1": every row of the batch is flagged alive, under its own number
     spdnn::init_lists_kernel<<<(batch + 255) / 256, 256, 0, s>>>(wv.gid[1], wv.flags[2], wv.flags[0], wv.count[1], batch,
-                                                                 row_offset);
+                                                                 row_offset, chain ? h->chain_rows : nullptr, chain ? L + 1 : 0);
     int32_t bound = batch;  // upper bound of the rows active at the layer being launched
     int32_t run = 0;        // layers launched
+    int32_t rot = 0;        // how often the lists have rotated (= run, unless all layers ran in one launch)
+    int32_t final_buf = 0;  // work buffer that holds the last layer's output
+    std::vector<int> chain_rows_host;
+    // All layers in one launch, if the model allows it and a workgroup's share of the rows fits its lists.
+    if (chain) {
+        if (h->profiling) HIP_TRY(hipEventRecord(h->t0[0], s));
+        spdnn::RowLists rl;  // as "layer 0" of the lists' rotation
+        rl.flags_prev = wv.flags[2];
+        rl.count_prev = wv.count[1];
+        rl.gid_prev = wv.gid[1];
+        rl.cat = wv.cat[0];
+        rl.gid = wv.gid[0];
+        rl.count = wv.count[0];
+        rl.host_count = h->host_counts;
+        rl.flags_clear = wv.flags[1];
+        const spdnn::ChainArgs ca{h->chain_layers, L, h->chain_rows};
+        const size_t lds = spdnn::tile_pair_bytes((h->chain_lds_cols + 255) / 256 * 256);
+        spdnn::fused_chain_kernel<<<(chain_q + 7) / 8 * 8, spdnn::kBlk, lds, s>>>(Y0_dev, wv.Y[0], wv.Y[1], wv.flags[0], rl, ca,
+                                                                                  h->bias_dev, N, chain_q);
+        HIP_TRY(hipGetLastError());
+        if (h->profiling) HIP_TRY(hipEventRecord(h->t1[0], s));
+        chain_rows_host.resize((size_t)L + 1);
+        HIP_TRY(hipMemcpyAsync(chain_rows_host.data(), h->chain_rows, sizeof(int) * ((size_t)L + 1), hipMemcpyDeviceToHost, s));
+        rot = 1;
+        final_buf = (L - 1) & 1;
+    }
     // Out-of-core weights (Section III-B-1): pass p runs from device slot p & 1.  The copy stream fills
     // the two slots, and refills a slot with pass p + 2 as soon as the kernels of pass p are done with
     // it, so the transfer of the next layer runs under the current layer's kernel.
@@ -842,7 +907,7 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
     } drain{h->ooc_stream};
     if (h->ooc_host)
         for (int32_t p = 0; p < std::min(P, 2); ++p) HIP_TRY(ooc_fetch(p));
-    for (int32_t l = 0; l < L; ++l) {
+    for (int32_t l = 0; l < L && !chain; ++l) {
         const float* Yin = (l == 0) ? Y0_dev : wv.Y[(l - 1) & 1];
         float* Yout = wv.Y[l & 1];
         if (h->profiling) HIP_TRY(hipEventRecord(h->t0[l], s));
@@ -966,25 +1031,39 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
             if (bound == 0) break;
         }
     }
-    // the rows that survive the last layer launched: the same compaction, as a kernel of its own
-    spdnn::compact_kernel<<<spdnn::kCompactWGs, 1024, 0, s>>>(wv.flags[(run + 2) % 3], wv.flags[(run + 1) % 3],
-                                                              wv.count[(run + 1) & 1], wv.count[run & 1], wv.gid[(run + 1) & 1],
-                                                              wv.gid[run & 1], wv.cat[run & 1], h->host_counts + run);
+    if (!chain) {
+        rot = run;
+        final_buf = (run - 1) & 1;
+    }
+    // the rows that survive the last layer launched: the same compaction, as a kernel of its own.  Its count goes
+    // to host_counts[run] (rows on entry to the layer that would come next); after a one-launch run the entries
+    // 1 .. L are the launch's own counts, and the survivors' count goes to the spare entry L + 1.
+    const int32_t final_slot = chain ? L + 1 : run;
+    h->host_counts[L + 1] = -1;
+    spdnn::compact_kernel<<<spdnn::kCompactWGs, 1024, 0, s>>>(wv.flags[(rot + 2) % 3], wv.flags[(rot + 1) % 3],
+                                                              wv.count[(rot + 1) & 1], wv.count[rot & 1], wv.gid[(rot + 1) & 1],
+                                                              wv.gid[rot & 1], wv.cat[rot & 1], h->host_counts + final_slot);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(s));
-    const int32_t n = h->host_counts[run];
+    const int32_t n = h->host_counts[final_slot];
     if (n < 0) return fail(SPDNN_EHIP, "layer %d finished without reporting its active rows", run - 1);
+    if (chain) {  // rows on entry to every layer, from the launch's counters; "launched" = up to the first layer without rows
+        run = L;
+        for (int32_t l = 1; l <= L; ++l) {
+            h->host_counts[l] = chain_rows_host[(size_t)l];
+            if (chain_rows_host[(size_t)l] == 0 && run == L && l < L) run = l + 1;
+        }
+    }
     *n_active_host = n;
     if (n > 0) {
-        const int32_t lf = run - 1;  // == L-1 here: rows survive only if every layer ran
-        const int* cat_f = wv.cat[run & 1];
-        const int* gid_f = wv.gid[run & 1];
+        const int* cat_f = wv.cat[rot & 1];
+        const int* gid_f = wv.gid[rot & 1];
         HIP_TRY(hipMemcpyAsync(active_rows_dev, gid_f, sizeof(int) * (size_t)n, hipMemcpyDeviceToDevice, s));
         if (Y_final_dev) {
             const int n4 = N / 4;
             const size_t total = (size_t)n * n4;
             const int g = (int)std::min<size_t>((total + 255) / 256, 65536);
-            spdnn::gather_rows_kernel<<<g, 256, 0, s>>>(reinterpret_cast<const float4*>(wv.Y[lf & 1]), cat_f, n, n4,
+            spdnn::gather_rows_kernel<<<g, 256, 0, s>>>(reinterpret_cast<const float4*>(wv.Y[final_buf]), cat_f, n, n4,
                                                        reinterpret_cast<float4*>(Y_final_dev));
             HIP_TRY(hipGetLastError());
         }
@@ -995,9 +1074,18 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
         h->prof_layers = run;
         h->prof_ms.assign(run, 0.0f);
         h->prof_rows.assign(run, 0);
+        float chain_ms = 0.0f;
+        double chain_rows_sum = 0.0;
+        if (chain) {  // one launch: its time is shared out among the layers by the rows they had
+            HIP_TRY(hipEventElapsedTime(&chain_ms, h->t0[0], h->t1[0]));
+            for (int32_t l = 0; l < run; ++l) chain_rows_sum += (double)h->host_counts[l];
+        }
         for (int32_t l = 0; l < run; ++l) {
             h->prof_rows[l] = h->host_counts[l];
-            HIP_TRY(hipEventElapsedTime(&h->prof_ms[l], h->t0[l], h->t1[l]));
+            if (chain)
+                h->prof_ms[l] = chain_rows_sum > 0 ? (float)(chain_ms * (double)h->host_counts[l] / chain_rows_sum) : 0.0f;
+            else
+                HIP_TRY(hipEventElapsedTime(&h->prof_ms[l], h->t0[l], h->t1[l]));
         }
     }
     return SPDNN_OK;
@@ -1210,6 +1298,13 @@ int spdnn_layer_kernel(spdnn_t h, int32_t l, int32_t* kind) {
                   "layer modes are the header's kernel kinds");
     const LayerDesc& d = h->layers[h->first_pass[l]];
     *kind = (d.mode == kWidePair && d.pair4) ? SPDNN_KERNEL_WIDE_PAIR4 : d.mode == kRow2 ? SPDNN_KERNEL_ROW2 : d.mode;
+    return SPDNN_OK;
+}
+
+int spdnn_one_launch(spdnn_t h, int32_t batch, int32_t* yes) {
+    if (!h || !yes) return fail(SPDNN_EINVAL, "null argument");
+    if (batch < 0) return fail(SPDNN_EINVAL, "batch < 0");
+    *yes = one_launch_shape(h, batch, nullptr) ? 1 : 0;
     return SPDNN_OK;
 }
 

@@ -1676,6 +1676,7 @@ __global__ __launch_bounds__(kBlk) void fused_wide_pair4_kernel(
 
 }  // namespace spdnn
 #include "spdnn_row2.h"
+#include "spdnn_chain.h"
 namespace spdnn {
 
 // Compact form of a wide layer's steps for the two-neurons-per-lane wide kernels: the 16-bit
@@ -1817,7 +1818,7 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* __restrict
 // numbered through).
 __global__ void init_lists_kernel(int* __restrict__ gid_prev, uint8_t* __restrict__ flags_prev,
                                   uint8_t* __restrict__ flags_first, int* __restrict__ count_prev, int batch,
-                                  int row_offset) {
+                                  int row_offset, int* __restrict__ counters = nullptr, int ncounters = 0) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < batch) {
         gid_prev[i] = row_offset + i;
@@ -1825,6 +1826,8 @@ __global__ void init_lists_kernel(int* __restrict__ gid_prev, uint8_t* __restric
         flags_first[i] = 0;
     }
     if (i == 0) *count_prev = batch;
+    // counters that the inference adds to (rows per layer of a one-launch run), cleared here
+    for (int k = i; k < ncounters; k += gridDim.x * blockDim.x) counters[k] = 0;
 }
 
 // a4: surviving rows of Y_L, gathered into a dense [n][N] array (16-byte pieces).

@@ -152,9 +152,14 @@ int main(void) {
         }
         hipFree(harena);
     }
-    int32_t kind = -1, passes = -1;
+    int32_t kind = -1, passes = -1, one = -1;
     CHECK_SP(spdnn_layer_kernel(net, 0, &kind));
     CHECK_SP(spdnn_layer_passes(net, 0, &passes));
+    CHECK_SP(spdnn_one_launch(net, BATCH, &one));
+    if (one != 0 && one != 1) {
+        fprintf(stderr, "spdnn_one_launch answered %d\n", one);
+        return 1;
+    }
     CHECK_SP(spdnn_destroy(net));
     /* error path: a positive bias must be refused */
     bias[5] = 0.5f;

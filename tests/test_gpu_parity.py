@@ -549,6 +549,47 @@ def test_rows_die_in_every_layer_closed_form(N, batch, kernel):
     m.close()
 
 
+@pytest.mark.parametrize("N,L", [(1024, 7), (96, 5)])
+def test_all_layers_in_one_launch_equals_one_launch_per_layer(N, L):
+    """Networks of at most 1024 neurons run all layers in one launch when a workgroup's share of the rows is
+    small (Listing 1's loop over the layers inside the workgroup), one launch per layer otherwise.  The
+    arithmetic per row is the same: the rows of a small batch must come out bit for bit as the same rows do
+    inside a large batch, with the same rows alive on entry to every layer; and both agree with the oracle."""
+    import torch
+    import paper_2007_14152_amd as sp
+    dev = "cuda:0"
+    rng = np.random.default_rng(N + L)
+    idx = [np.sort(rng.integers(0, N, size=(N, 32)), axis=1).astype(np.int32) for _ in range(L)]
+    val = [rng.uniform(0.02, 0.11, size=(N, 32)).astype(np.float32) for _ in range(L)]
+    bias = -rng.uniform(0.0, 0.4, size=N).astype(np.float32)
+    big, small = 40000, 3001
+    Y0 = synth.gen_y0(big, N, 17, density="mixed")
+    m = sp.Model(idx, val, bias, device=dev)
+    assert m.one_launch(small) and not m.one_launch(big) and m.one_launch(128 * 256) and not m.one_launch(128 * 256 + 4)
+    m.set_profiling(True)
+    y_big = torch.from_numpy(Y0).to(dev)
+    nb, rb, Yb = m.infer(y_big)
+    run_b, rows_b, _ = m.profile()
+    ns, rs, Ys = m.infer(y_big[:small].contiguous())
+    run_s, rows_s, ms_s = m.profile()
+    rb_h, rs_h = rb.cpu().numpy(), rs.cpu().numpy()
+    assert 0 < ns < small
+    keep = rb_h < small
+    assert np.array_equal(rb_h[keep], rs_h)
+    assert torch.equal(Yb[torch.from_numpy(keep).to(dev)], Ys)
+    ref = oracle.infer(idx, val, bias, Y0[:small])
+    check_against_oracle(ref, ns, rs_h, Ys.cpu().numpy(), what="one launch N=%d" % N)
+    # rows on entry to every layer, from the launch's own counters
+    assert run_s == L and [int(x) for x in rows_s[:L]] == [int(x) for x in ref.active_per_layer[:L]]
+    assert float(ms_s.sum()) > 0 and all(float(x) > 0 for x in ms_s[:L])
+    # every row dies: "launched" ends one layer after the first without rows, as with one launch per layer
+    zero = torch.zeros((500, N), dtype=torch.float32, device=dev)
+    n0, _, _ = m.infer(zero)
+    run0, rows0, _ = m.profile()
+    assert n0 == 0 and run0 == 2 and [int(x) for x in rows0[:2]] == [500, 0]
+    m.close()
+
+
 @pytest.mark.parametrize("uniform", [True, False])
 def test_largest_n_with_columns_anywhere(uniform):
     """N = 65536 (the largest the 16-bit column offsets allow) with columns drawn from the whole
