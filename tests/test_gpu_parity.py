@@ -696,6 +696,43 @@ def test_strided_layers_wrap_around_the_row_end(N, strides, uniform, kinds):
     assert common > 0
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_seeded_sweep_over_layer_shapes(seed):
+    """Drawn combinations of N, depth, batch, one weight or many, and strides: whatever kernel and launch mode
+    the library picks for them (one launch for all layers, one to four neurons per lane, units of interleaved
+    segments, wide windows), the result is the oracle's."""
+    import paper_2007_14152_amd as sp
+    seen = set()
+    for case in range(16):
+        rng = np.random.default_rng(seed * 100003 + case)
+        if case % 2 == 0:
+            N = int(rng.choice([32, 64, 100, 512, 1024, 1028, 2048, 4096]))
+            L = int(rng.integers(1, 5))
+            batch = int(rng.choice([1, 3, 7, 129, 1000, 5000, 40000 if N <= 1024 else 300]))
+            idx = [np.sort(rng.integers(0, N, size=(N, 32)), axis=1).astype(np.int32) for _ in range(L)]
+            uni = rng.uniform() < 0.4
+            val = [np.full((N, 32), 0.0625, np.float32) if uni else rng.uniform(0.02, 0.11, size=(N, 32)).astype(np.float32)
+                   for _ in range(L)]
+            bias = -rng.uniform(0.0, 0.4, size=N).astype(np.float32)
+        else:
+            N = int(rng.choice([4096, 8192, 12288, 16384, 32768]))
+            L = int(rng.integers(1, 4))
+            batch = int(rng.choice([2, 9, 31]))
+            idx = [synth.gen_layer_strided(N, int(rng.choice([1, 4, 32, N // 64, N // 32, N // 16, 1000]))) for _ in range(L)]
+            val = [synth.gen_values(N) for _ in range(L)]
+            bias = synth.gen_bias(N, -0.3)
+        Y0 = synth.gen_y0(batch, N, case, density="mixed")
+        ref = oracle.infer(idx, val, bias, Y0)
+        m = sp.Model(idx, val, bias)
+        what = "sweep %d/%d N=%d L=%d batch=%d one launch=%s kernels=%s" % (
+            seed, case, N, L, batch, m.one_launch(batch), [sp.KERNEL_NAMES[m.layer_kernel(l)] for l in range(L)])
+        seen.add("one launch" if m.one_launch(batch) else sp.KERNEL_NAMES[m.layer_kernel(0)])
+        n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
+        m.close()
+        check_against_oracle(ref, n, rows, Y, what=what)
+    assert len(seen) >= 4, seen
+
+
 @pytest.mark.parametrize("rows_per_batch", [1000, 257, 64, 5000])
 def test_inputs_in_host_memory_in_serial_batches(rows_per_batch):
     """Section III-B-2: the inputs stay on the host and go through the GPU batch by batch
