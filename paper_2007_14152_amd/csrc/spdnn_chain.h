@@ -116,22 +116,6 @@ __global__ __launch_bounds__(kBlk) void fused_chain_kernel(
         float* Yout = (l & 1) ? Yb : Ya;
         const int2 win = w.win[0];
         const int c_lo = win.x, ncols = win.y;
-        // my neuron's connections: LDS byte address (buffer 0) of the column, and the weight
-        uint32_t off[kNnz];
-        float wv[kNnz];
-        {
-            // (the lane number is made opaque per layer: the 64 load addresses it leads to would otherwise be worked
-            // out once, ahead of the layer loop, and kept -- spilled -- for all layers)
-            int tl = tid;
-            asm volatile("" : "+v"(tl));
-            const uint16_t* prel = w.rel + tl;
-            const float* pval = w.val + tl;
-#pragma unroll
-            for (int k = 0; k < kNnz; ++k) {
-                off[k] = lds_base + tile_offset((uint32_t)prel[k * kBlk] & (kCap - 1));
-                wv[k] = pval[k * kBlk];
-            }
-        }
         const uint32_t qp = w.qsel[tid];
         const size_t coff = (size_t)win_col(c_lo, min(4 * tid, ncols - 4), N);  // my four staged columns (windows are cyclic)
         const bool staging = wave_col < ncols;
@@ -161,6 +145,26 @@ __global__ __launch_bounds__(kBlk) void fused_chain_kernel(
         auto store_tile = [&](int P) {
             if (staging) stage_store(st, st_addr + P * kBufSkew, qp);
         };
+        // the first tile's loads go out ahead of the layer's connections, so that both are in flight together
+        fetch_rows(0);
+        load_tile();
+        // my neuron's connections: LDS byte address (buffer 0) of the column, and the weight
+        uint32_t off[kNnz];
+        float wv[kNnz];
+        {
+            // (the lane number is made opaque per layer: the 64 load addresses it leads to would otherwise be worked
+            // out once, ahead of the layer loop, and kept -- spilled -- for all layers)
+            int tl = tid;
+            asm volatile("" : "+v"(tl));
+            const uint16_t* prel = w.rel + tl;
+            const float* pval = w.val + tl;
+#pragma unroll
+            for (int k = 0; k < kNnz; ++k) {
+                off[k] = lds_base + tile_offset((uint32_t)prel[k * kBlk] & (kCap - 1));
+                wv[k] = pval[k * kBlk];
+            }
+        }
+
         float acc[kRows] = {0.f, 0.f, 0.f, 0.f};
         auto compute = [&](auto Ptag, auto Ktag) {
             constexpr int P = decltype(Ptag)::value;
@@ -194,8 +198,6 @@ __global__ __launch_bounds__(kBlk) void fused_chain_kernel(
         };
         using P0 = std::integral_constant<int, 0>;
         using P1 = std::integral_constant<int, 1>;
-        fetch_rows(0);
-        load_tile();
         store_tile(0);
         if (T > 1) {
             fetch_rows(1);
