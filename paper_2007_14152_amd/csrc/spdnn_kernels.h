@@ -778,7 +778,7 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
     const int cat_last = rows_of.last();  // used by the last, ragged group only: then the list's last entry
     int4 c4 = make_int4(0, 0, 0, 0);  // slots (in Yin) of the 4 rows of the tile to load next
 
-    // cat[] is padded so that the 16-byte read of the last, ragged group stays inside it
+    // the four rows of the tile to load next (the last, ragged group repeats the list's last row)
     auto fetch_rows = [&](int t) {
         const int gi = MULTI ? t / nstage : t;
         c4 = rows_of.get4((g0 + gi) * kRows);
