@@ -78,6 +78,8 @@ struct LayerDesc {
     spdnn::VirtInfo virt;
     int virt_lanes = 1;  // multi: lanes of the layer's longest neuron (the layer's passes)
     int virt_blocks = 0;  // multi: workgroups of this launch that have neurons
+    bool relabel = false;  // kPair under new names for neurons and columns (spdnn::PairRelabel)
+    spdnn::PairRelabel rn{};
 };
 
 }  // namespace
@@ -237,7 +239,9 @@ int allow_large_lds() {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<1>)));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<2>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(spdnn::BalanceScratch<2>)));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel),
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_pair_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::fused_wide_pair_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds + spdnn::kPadLds));
@@ -639,6 +643,63 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipMemcpyAsync(pair_info, pair_dev, sizeof(pair_info), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
+        // One weight, but the windows are too wide for two neurons per lane.  If units of 2048 neurons in segments
+        // (unit_neuron) read columns that do not overlap, at most 2048 each -- the strided patterns that RadiX-Net
+        // layers are (Section II-A) -- neurons and columns get new names under which every unit has a contiguous
+        // window, and the layer is set up again as an ordinary one for the two-neurons-per-lane kernel.
+        if (pair_info[0] == 2 && r2_room && d.ww.pk != nullptr && N % spdnn::kPairUnit == 0) {
+            const int32_t nunit2 = N / spdnn::kPairUnit;
+            constexpr int kCand2 = spdnn::kSegLog2Max - 1 - 5 + 1;  // segments of 2048 down to 32 neurons
+            std::vector<int> ngr2((size_t)nunit2 * kCand2);
+            int* cnt_dev = reinterpret_cast<int*>(d.r2_map);
+            spdnn::row2_footprint_kernel<<<dim3(nunit2, kCand2), spdnn::kBlk, 0, stream>>>(di, N, cnt_dev, spdnn::kPairUnit);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(hipMemcpyAsync(ngr2.data(), cnt_dev, sizeof(int) * ngr2.size(), hipMemcpyDeviceToHost, stream));
+            HIP_TRY(hipStreamSynchronize(stream));
+            int best_a = -1, best = spdnn::kPairUnit / 4 + 1;
+            for (int y = 0; y < kCand2; ++y) {
+                const int most = *std::max_element(ngr2.begin() + (size_t)y * nunit2, ngr2.begin() + (size_t)(y + 1) * nunit2);
+                if (most < best) {
+                    best = most;
+                    best_a = spdnn::kSegLog2Max - 1 - y;
+                }
+            }
+            if (best_a >= 0) {  // every unit within 2048 columns: do they overlap?
+                const int stride2 = nunit2 << best_a;
+                int* owner = reinterpret_cast<int*>(slot_tab);  // this stream's table as scratch: N/4 owners, N/4 new names, a flag
+                int* newname = owner + N / 4;
+                int* conflict = newname + N / 4;
+                HIP_TRY(hipMemsetAsync(owner, 0xff, sizeof(int) * (size_t)(N / 4), stream));
+                HIP_TRY(hipMemsetAsync(conflict, 0, sizeof(int), stream));
+                spdnn::relabel_owner_kernel<<<nunit2, spdnn::kBlk, 0, stream>>>(di, N, best_a, stride2, owner, conflict);
+                spdnn::relabel_rank_kernel<<<nunit2, spdnn::kBlk, 0, stream>>>(owner, N, newname, d.r2_map, conflict);
+                HIP_TRY(hipGetLastError());
+                int clash = 1;
+                HIP_TRY(hipMemcpyAsync(&clash, conflict, sizeof(int), hipMemcpyDeviceToHost, stream));
+                HIP_TRY(hipStreamSynchronize(stream));
+                if (!clash) {
+                    // the layer under its new names is written where its wide format would go (it will not have one):
+                    // room for 32 steps of 8 bytes per neuron, of which 4 bytes per connection are needed
+                    int32_t* renamed = reinterpret_cast<int32_t*>(const_cast<uint2*>(d.ww.pk));
+                    spdnn::relabel_apply_kernel<<<(unsigned)((raw + 255) / 256), 256, 0, stream>>>(di, N, best_a, stride2, newname, renamed);
+                    HIP_TRY(hipGetLastError());
+                    di = renamed;
+                    d.relabel = true;
+                    d.rn = spdnn::PairRelabel{d.r2_map, best_a, stride2};
+                    // the windows, and whether pairs of blocks fit one stage, under the new names
+                    HIP_TRY(hipMemsetAsync(widest_dev, 0, sizeof(int), stream));
+                    spdnn::block_window_kernel<<<nblk, spdnn::kBlk, 0, stream>>>(di, N, win_dev[l], err_dev, widest_dev, dv,
+                                                                                   err_dev + 1 + 2 * P + l, nrows);
+                    spdnn::pair_merge_kernel<<<1, 64, 0, stream>>>(win_dev[l], nblk, N, dv, err_dev + 1 + 2 * P + l, widest_dev,
+                                                                   pair_dev);
+                    HIP_TRY(hipGetLastError());
+                    HIP_TRY(hipMemcpyAsync(&hw[(size_t)l * nblk], win_dev[l], sizeof(int2) * nblk, hipMemcpyDeviceToHost, stream));
+                    HIP_TRY(hipMemcpyAsync(pair_info, pair_dev, sizeof(pair_info), hipMemcpyDeviceToHost, stream));
+                    HIP_TRY(hipStreamSynchronize(stream));
+                    if (pair_info[0] != 1) return fail(SPDNN_EHIP, "layer %d: relabelled units do not fit one stage", ll);
+                }
+            }
+        }
         const int pair = pair_info[0] == 1;        // two neurons per lane, single stage
         const bool wide_pair = pair_info[0] == 2;  // ... if the layer also fits the wide format
         // one weight, every block wider than one stage, and every 4096-neuron unit within 16384 columns:
@@ -970,8 +1031,11 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
                     spdnn::fused_layer_kernel<false, true><<<grid, spdnn::kBlk, lds + kVirtLds, s>>>(
                         Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, h->nblk, G, Q, vi);
             }
+            else if (d.mode == kPair && d.relabel)
+                spdnn::fused_pair_kernel<true><<<grid, spdnn::kBlk, lds, s>>>(
+                    Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, ncb, G, Q, d.wuni, d.rn);
             else if (d.mode == kPair)
-                spdnn::fused_pair_kernel<<<grid, spdnn::kBlk, lds, s>>>(
+                spdnn::fused_pair_kernel<false><<<grid, spdnn::kBlk, lds, s>>>(
                     Yin, Yout, wv.flags[l % 3], rl, d.w, h->bias_dev, N, ncb, G, Q, d.wuni);
             else if (d.mode == kWidePair && d.pair4 && d.ww.nstage == 2)  // + the all-zero entries and the spill table
                 spdnn::fused_wide_pair4_kernel<2, 32><<<grid, spdnn::kBlk, lds + spdnn::kPair4LdsExtra, s>>>(

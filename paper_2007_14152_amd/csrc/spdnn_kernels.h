@@ -932,11 +932,22 @@ __global__ __launch_bounds__(kBlk) void fused_layer_kernel(
 // 2u+1, set up with one common window and one common tile layout).  A staged tile
 // then serves 2048 outputs: half the tile loads, LDS tile writes and L2 -> CU bytes
 // per output.  Same pipeline as fused_layer_kernel<false>; nunit = number of units.
+//
+// RELABEL: the layer was set up under new names for neurons and columns (PairRelabel): the unit's 2048
+// neurons are segments of neighbours at a stride (unit_neuron) and its tile holds the groups of four columns
+// the unit reads, wherever they lie in the row.  Only what touches global memory knows: the staging lanes'
+// load offsets come from the list of those groups, and bias and output addresses use the neurons' real numbers.
 // ---------------------------------------------------------------------------
+struct PairRelabel {
+    const int32_t* col;  // [N / 4] first real column of the group of four columns that carries the new name 4g .. 4g+3
+    int seg_log2;        // a unit's neurons: segments of 1 << seg_log2 neighbours, one every seg_stride neurons
+    int seg_stride;
+};
+template <bool RELABEL = false>
 __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
     RowLists rl, LayerWeights w,
-    const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni) {
+    const float* __restrict__ bias, int N, int nunit, int G, int Q, float wuni, PairRelabel rn = PairRelabel{}) {
     extern __shared__ float4 lds4[];
     const int tid = threadIdx.x;
     WorkItem wi;
@@ -946,7 +957,9 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     const int u = wi.cb, A = wi.A, g0 = wi.g0, g1 = wi.g1;
     const int b = 2 * u;  // first of the unit's two output blocks
 
-    const int jA = b * kBlk + tid, jB = jA + kBlk;  // N is a multiple of 2048 here: both exist
+    // my two neurons (N is a multiple of 2048 here: both exist); four neighbouring lanes hold four neighbouring neurons
+    const int jA = RELABEL ? unit_neuron(u, tid, rn.seg_log2, rn.seg_stride) : b * kBlk + tid;
+    const int jB = RELABEL ? unit_neuron(u, kBlk + tid, rn.seg_log2, rn.seg_stride) : jA + kBlk;
     const int2 win = w.win[b];
     const int c_lo = win.x;
     const int ncols = win.y;
@@ -972,7 +985,8 @@ __global__ __launch_bounds__(kBlk) void fused_pair_kernel(
     ListWindow rows_of(cat, g0 * kRows, min(A, g1 * kRows), wi.identity);
     const int cat_last = rows_of.last();  // used by the last, ragged group only: then the list's last entry
     // byte offset of my four columns in a row; lanes past the window re-read its last columns
-    const uint32_t ld_off = 4u * (uint32_t)win_col(c_lo, min(4 * tid, ncols - 4), N);  // windows are cyclic
+    const uint32_t ld_off = 4u * (uint32_t)(RELABEL ? rn.col[win_col(c_lo, min(4 * tid, ncols - 4), N) >> 2]
+                                                    : win_col(c_lo, min(4 * tid, ncols - 4), N));  // windows are cyclic
     const char* ld_row[kRows] = {nullptr, nullptr, nullptr, nullptr};  // bases of the 4 rows of the tile to load (scalar)
 
     auto fetch_rows = [&](int t) {

@@ -401,19 +401,21 @@ __global__ __launch_bounds__(kBlk) void row2_gather_kernel(const int32_t* __rest
 }
 
 // The sizes alone, for every segment length at once: workgroup (u, y) counts the groups of four columns that
-// unit u touches with segments of 1 << (kSegLog2Max - y) neurons; out[y * gridDim.x + u].
-__global__ __launch_bounds__(kBlk) void row2_footprint_kernel(const int32_t* __restrict__ idx, int N, int* __restrict__ out) {
+// unit u (of `unit` neurons: 4096, or 2048 for the two-neurons-per-lane kernel) touches with segments of
+// 1 << (log2(unit) - y) neurons; out[y * gridDim.x + u].
+__global__ __launch_bounds__(kBlk) void row2_footprint_kernel(const int32_t* __restrict__ idx, int N, int* __restrict__ out,
+                                                              int unit = kUnit4) {
     __shared__ uint32_t bits[65536 / 4 / 32];
     __shared__ int total;
     const int u = blockIdx.x;
-    const int seg_log2 = kSegLog2Max - (int)blockIdx.y;
-    const int seg_stride = (N / kUnit4) << seg_log2;
+    const int seg_log2 = (unit == kUnit4 ? kSegLog2Max : kSegLog2Max - 1) - (int)blockIdx.y;
+    const int seg_stride = (N / unit) << seg_log2;
     const int tid = threadIdx.x;
     const int words = (N / 4 + 31) / 32;
     for (int i = tid; i < words; i += kBlk) bits[i] = 0;
     if (tid == 0) total = 0;
     __syncthreads();
-    for (int e = tid; e < kUnit4 * kNnz; e += kBlk) {
+    for (int e = tid; e < unit * kNnz; e += kBlk) {
         const int c = idx[(size_t)unit_neuron(u, e / kNnz, seg_log2, seg_stride) * kNnz + (e % kNnz)];
         if (c >= 0 && c < N) atomicOr(&bits[c >> 7], 1u << ((c >> 2) & 31));
     }
@@ -459,6 +461,89 @@ __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32
             const size_t word = ((size_t)(u * 4 + s) * 4 + (step >> 3)) * kBlk + lane0 + l;
             codes[word * 8 + (step & 7)] = (uint16_t)pos_of(l, k);
         });
+}
+
+// ---------------------------------------------------------------------------
+// a0: new names for neurons and columns, so that a strided layer fits the two-neurons-per-lane kernel
+// (PairRelabel).  Units of kPairUnit neurons in segments (unit_neuron); if the units' columns do not overlap and
+// no unit reads more than kPairUnit columns, unit u's groups of four columns get the new names u * kPairUnit / 4 + rank
+// (ascending), its neurons the new numbers u * kPairUnit + local index, and under the new names every unit has a
+// contiguous window of at most kPairUnit columns: an ordinary layer for the set-up and the kernel.
+// ---------------------------------------------------------------------------
+constexpr int kPairUnit = 2 * kBlk;
+
+// owner[g] = the unit that reads group g (-1: none); *conflict = 1 if two units read the same group.
+__global__ __launch_bounds__(kBlk) void relabel_owner_kernel(const int32_t* __restrict__ idx, int N, int seg_log2,
+                                                             int seg_stride, int* __restrict__ owner,
+                                                             int* __restrict__ conflict) {
+    const int u = blockIdx.x;
+    for (int e = threadIdx.x; e < kPairUnit * kNnz; e += kBlk) {
+        const int c = idx[(size_t)unit_neuron(u, e / kNnz, seg_log2, seg_stride) * kNnz + (e % kNnz)];
+        if (c < 0 || c >= N) continue;  // reported by the window scan
+        const int old = atomicCAS(&owner[c >> 2], -1, u);
+        if (old != -1 && old != u) *conflict = 1;
+    }
+}
+
+// Unit u's groups in ascending order: newname[g] = u * (kPairUnit / 4) + rank, col[that] = 4 g; names of the unit
+// that no group got point at the unit's last group (or column 0).  *conflict = 1 if a unit has more than
+// kPairUnit / 4 groups.
+__global__ __launch_bounds__(kBlk) void relabel_rank_kernel(const int* __restrict__ owner, int N, int* __restrict__ newname,
+                                                            int32_t* __restrict__ col, int* __restrict__ conflict) {
+    __shared__ int wave_cnt[17];
+    __shared__ int s_max;
+    const int u = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int cap = kPairUnit / 4;
+    int base = 0;
+    for (int g0 = 0; g0 < N / 4; g0 += kBlk) {
+        const int g = g0 + tid;
+        const bool mine = g < N / 4 && owner[g] == u;
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(mine);
+        __syncthreads();
+        if (lane == 0) wave_cnt[wave] = __popcll(m);
+        __syncthreads();
+        if (tid == 0) {
+            int run = 0;
+            for (int k = 0; k < 16; ++k) {
+                const int v = wave_cnt[k];
+                wave_cnt[k] = run;
+                run += v;
+            }
+            wave_cnt[16] = run;
+        }
+        __syncthreads();
+        if (mine) {
+            const int r = base + wave_cnt[wave] + __popcll(m & ((1ull << lane) - 1ull));
+            if (r < cap) {
+                newname[g] = u * cap + r;
+                col[u * cap + r] = 4 * g;
+            } else {
+                *conflict = 1;
+            }
+        }
+        base += wave_cnt[16];
+    }
+    __syncthreads();
+    // the names past the unit's last group: any of its columns will do (a harmless load); take its largest
+    if (base < cap) {
+        if (tid == 0) s_max = 0;
+        __syncthreads();
+        for (int r = tid; r < base; r += kBlk) atomicMax(&s_max, col[u * cap + r]);
+        __syncthreads();
+        for (int r = base + tid; r < cap; r += kBlk) col[u * cap + r] = s_max;
+    }
+}
+
+// The layer under the new names: row u * kPairUnit + p = the connections of unit u's p-th neuron, every column
+// by its new name (columns out of range are passed through, for the window scan to report).
+__global__ void relabel_apply_kernel(const int32_t* __restrict__ idx, int N, int seg_log2, int seg_stride,
+                                     const int* __restrict__ newname, int32_t* __restrict__ out_idx) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)N * kNnz) return;
+    const int v = (int)(i / kNnz), k = (int)(i % kNnz);
+    const int c = idx[(size_t)unit_neuron(v / kPairUnit, v % kPairUnit, seg_log2, seg_stride) * kNnz + k];
+    out_idx[i] = (c >= 0 && c < N) ? 4 * newname[c >> 2] + (c & 3) : c;
 }
 
 }  // namespace spdnn

@@ -662,14 +662,16 @@ def test_scattered_windows_gathered_footprint(N, w, batch):
     (8192, (1, 32), True, "PAIR"),              # the last unit's window runs over the row end
     (8192, (32, 1), False, "SINGLE"),           # the same with two weight values: one neuron per lane
     (8192, (160,), False, "STAGED"),            # two stages, cyclic
-    (16384, (256, 1, 32), True, "ROW2 PAIR PAIR"),  # two-row tiles whose window wraps
+    (16384, (256, 1, 32), True, "PAIR PAIR PAIR"),  # stride 256: two neurons per lane under new names for neurons and columns
     (16384, (256,), False, "WIDE"),             # three stages, one neuron per lane
     (10240, (256,), True, "WIDE_PAIR4"),        # three stages, two neurons per lane, step lists in registers
     (32768, (700,), True, "WIDE_PAIR"),         # six stages, two neurons per lane
     (65536, (1500,), False, "WIDE"),            # twelve stages of eight steps
-    (65536, (1024, 2048, 32), True, "ROW2 ROW2 PAIR"),  # units of interleaved segments: 64 x 64 and 32 x 128 neurons
-    (16384, (512,), True, "ROW2"),              # the window fits the tile, the interleaved unit needs a quarter of it
-    (12288, (384,), True, "ROW2"),              # three units, segments every 384 neurons
+    (65536, (1024, 2048, 32), True, "PAIR PAIR PAIR"),  # units of 64 segments of 32 and 32 segments of 64 neurons, renamed
+    (16384, (512,), True, "PAIR"),              # 8 units of 32 segments of 64 neurons
+    (12288, (384,), True, "PAIR"),              # six units, segments every 384 neurons
+    (65536, (-1024,), True, "ROW2"),            # (see below) neighbouring units share columns: no renaming; units of
+                                                # interleaved segments on two-row tiles
 ])
 def test_strided_layers_wrap_around_the_row_end(N, strides, uniform, kinds):
     """Strided, modular patterns (neuron j reads (j + k*S) mod N): the footprint of the last blocks runs
@@ -678,7 +680,14 @@ def test_strided_layers_wrap_around_the_row_end(N, strides, uniform, kinds):
     import paper_2007_14152_amd as sp
     rng = np.random.default_rng(N + len(strides))
     L, batch = len(strides), 11
-    idx = [synth.gen_layer_strided(N, s_) for s_ in strides]
+    def layer(s_):
+        if s_ > 0:
+            return synth.gen_layer_strided(N, s_)
+        # stride -s_, every other connection 32 columns further on: the columns of neighbouring 32-residue classes overlap
+        j = np.arange(N, dtype=np.int64)[:, None]
+        k = np.arange(32, dtype=np.int64)[None, :]
+        return np.sort((j + k * (-s_) + (k & 1) * 32) % N, axis=1).astype(np.int32)
+    idx = [layer(s_) for s_ in strides]
     if uniform:
         val = [synth.gen_values(N) for _ in range(L)]
     else:
@@ -730,7 +739,7 @@ def test_seeded_sweep_over_layer_shapes(seed):
         n, rows, Y = gpu_infer(idx, val, bias, Y0, model=m)
         m.close()
         check_against_oracle(ref, n, rows, Y, what=what)
-    assert len(seen) >= 4, seen
+    assert len(seen) >= 3, seen
 
 
 @pytest.mark.parametrize("rows_per_batch", [1000, 257, 64, 5000])
