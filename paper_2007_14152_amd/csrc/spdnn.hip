@@ -580,7 +580,50 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
                 const size_t plain = (size_t)(N + R - 1) / R;
                 if (virt_ranges.size() > (size_t)passes_of[ll] * nblk || 4 * virt_ranges.size() > 3 * plain) {
                     virt_ranges.clear();
-                    for (int j = 0; j < N; j += R) virt_ranges.push_back(make_int2(j, std::min(R, N - j)));
+                    // The workgroups that will share an XCD (a run of Gl: they read the same rows through one
+                    // window, and stay within reach of each other in the L2 only if they take equally long) get
+                    // equally many lanes rather than equally many neurons.
+                    int Gl = 1;
+                    for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
+                        if (g <= m->G * passes_of[ll] && nblk % g == 0) {
+                            Gl = g;
+                            break;
+                        }
+                    auto lanes4 = [&](int j) {
+                        int q = 0;
+                        for (int i = 0; i < 4; ++i) q += (hp[j + i + 1] - hp[j + i] + spdnn::kNnz - 1) / spdnn::kNnz;
+                        return q;
+                    };
+                    for (int r0 = 0; r0 < N; r0 += Gl * R) {
+                        const int r1 = std::min(N, r0 + Gl * R);
+                        const int nW = (r1 - r0 + R - 1) / R;
+                        long left = 0;
+                        for (int j = r0; j < r1; j += 4) left += lanes4(j);
+                        const size_t mark = virt_ranges.size();
+                        int first = r0, lanes = 0, wleft = nW;
+                        long target = (left + wleft - 1) / wleft;
+                        bool ok = true;
+                        for (int j = r0; j < r1; j += 4) {
+                            const int q = lanes4(j);
+                            const bool full = lanes + q > spdnn::kBlk || j - first == spdnn::kBlk;
+                            if (j > first && (full || (wleft > 1 && lanes + q - target > target - lanes))) {
+                                virt_ranges.push_back(make_int2(first, j - first));
+                                left -= lanes;
+                                wleft = std::max(1, wleft - 1);
+                                target = (left + wleft - 1) / wleft;
+                                first = j;
+                                lanes = 0;
+                            }
+                            lanes += q;
+                        }
+                        virt_ranges.push_back(make_int2(first, r1 - first));
+                        ok = virt_ranges.size() - mark <= (size_t)nW;
+                        if (!ok) {  // (only if a workgroup overflowed on the way) the cut by neurons always fits
+                            virt_ranges.resize(mark);
+                            for (int j = r0; j < r1; j += R) virt_ranges.push_back(make_int2(j, std::min(R, r1 - j)));
+                        }
+                        while (virt_ranges.size() - mark < (size_t)nW) virt_ranges.push_back(make_int2(N, 0));
+                    }
                 }
             }
             std::vector<int2> mine((size_t)nblk, make_int2(N, 0));
