@@ -800,9 +800,8 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
             // common windows of block pairs, whose unions per unit are the same
             d.r2 = spdnn::Row2Weights{reinterpret_cast<const uint4*>(d.r2_codes), win_dev[l], gather_map, seg_log2, seg_stride};
             const int groups = N / spdnn::kGroup32;
-            spdnn::row2_pack_kernel<<<(groups + spdnn::kRow2PackThreads - 1) / spdnn::kRow2PackThreads,
-                                      spdnn::kRow2PackThreads, 0, stream>>>(di, N, win_dev[l], gather_rank, seg_log2, seg_stride,
-                                                                            d.r2_codes);
+            spdnn::row2_pack_kernel<<<groups, spdnn::kRow2PackThreads, 0, stream>>>(di, N, win_dev[l], gather_rank, seg_log2,
+                                                                                    seg_stride, d.r2_codes);
             HIP_TRY(hipGetLastError());
             d.mode = kRow2;
             d.lds_cols = spdnn::kRow2Cols;

@@ -427,20 +427,42 @@ __global__ __launch_bounds__(kBlk) void row2_footprint_kernel(const int32_t* __r
     if (tid == 0) out[blockIdx.y * gridDim.x + u] = total;
 }
 
-// a0 for fused_row2_kernel: one thread per group of 32 neighbouring neurons of one neuron slot
+// a0 for fused_row2_kernel: one wave per group of 32 neighbouring neurons of one neuron slot
 // (the lanes a ds_read_b64 serves together).  Orders the group's connections so that in every
-// step the 32 lanes read 32 different bank pairs whenever possible (order_group32) and writes the
-// steps as 16-bit tile positions, eight per 16-byte word, lane-major.
-// The search diverges from group to group, so the groups do not share a wave: one thread per workgroup,
-// and the layer's N / 32 groups spread over all CUs.
-constexpr int kRow2PackThreads = 1;
+// step the 32 lanes read 32 different bank pairs whenever possible and writes the steps as 16-bit
+// tile positions, eight per 16-byte word, lane-major.
+//
+// The ordering is order_group32's (spdnn_order.h), choice for choice, with the wave's first 32 lanes
+// in two roles: lane l as the group's l-th neuron (its unplaced connections, its pair of the current
+// step, its parent in the search) and lane q as bank pair q (the lanes that still have a connection
+// there, how many connections, the lane it is matched with).  What the serial routine loops over --
+// the 32 pairs for the most urgent one, the lanes a pair reaches, the pairs a lane may share -- is a
+// wave reduction or a bit mask here; the breadth-first search itself stays serial, one pair per turn.
+// One thread per group took 14 ms per 16384-neuron layer; this takes well under one.
+constexpr int kRow2PackThreads = 64;
+struct Pack32Scratch {
+    uint32_t conn[32][32];  // [q][l]: connections (bit k) of lane l that fall in pair q
+    uint32_t adj[32];       // lanes that still have a connection in pair q
+    uint32_t remq[32];      // connections not placed yet in pair q, whole group
+    uint32_t queue[36];
+};
+__device__ __forceinline__ int wave32_max(int v) {  // over lanes 0..31 (and, separately, 32..63)
+#pragma unroll
+    for (int d = 1; d < 32; d <<= 1) v = max(v, __shfl_xor(v, d, 32));
+    return v;
+}
+__device__ __forceinline__ int wave32_min(int v) {
+#pragma unroll
+    for (int d = 1; d < 32; d <<= 1) v = min(v, __shfl_xor(v, d, 32));
+    return v;
+}
 __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32_t* __restrict__ idx, int N,
                                                                      const int2* __restrict__ win,
                                                                      const uint16_t* __restrict__ rank,  // NULL: contiguous windows
                                                                      int seg_log2, int seg_stride,
                                                                      uint16_t* __restrict__ codes) {
-    __shared__ Order32Scratch scratch[kRow2PackThreads];
-    const int g = blockIdx.x * kRow2PackThreads + threadIdx.x;  // group: unit, slot, 32 lanes
+    __shared__ Pack32Scratch S;
+    const int g = blockIdx.x;  // group: unit, slot, 32 lanes
     const int groups_per_unit = kUnit4 / kGroup32;
     const int u = g / groups_per_unit;
     if (u * kUnit4 >= N) return;
@@ -448,19 +470,112 @@ __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32
     const int s = in_unit / (kBlk / kGroup32);
     const int lane0 = (in_unit - s * (kBlk / kGroup32)) * kGroup32;
     const int c_lo = rank ? 0 : row2_window(win, u, N).x;
-    auto pos_of = [&](int l, int k) -> uint32_t {  // out-of-range columns were reported; keep them harmless
-        int c = idx[(size_t)unit_neuron(u, s * kBlk + lane0 + l, seg_log2, seg_stride) * kNnz + k];
+    const int lane = threadIdx.x;
+    const bool on = lane < 32;       // the upper half of the wave only keeps the reductions company
+    const int l = lane & 31;
+    const int32_t* mine = idx + (size_t)unit_neuron(u, s * kBlk + lane0 + l, seg_log2, seg_stride) * kNnz;
+    auto pos_of = [&](int k) -> uint32_t {  // out-of-range columns were reported; keep them harmless
+        int c = mine[k];
         if (c < 0 || c >= N) c = c_lo;
         // tile column: inside the window, or in the gathered list group rank[c >> 2], column c & 3 of it
         const uint32_t tc = rank ? 4u * rank[(size_t)u * (N / 4) + (c >> 2)] + (uint32_t)(c & 3) : (uint32_t)win_rel(c, c_lo, N);
         return row2_pos(tc & (kRow2Cols - 1));
     };
-    order_group32(
-        scratch[threadIdx.x], [&](int l, int k) -> unsigned { return pos_of(l, k) & 31u; },
-        [&](int l, int step, int k) {
+    for (int q = 0; q < 32; ++q)
+        if (on) S.conn[q][l] = 0;
+    if (on) {
+        S.adj[l] = 0;
+        S.remq[l] = 0;
+    }
+    __syncthreads();
+    if (on)
+        for (int k = 0; k < 32; ++k) {
+            const int q = (int)(pos_of(k) & 31u);
+            S.conn[q][l] |= 1u << k;  // my own column of the table
+        }
+    __syncthreads();
+    if (on)
+        for (int q = 0; q < 32; ++q) {
+            const uint32_t m = S.conn[q][l];
+            if (m) {
+                atomicOr(&S.adj[q], 1u << l);
+                atomicAdd(&S.remq[q], (uint32_t)__popc(m));
+            }
+        }
+    __syncthreads();
+    uint32_t unplaced = 0xFFFFFFFFu;  // lane l's connections not placed yet
+    for (int step = 0; step < 32; ++step) {
+        const int left = 32 - step;
+        const uint32_t adj = on ? S.adj[l] : 0u;  // as pair q = l
+        const int remq = on ? (int)S.remq[l] : 0;
+        int lane_of_pair = -1;  // as pair
+        int pair_of_lane = -1;  // as lane
+        int parent = -1;        // as lane: the pair from which the search reached me
+        uint32_t free_lanes = 0xFFFFFFFFu;  // lanes without a pair (the same in every lane)
+        uint32_t done = 0;                  // pairs already offered
+        for (int r = 0; r < 32; ++r) {
+            // the most urgent pair not offered yet, the lowest-numbered one among equals
+            const int key = (!on || ((done >> l) & 1u)) ? -1 : ((((remq >= left) ? 4096 : 0) + remq) << 5) | (31 - l);
+            const int best = __builtin_amdgcn_readfirstlane(wave32_max(key));
+            const int q0 = 31 - (best & 31);
+            done |= 1u << q0;
+            if (((best >> 5) & 4095) == 0) break;  // the rest are empty too
+            // breadth-first search for an augmenting path from pair q0 to a lane without a pair
+            int head = 0, tail = 1, found = -1;
+            uint32_t seen = 0;
+            if (lane == 0) S.queue[0] = (uint32_t)q0;
+            __syncthreads();
+            while (head < tail && found < 0) {
+                const int q = __builtin_amdgcn_readfirstlane((int)S.queue[head]);
+                ++head;
+                const uint32_t cand = (uint32_t)__builtin_amdgcn_readlane((int)adj, q) & ~seen;
+                const uint32_t hit = cand & free_lanes;
+                if (hit) {
+                    found = __builtin_ctz(hit);
+                    if (lane == found) parent = q;
+                } else if (cand) {
+                    seen |= cand;
+                    if (on && ((cand >> l) & 1u)) {
+                        parent = q;
+                        S.queue[tail + __popc(cand & ((1u << l) - 1u))] = (uint32_t)pair_of_lane;  // a lane is seen once: at most 32 entries follow q0
+                    }
+                    tail += __popc(cand);
+                    __syncthreads();
+                }
+            }
+            if (found < 0) continue;
+            free_lanes &= ~(1u << found);
+            for (int cur = found;;) {
+                const int q = __builtin_amdgcn_readlane(parent, cur);
+                const int next = __builtin_amdgcn_readlane(lane_of_pair, q);  // the lane that gives q up (meaningful unless q == q0)
+                if (lane == q) lane_of_pair = cur;
+                if (lane == cur) pair_of_lane = q;
+                if (q == q0) break;
+                cur = next;
+            }
+        }
+        // a lane left without a pair of its own shares the least used pair it can, lanes in ascending order
+        int mult = (on && lane_of_pair >= 0) ? 1 : 0;  // as pair: lanes using me in this step
+        for (uint32_t rest = free_lanes; rest;) {
+            const int ll = __builtin_ctz(rest);
+            rest &= rest - 1;
+            const int key = (on && ((adj >> ll) & 1u)) ? ((mult * 65536 - remq + 2048) << 5) | l : 0x7fffffff;
+            const int bq = __builtin_amdgcn_readfirstlane(wave32_min(key)) & 31;
+            if (lane == ll) pair_of_lane = bq;
+            if (lane == bq) ++mult;
+        }
+        // place: the lowest unplaced connection of my pair
+        if (on) {
+            const uint32_t in_pair = S.conn[pair_of_lane][l];
+            const int k = __builtin_ctz(in_pair & unplaced);
+            unplaced &= ~(1u << k);
+            atomicSub(&S.remq[pair_of_lane], 1u);
+            if ((in_pair & unplaced) == 0) atomicAnd(&S.adj[pair_of_lane], ~(1u << l));
             const size_t word = ((size_t)(u * 4 + s) * 4 + (step >> 3)) * kBlk + lane0 + l;
-            codes[word * 8 + (step & 7)] = (uint16_t)pos_of(l, k);
-        });
+            codes[word * 8 + (step & 7)] = (uint16_t)pos_of(k);
+        }
+        __syncthreads();
+    }
 }
 
 // ---------------------------------------------------------------------------
