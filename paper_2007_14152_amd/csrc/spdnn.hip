@@ -222,17 +222,14 @@ hipError_t allow_big_lds() {
 }
 
 
-// The fused kernels and two set-up kernels use more dynamic LDS than the default limit allows.
+// The fused kernels and set-up kernels use more dynamic LDS than the default limit allows.
 int allow_large_lds() {
-    constexpr size_t order_lds = spdnn::kOrderPackThreads * sizeof(spdnn::OrderScratch);
     constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
     const int tile_lds = (int)spdnn::tile_pair_bytes(spdnn::kCap);
     HIP_TRY((allow_big_lds<false, false>()));
     HIP_TRY((allow_big_lds<true, false>()));
     HIP_TRY((allow_big_lds<false, true>()));
     HIP_TRY((allow_big_lds<true, true>()));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::order_pack_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::wide_pack_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)wide_lds));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&spdnn::balance_kernel<1>),
@@ -396,7 +393,6 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         void* unused = nullptr;
         if (static_scratch(&unused) != SPDNN_OK) return SPDNN_EHIP;
     }
-    constexpr size_t order_lds = spdnn::kOrderPackThreads * sizeof(spdnn::OrderScratch);
     constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 2),  // [L + 1]: see infer_impl
                           hipHostMallocDefault));
@@ -818,7 +814,7 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
         else
             spdnn::balance_kernel<1><<<nblk, spdnn::kBalanceThreads, sizeof(spdnn::BalanceScratch<1>), stream>>>(
                 di, N, win_dev[l], widest_dev, slot_tab, const_cast<uint32_t*>(d.w.qsel), nrows);
-        spdnn::order_pack_kernel<<<nblk * (spdnn::kOrderThreads / spdnn::kOrderPackThreads), spdnn::kOrderPackThreads, order_lds, stream>>>(
+        spdnn::order_pack_kernel<<<nblk * spdnn::kOrderThreads, spdnn::kOrderPackThreads, 0, stream>>>(
             di, dv, N, win_dev[l], widest_dev, slot_tab, pair, const_cast<uint16_t*>(d.w.rel),
             const_cast<float*>(d.w.val), nrows, lens, lens ? const_cast<uint8_t*>(d.virt.nb8) : nullptr);
         HIP_TRY(hipGetLastError());

@@ -381,6 +381,22 @@ __device__ __forceinline__ void fma_block8ps(float (&acc)[4], uint32_t p0, uint3
         : "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "memory");
 }
 
+// Maximum / minimum over each row of 16 lanes, left in all 16 of them: four DPP rotations inside the row.
+__device__ __forceinline__ int row16_max(int v) {
+    v = max(v, __builtin_amdgcn_mov_dpp(v, 0x128, 0xF, 0xF, true));  // row_ror:8
+    v = max(v, __builtin_amdgcn_mov_dpp(v, 0x124, 0xF, 0xF, true));  // row_ror:4
+    v = max(v, __builtin_amdgcn_mov_dpp(v, 0x122, 0xF, 0xF, true));  // row_ror:2
+    v = max(v, __builtin_amdgcn_mov_dpp(v, 0x121, 0xF, 0xF, true));  // row_ror:1
+    return v;
+}
+__device__ __forceinline__ int row16_min(int v) {
+    v = min(v, __builtin_amdgcn_mov_dpp(v, 0x128, 0xF, 0xF, true));
+    v = min(v, __builtin_amdgcn_mov_dpp(v, 0x124, 0xF, 0xF, true));
+    v = min(v, __builtin_amdgcn_mov_dpp(v, 0x122, 0xF, 0xF, true));
+    v = min(v, __builtin_amdgcn_mov_dpp(v, 0x121, 0xF, 0xF, true));
+    return v;
+}
+
 // Number of set bytes among flags[0 .. n), counted by the whole workgroup.  red: 17 ints of LDS.
 // Four 16-byte loads per thread are in flight at a time (the count sits on every workgroup's way in).
 __device__ __forceinline__ int count_flags(const uint8_t* __restrict__ flags, int n, int* red) {
@@ -2180,7 +2196,7 @@ struct BalanceScratch {
     uint32_t cursor[kCap];                 // connections per column, then fill position
     uint32_t ofs[kCap + 4];                // start of column c's entries in ent[]
     uint8_t ent[UB * kNnz * kBlk];         // lane set (0..64*UB-1) of every connection, grouped by column
-    uint16_t load[UB * kBlk / kGroup][16];  // connections lane set S already has in quad q
+    uint32_t load[UB * kBlk / kGroup][16];  // connections lane set S already has in quad q
     uint16_t cost[16][16];
 };
 constexpr int kBalanceThreads = 64;
@@ -2191,7 +2207,7 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
                                                                   uint16_t* __restrict__ slot_tab,
                                                                   uint32_t* __restrict__ qsel,
                                                                   int nrows = -1) {  // rows of idx, if not N
-    extern __shared__ char balance_scratch[];
+    extern __shared__ __align__(16) char balance_scratch[];
     BalanceScratch<UB>& B = *reinterpret_cast<BalanceScratch<UB>*>(balance_scratch);
     if (*widest > kCap) return;
     const int b = blockIdx.x * UB;
@@ -2241,42 +2257,62 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
     }
     __syncthreads();
 
-    const int row = lane >> 2;  // cost phase: lane computes quads 4*part .. 4*part+3 of column `row`
-    const int part = lane & 3;
+    // Cost phase: lanes 4 i .. 4 i + 3 share column i of the group, each takes every fourth of its connections
+    // and adds up, for all 16 quads, what the connections' lane sets already hold there.
+    const int row = lane >> 2;
+    const int sub = lane & 3;
     uint32_t packed = 0;  // lanes 0..15: quads (times 16) chosen so far for the staging lane's columns
     for (int g = 0; g < kCap / 16; ++g) {
         const int a = g & 3, set = (g >> 2) & 3, wave = g >> 4;
         auto column_of = [&](int i) { return 4 * (wave * 64 + lane_of_group(set, i)) + a; };
+        const int c_row = column_of(row);
+        const uint32_t e0 = B.ofs[c_row], e1 = B.ofs[c_row + 1];
         {
-            const int c = column_of(row);
-            uint32_t acc[4] = {0, 0, 0, 0};
-            for (uint32_t e = B.ofs[c]; e < B.ofs[c + 1]; ++e) {
-                const uint16_t* ld = &B.load[B.ent[e]][4 * part];
-                acc[0] += ld[0];
-                acc[1] += ld[1];
-                acc[2] += ld[2];
-                acc[3] += ld[3];
+            uint32_t acc[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[q] = 0;
+            for (uint32_t e = e0 + sub; e < e1; e += 4) {
+                const uint4* ld = reinterpret_cast<const uint4*>(&B.load[B.ent[e]][0]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const uint4 x = ld[v];
+                    acc[4 * v + 0] += x.x;
+                    acc[4 * v + 1] += x.y;
+                    acc[4 * v + 2] += x.z;
+                    acc[4 * v + 3] += x.w;
+                }
             }
-            for (int i = 0; i < 4; ++i) B.cost[row][4 * part + i] = (uint16_t)min(acc[i], 4095u);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                acc[q] += (uint32_t)__builtin_amdgcn_mov_dpp((int)acc[q], 0xB1, 0xF, 0xF, true);  // lanes ^ 1
+                acc[q] += (uint32_t)__builtin_amdgcn_mov_dpp((int)acc[q], 0x4E, 0xF, 0xF, true);  // lanes ^ 2
+            }
+            if (sub == 0) {
+                uint32_t* out = reinterpret_cast<uint32_t*>(&B.cost[row][0]);
+#pragma unroll
+                for (int q = 0; q < 16; q += 2) out[q >> 1] = min(acc[q], 4095u) | (min(acc[q + 1], 4095u) << 16);
+            }
         }
         __syncthreads();
-        // lanes 0..15 in two roles: as column i = lane (count, chosen quad) and as quad q = lane
+        // every 16 lanes in two roles: as column i = lane & 15 (count, chosen quad) and as quad q = lane & 15
         const int c_mine = column_of(lane & 15);
         const int cnt = (int)B.ofs[c_mine + 1] - (int)B.ofs[c_mine];
         int chosen = -1;
         bool quad_free = true;
         for (int it = 0; it < 16; ++it) {
-            int key = chosen < 0 ? ((cnt << 4) | (15 - (lane & 15))) : -1;  // busiest unplaced column, lowest index first
-            for (int d = 1; d < 16; d <<= 1) key = max(key, __shfl_xor(key, d, 16));
-            const int i = 15 - (key & 15);
-            int k2 = quad_free ? (((int)B.cost[i][lane & 15] << 4) | (lane & 15)) : 0x7fffffff;
-            for (int d = 1; d < 16; d <<= 1) k2 = min(k2, __shfl_xor(k2, d, 16));
-            const int q = k2 & 15;
+            const int key = chosen < 0 ? ((cnt << 4) | (15 - (lane & 15))) : -1;  // busiest unplaced column, lowest index first
+            const int i = 15 - (row16_max(key) & 15);
+            const int k2 = quad_free ? (((int)B.cost[i][lane & 15] << 4) | (lane & 15)) : 0x7fffffff;
+            const int q = row16_min(k2) & 15;
             if ((lane & 15) == i) chosen = q;
             if ((lane & 15) == q) quad_free = false;
         }
+        // the chosen quads take the columns' connections on board (all 64 lanes: column `row`, every fourth entry)
+        {
+            const int ch = __shfl(chosen, row);
+            for (uint32_t e = e0 + sub; e < e1; e += 4) atomicAdd(&B.load[B.ent[e]][ch], 1u);
+        }
         if (lane < 16) {
-            for (uint32_t e = B.ofs[c_mine]; e < B.ofs[c_mine + 1]; ++e) B.load[B.ent[e]][chosen]++;
             slot_tab[(size_t)b * kCap + c_mine] = (uint16_t)((g << 4) | chosen);
             packed |= (uint32_t)(chosen << 4) << (8 * a);
             if (a == 3) {
@@ -2288,16 +2324,26 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
     }
 }
 
-// One thread per set of 16 neurons whose lanes are served together (64 threads =
-// one output block of 16 waves x 4 sets): orders the set's connections for
-// conflict-free LDS reads (spdnn_order.h) and writes them lane-major: entry
+// One wave per set of 16 neurons whose lanes are served together: orders the set's
+// connections for conflict-free LDS reads and writes them lane-major: entry
 // (block b, step s, lane t) holds the LDS slot of the connection's column (plus
 // the stage number in bits 12 and up) and its weight, for the connection lane t
 // uses at step s.
+//
+// The ordering is order_group's (spdnn_order.h), choice for choice, with the wave's first 16 lanes in
+// two roles: lane l as the set's l-th neuron (its unplaced connections, its quad of the current step,
+// its parent in the search) and lane q as bank quad q (the lanes that still have a connection there,
+// how many connections, how many lanes use it in this step).  What the serial routine loops over is a
+// 16-lane reduction or a bit mask here; the breadth-first search stays serial, one quad per turn.
+// A thread per set took 3.1 ms per 65536-neuron layer.
 constexpr int kOrderThreads = kBlk / kGroup;  // lane sets per output block
-// The search diverges from set to set, so few of them share a wave: kOrderPackThreads threads per workgroup,
-// kOrderThreads / kOrderPackThreads workgroups per output block.
-constexpr int kOrderPackThreads = 4;
+constexpr int kOrderPackThreads = 64;
+struct Pack16Scratch {
+    uint32_t conn[16][16];  // [q][l]: connections (bit k) of lane l that fall in quad q
+    uint32_t adj[16];       // lanes that still have a connection in quad q
+    uint32_t remq[16];      // connections not placed yet in quad q, whole set
+    uint32_t queue[20];
+};
 __global__ __launch_bounds__(kOrderPackThreads) void order_pack_kernel(const int32_t* __restrict__ idx,
                                                                    const float* __restrict__ val, int N,
                                                                    const int2* __restrict__ win,
@@ -2313,64 +2359,151 @@ __global__ __launch_bounds__(kOrderPackThreads) void order_pack_kernel(const int
                                                                    // nb8[block][wave] = blocks of 8 steps the wave then runs
                                                                    int nrows = -1, const uint8_t* __restrict__ len = nullptr,
                                                                    uint8_t* __restrict__ nb8 = nullptr) {
-    extern __shared__ OrderScratch order_scratch[];
-    __shared__ int wave_steps;
-    const int gset = blockIdx.x * kOrderPackThreads + threadIdx.x;  // lane set, counted over the whole layer
+    __shared__ Pack16Scratch S;
+    const int gset = blockIdx.x;  // lane set, counted over the whole layer
     const int b = gset / kOrderThreads;
     const int t = gset - b * kOrderThreads;
-    const int wave0 = (t >> 2) * 64;  // first lane of this thread's wave inside the block
+    const int wave0 = (t >> 2) * 64;  // first lane of this set's wave inside the block
     const int set = t & 3;
     const int c_lo = win[b].x;
     const int rows = nrows < 0 ? N : nrows;
-    auto neuron = [&](int l) -> int { return b * kBlk + wave0 + lane_of_group(set, l); };
-    auto column = [&](int l, int k) -> int {  // out-of-range columns were reported; keep them harmless
-        const int c = idx[(size_t)neuron(l) * kNnz + k];
-        return (c < 0 || c >= N) ? c_lo : c;
-    };
+    const int lane = threadIdx.x;
+    const bool on = lane < kGroup;  // the other lanes only keep the reductions company (and help with nb8)
+    const int l = lane & 15;
+    const int my_lane = wave0 + lane_of_group(set, l);  // my neuron's lane inside the block
+    const int j = b * kBlk + my_lane;                   // my neuron
+    const bool exists = j < rows;
     // LDS slot of stage-local column r: from balance_kernel for single-stage layers
     const bool balanced = *widest <= kCap;
     const uint16_t* tab = slot_tab + (size_t)(pair ? (b & ~1) : b) * kCap;
     auto slot_of = [&](uint32_t r) -> uint32_t { return balanced ? tab[r] : col_slot(r); };
+    auto entry = [&](int step) -> size_t { return ((size_t)b * kNnz + step) * kBlk + my_lane; };
     int nsteps = kNnz;
+    const int my_len = !exists ? 0 : len ? (int)len[j] : kNnz;
     if (len) {  // steps this set needs; everything else is weight 0 on the window's first column
-        int longest = 0;
-        for (int l = 0; l < kGroup; ++l) longest = max(longest, (int)len[neuron(l)]);
-        nsteps = (longest + 7) & ~7;
-        for (int l = 0; l < kGroup; ++l)
-            for (int step = 0; step < kNnz; ++step) {
-                const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
-                rel[e] = (uint16_t)slot_of(0);
-                wval[e] = 0.0f;
-            }
-        // the four threads of a workgroup are the four sets of one wave (kOrderPackThreads == 4)
-        if (threadIdx.x == 0) wave_steps = 0;
-        __syncthreads();
-        atomicMax(&wave_steps, nsteps);
-        __syncthreads();
-        if (threadIdx.x == 0 && nb8) nb8[b * 16 + (t >> 2)] = (uint8_t)(wave_steps / 8);
+        nsteps = (__builtin_amdgcn_readfirstlane(row16_max(on ? my_len : 0)) + 7) & ~7;
+        const int jw = b * kBlk + wave0 + lane;  // lane `lane` of the wave this set belongs to
+        int longest = jw < rows ? (int)len[jw] : 0;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) longest = max(longest, __shfl_xor(longest, d, 64));
+        if (set == 0 && lane == 0 && nb8) nb8[b * 16 + (t >> 2)] = (uint8_t)(((longest + 7) & ~7) / 8);
     }
-    order_group(
-        order_scratch[threadIdx.x], nsteps,
-        [&](int l, int k) -> unsigned {
-            if (neuron(l) >= rows || (len && k >= (int)len[neuron(l)])) return 255u;
-            return slot_of((uint32_t)win_rel(column(l, k), c_lo, N) & (kCap - 1)) & 15u;
-        },
-        [&](int l, int step, int k) {
-            const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
-            const size_t src = (size_t)neuron(l) * kNnz + k;
+    if (on && (len || !exists)) {  // lanes past the last neuron, and the steps a short lane leaves empty
+        const uint16_t zero_slot = (uint16_t)slot_of(0);
+        for (int step = 0; step < kNnz; ++step) {
+            rel[entry(step)] = zero_slot;
+            wval[entry(step)] = 0.0f;
+        }
+    }
+    auto column = [&](int k) -> int {  // out-of-range columns were reported; keep them harmless
+        const int c = idx[(size_t)j * kNnz + k];
+        return (c < 0 || c >= N) ? c_lo : c;
+    };
+    for (int q = 0; q < 16; ++q)
+        if (on) S.conn[q][l] = 0;
+    if (on) {
+        S.adj[l] = 0;
+        S.remq[l] = 0;
+    }
+    __syncthreads();
+    uint32_t unplaced = 0;  // my connections not placed yet (bit k)
+    if (on)
+        for (int k = 0; k < my_len; ++k) {
+            const int q = (int)(slot_of((uint32_t)win_rel(column(k), c_lo, N) & (kCap - 1)) & 15u);
+            S.conn[q][l] |= 1u << k;  // my own column of the table
+            unplaced |= 1u << k;
+        }
+    __syncthreads();
+    if (on)
+        for (int q = 0; q < 16; ++q) {
+            const uint32_t m = S.conn[q][l];
+            if (m) {
+                atomicOr(&S.adj[q], 1u << l);
+                atomicAdd(&S.remq[q], (uint32_t)__popc(m));
+            }
+        }
+    __syncthreads();
+    for (int step = 0; step < nsteps; ++step) {
+        const int left = nsteps - step;
+        const uint32_t adj = on ? S.adj[l] : 0u;  // as quad q = l
+        const int remq = on ? (int)S.remq[l] : 0;
+        int lane_of_quad = -1;  // as quad
+        int quad_of_lane = -1;  // as lane
+        int parent = -1;        // as lane: the quad from which the search reached me
+        uint32_t free_lanes = 0xFFFFu;  // lanes without a quad (the same in every lane)
+        uint32_t done = 0;              // quads already offered
+        for (int r = 0; r < 16; ++r) {
+            // the most urgent quad not offered yet, the lowest-numbered one among equals
+            const int key = (!on || ((done >> l) & 1u)) ? -1 : ((((remq >= left) ? 4096 : 0) + remq) << 4) | (15 - l);
+            const int best = __builtin_amdgcn_readfirstlane(row16_max(key));
+            const int q0 = 15 - (best & 15);
+            done |= 1u << q0;
+            if (((best >> 4) & 4095) == 0) break;  // the rest are empty too
+            // breadth-first search for an augmenting path from q0 to a free lane
+            int head = 0, tail = 1, found = -1;
+            uint32_t seen = 0;
+            if (lane == 0) S.queue[0] = (uint32_t)q0;
+            __syncthreads();
+            while (head < tail && found < 0) {
+                const int q = __builtin_amdgcn_readfirstlane((int)S.queue[head]);
+                ++head;
+                const uint32_t cand = (uint32_t)__builtin_amdgcn_readlane((int)adj, q) & ~seen;
+                const uint32_t hit = cand & free_lanes;
+                if (hit) {
+                    found = __builtin_ctz(hit);
+                    if (lane == found) parent = q;
+                } else if (cand) {
+                    seen |= cand;
+                    if (on && ((cand >> l) & 1u)) {
+                        parent = q;
+                        S.queue[tail + __popc(cand & ((1u << l) - 1u))] = (uint32_t)quad_of_lane;  // a lane is seen once: at most 16 entries follow q0
+                    }
+                    tail += __popc(cand);
+                    __syncthreads();
+                }
+            }
+            if (found < 0) continue;
+            free_lanes &= ~(1u << found);
+            for (int cur = found;;) {
+                const int q = __builtin_amdgcn_readlane(parent, cur);
+                const int next = __builtin_amdgcn_readlane(lane_of_quad, q);  // meaningful only if q was matched
+                if (lane == q) lane_of_quad = cur;
+                if (lane == cur) quad_of_lane = q;
+                if (q == q0) break;
+                cur = next;
+            }
+        }
+        // lanes without a quad of their own share the least loaded one they can use, in ascending order; a lane
+        // with fewer connections left than steps sits this step out
+        int mult = (on && lane_of_quad >= 0) ? 1 : 0;  // as quad: uses in this step (saturates at 15)
+        const int reml = __popc(unplaced);
+        for (uint32_t rest = free_lanes; rest;) {
+            const int ll = __builtin_ctz(rest);
+            rest &= rest - 1;
+            const int r_ll = __builtin_amdgcn_readlane(reml, ll);
+            if (r_ll == 0 || r_ll < left) continue;
+            const uint32_t u_ll = (uint32_t)__builtin_amdgcn_readlane((int)unplaced, ll);
+            const int cnt = on ? __popc(S.conn[l][ll] & u_ll) : 0;  // lane ll's unplaced connections in quad l
+            const int key = cnt ? ((mult * 65536 - (remq - left) * 64 - cnt + 65536) << 4) | l : 0x7fffffff;
+            const int bq = __builtin_amdgcn_readfirstlane(row16_min(key)) & 15;
+            if (lane == ll) quad_of_lane = bq;
+            if (lane == bq) mult = min(mult + 1, 15);
+        }
+        // place the chosen connections: the lowest unplaced one of the lane's quad
+        if (on && quad_of_lane >= 0) {
+            const uint32_t in_quad = S.conn[quad_of_lane][l];
+            const int k = __builtin_ctz(in_quad & unplaced);
+            unplaced &= ~(1u << k);
+            atomicSub(&S.remq[quad_of_lane], 1u);
+            if ((in_quad & unplaced) == 0) atomicAnd(&S.adj[quad_of_lane], ~(1u << l));
+            const size_t src = (size_t)j * kNnz + k;
             const int c = idx[src];
             const bool ok = c >= 0 && c < N;
             const uint32_t r = ok ? (uint32_t)win_rel(c, c_lo, N) : 0u;  // stage number | slot inside the stage
-            rel[e] = (uint16_t)((r & ~(uint32_t)(kCap - 1)) | slot_of(r & (kCap - 1)));
-            wval[e] = ok ? val[src] : 0.0f;
-        });
-    for (int l = 0; l < kGroup; ++l) {
-        if (neuron(l) < rows) continue;
-        for (int step = 0; step < kNnz; ++step) {  // lanes past the last neuron: weight 0 on column c_lo
-            const size_t e = ((size_t)b * kNnz + step) * kBlk + wave0 + lane_of_group(set, l);
-            rel[e] = (uint16_t)slot_of(0);
-            wval[e] = 0.0f;
+            rel[entry(step)] = (uint16_t)((r & ~(uint32_t)(kCap - 1)) | slot_of(r & (kCap - 1)));
+            wval[entry(step)] = ok ? val[src] : 0.0f;
         }
+        __syncthreads();
     }
 }
 

@@ -446,15 +446,14 @@ struct Pack32Scratch {
     uint32_t remq[32];      // connections not placed yet in pair q, whole group
     uint32_t queue[36];
 };
-__device__ __forceinline__ int wave32_max(int v) {  // over lanes 0..31 (and, separately, 32..63)
-#pragma unroll
-    for (int d = 1; d < 32; d <<= 1) v = max(v, __shfl_xor(v, d, 32));
-    return v;
+// over lanes 0..31: the two rows of 16, then one value from each
+__device__ __forceinline__ int wave32_max(int v) {
+    v = row16_max(v);
+    return max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16));
 }
 __device__ __forceinline__ int wave32_min(int v) {
-#pragma unroll
-    for (int d = 1; d < 32; d <<= 1) v = min(v, __shfl_xor(v, d, 32));
-    return v;
+    v = row16_min(v);
+    return min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16));
 }
 __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32_t* __restrict__ idx, int N,
                                                                      const int2* __restrict__ win,
@@ -516,7 +515,7 @@ __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32
         for (int r = 0; r < 32; ++r) {
             // the most urgent pair not offered yet, the lowest-numbered one among equals
             const int key = (!on || ((done >> l) & 1u)) ? -1 : ((((remq >= left) ? 4096 : 0) + remq) << 5) | (31 - l);
-            const int best = __builtin_amdgcn_readfirstlane(wave32_max(key));
+            const int best = wave32_max(key);
             const int q0 = 31 - (best & 31);
             done |= 1u << q0;
             if (((best >> 5) & 4095) == 0) break;  // the rest are empty too
@@ -560,7 +559,7 @@ __global__ __launch_bounds__(kRow2PackThreads) void row2_pack_kernel(const int32
             const int ll = __builtin_ctz(rest);
             rest &= rest - 1;
             const int key = (on && ((adj >> ll) & 1u)) ? ((mult * 65536 - remq + 2048) << 5) | l : 0x7fffffff;
-            const int bq = __builtin_amdgcn_readfirstlane(wave32_min(key)) & 31;
+            const int bq = wave32_min(key) & 31;
             if (lane == ll) pair_of_lane = bq;
             if (lane == bq) ++mult;
         }
