@@ -2267,6 +2267,20 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
         auto column_of = [&](int i) { return 4 * (wave * 64 + lane_of_group(set, i)) + a; };
         const int c_row = column_of(row);
         const uint32_t e0 = B.ofs[c_row], e1 = B.ofs[c_row + 1];
+        // The columns choose in the order of their connection counts, busiest first, lowest index among equals:
+        // known before any cost is.  rank = my column's place in that order (every 16 lanes: column lane & 15).
+        const int c_mine = column_of(lane & 15);
+        const int cnt = (int)B.ofs[c_mine + 1] - (int)B.ofs[c_mine];
+        int rank = 0;
+        {
+            const int key = (cnt << 4) | (15 - (lane & 15));
+#define SPDNN_RANK_STEP(n) rank += __builtin_amdgcn_mov_dpp(key, 0x120 + (n), 0xF, 0xF, true) > key ? 1 : 0;
+            SPDNN_RANK_STEP(1) SPDNN_RANK_STEP(2) SPDNN_RANK_STEP(3) SPDNN_RANK_STEP(4) SPDNN_RANK_STEP(5)
+            SPDNN_RANK_STEP(6) SPDNN_RANK_STEP(7) SPDNN_RANK_STEP(8) SPDNN_RANK_STEP(9) SPDNN_RANK_STEP(10)
+            SPDNN_RANK_STEP(11) SPDNN_RANK_STEP(12) SPDNN_RANK_STEP(13) SPDNN_RANK_STEP(14) SPDNN_RANK_STEP(15)
+#undef SPDNN_RANK_STEP
+        }
+        const int rank_row = __shfl(rank, row);  // of column `row`: its costs go to row rank_row of the table
         {
             uint32_t acc[16];
 #pragma unroll
@@ -2288,23 +2302,24 @@ __global__ __launch_bounds__(kBalanceThreads) void balance_kernel(const int32_t*
                 acc[q] += (uint32_t)__builtin_amdgcn_mov_dpp((int)acc[q], 0x4E, 0xF, 0xF, true);  // lanes ^ 2
             }
             if (sub == 0) {
-                uint32_t* out = reinterpret_cast<uint32_t*>(&B.cost[row][0]);
+                uint32_t* out = reinterpret_cast<uint32_t*>(&B.cost[rank_row][0]);
 #pragma unroll
                 for (int q = 0; q < 16; q += 2) out[q >> 1] = min(acc[q], 4095u) | (min(acc[q + 1], 4095u) << 16);
             }
         }
         __syncthreads();
-        // every 16 lanes in two roles: as column i = lane & 15 (count, chosen quad) and as quad q = lane & 15
-        const int c_mine = column_of(lane & 15);
-        const int cnt = (int)B.ofs[c_mine + 1] - (int)B.ofs[c_mine];
+        // every 16 lanes in two roles: as column i = lane & 15 (chosen quad) and as quad q = lane & 15; the costs
+        // of the 16 turns are fetched at once, the turns themselves are a reduction each
+        int cst[16];
+#pragma unroll
+        for (int it = 0; it < 16; ++it) cst[it] = (int)B.cost[it][lane & 15];
         int chosen = -1;
         bool quad_free = true;
-        for (int it = 0; it < 16; ++it) {
-            const int key = chosen < 0 ? ((cnt << 4) | (15 - (lane & 15))) : -1;  // busiest unplaced column, lowest index first
-            const int i = 15 - (row16_max(key) & 15);
-            const int k2 = quad_free ? (((int)B.cost[i][lane & 15] << 4) | (lane & 15)) : 0x7fffffff;
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {  // the column of rank `it` picks its cheapest free quad, the lowest among equals
+            const int k2 = quad_free ? ((cst[it] << 4) | (lane & 15)) : 0x7fffffff;
             const int q = row16_min(k2) & 15;
-            if ((lane & 15) == i) chosen = q;
+            if (rank == it) chosen = q;
             if ((lane & 15) == q) quad_free = false;
         }
         // the chosen quads take the columns' connections on board (all 64 lanes: column `row`, every fourth entry)
