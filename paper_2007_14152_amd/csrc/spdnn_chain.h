@@ -39,9 +39,6 @@ struct ChainArgs {
 // finish_rows for four rows that are not neighbours in the output buffer: row r goes to slot rows[r].
 __device__ __forceinline__ unsigned finish_rows_at(float (&a)[kRows], float bj, float* Yout, int N, int j, bool jok,
                                                    int4 rows, int nlive, int lane) {
-    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
-    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
-    const bool b0 = lane & 1, b1 = lane & 2;
     float y0 = fminf(fmaxf(a[0] + bj, 0.0f), kClip);
     float y1 = fminf(fmaxf(a[1] + bj, 0.0f), kClip);
     float y2 = fminf(fmaxf(a[2] + bj, 0.0f), kClip);
@@ -51,22 +48,7 @@ __device__ __forceinline__ unsigned finish_rows_at(float (&a)[kRows], float bj, 
                          (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
                          (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
                          (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
-    {
-        const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
-        const float r0 = xor2(s0), r1 = xor2(s1);
-        y0 = b1 ? r0 : y0;
-        y1 = b1 ? r1 : y1;
-        y2 = b1 ? y2 : r0;
-        y3 = b1 ? y3 : r1;
-    }
-    {
-        const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
-        const float r0 = xor1(s0), r1 = xor1(s1);
-        y0 = b0 ? r0 : y0;
-        y1 = b0 ? y1 : r0;
-        y2 = b0 ? r1 : y2;
-        y3 = b0 ? y3 : r1;
-    }
+    transpose_quartet(y0, y1, y2, y3);
     const int r = lane & 3;
     const int row = r == 0 ? rows.x : r == 1 ? rows.y : r == 2 ? rows.z : rows.w;
     if (jok && r < nlive) *reinterpret_cast<float4*>(Yout + (size_t)row * N + (j & ~3)) = make_float4(y0, y1, y2, y3);

@@ -630,16 +630,50 @@ __device__ __forceinline__ void stage_store(f32x4 (&st)[kRows], uint32_t addr, u
     *reinterpret_cast<lds_f4*>(addr + (qp >> 24) + 3 * 512) = f32x4{st[0].w, st[1].w, st[2].w, st[3].w};
 }
 
+// 4x4 transpose inside each lane quartet: lane 4q+i comes in with four values of its own (y0..y3 = rows 0..3 of
+// neuron 4q+i) and leaves with y_k = what lane 4q+k held in its y_i (row i of neurons 4q..4q+3).  Two exchanges,
+// with the neighbour two lanes away and then the one next door, each a select whose one operand comes in through
+// DPP: eight instructions.  (As selects and DPP moves written in C++ they were sixteen.)
+__device__ __forceinline__ void transpose_quartet(float& y0, float& y1, float& y2, float& y3) {
+    float n0, n1, n2, n3, m0, m1, m2, m3;
+    const uint64_t hi2 = 0xCCCCCCCCCCCCCCCCull;  // lanes with bit 1 set
+    const uint64_t hi1 = 0xAAAAAAAAAAAAAAAAull;  // lanes with bit 0 set
+    asm volatile(
+        "s_nop 1\n\t"  // the values may have been written by the instruction before; DPP reads need two wait states
+        "s_not_b64 vcc, %[hi2]\n\t"
+        "v_cndmask_b32_dpp %[n0], %[y2], %[y0], vcc quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_cndmask_b32_dpp %[n1], %[y3], %[y1], vcc quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_mov_b64 vcc, %[hi2]\n\t"
+        "v_cndmask_b32_dpp %[n2], %[y0], %[y2], vcc quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_cndmask_b32_dpp %[n3], %[y1], %[y3], vcc quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_not_b64 vcc, %[hi1]\n\t"
+        "v_cndmask_b32_dpp %[m0], %[n1], %[n0], vcc quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_cndmask_b32_dpp %[m2], %[n3], %[n2], vcc quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_mov_b64 vcc, %[hi1]\n\t"
+        "v_cndmask_b32_dpp %[m1], %[n0], %[n1], vcc quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_cndmask_b32_dpp %[m3], %[n2], %[n3], vcc quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        : [n0] "=&v"(n0), [n1] "=&v"(n1), [n2] "=&v"(n2), [n3] "=&v"(n3), [m0] "=&v"(m0), [m1] "=&v"(m1),
+          [m2] "=&v"(m2), [m3] "=&v"(m3)
+        : [y0] "v"(y0), [y1] "v"(y1), [y2] "v"(y2), [y3] "v"(y3), [hi2] "s"(hi2), [hi1] "s"(hi1)
+        : "vcc", "scc");
+    y0 = m0;
+    y1 = m1;
+    y2 = m2;
+    y3 = m3;
+}
+
 // Epilogue of one 4-row group of one neuron (Eq. 1: bias, ReLU, clip at 32): lane 4q+i
 // holds rows 0..3 of neuron 4q+i; a 4x4 transpose inside each lane quartet (two DPP
 // exchanges) leaves it with row i of neurons 4q..4q+3, which is one 16-byte store.
 // Clears the accumulators.  Returns bit r set if row r has a positive output anywhere in
 // the wave (lanes past the last neuron carry zero weights and zero bias, so their y is 0).
+// The output goes out with the non-temporal hint: a layer's output is read again only by the next layer, by when
+// (at the sizes that matter) it has long left the caches, and without the hint it pushes out the input tiles that
+// workgroups share.  Measured: 1.5 to 3 % per layer on outputs of 0.25 GB and more, nothing either way on small
+// ones (1.6 % lost on one of 0.13 GB).
 __device__ __forceinline__ unsigned finish_rows(float (&a)[kRows], float bj, float* __restrict__ Yout, int N, int j,
                                                 bool jok, int row0, int nlive, int lane) {
-    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
-    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
-    const bool b0 = lane & 1, b1 = lane & 2;
     float y0 = fminf(fmaxf(a[0] + bj, 0.0f), kClip);
     float y1 = fminf(fmaxf(a[1] + bj, 0.0f), kClip);
     float y2 = fminf(fmaxf(a[2] + bj, 0.0f), kClip);
@@ -649,25 +683,10 @@ __device__ __forceinline__ unsigned finish_rows(float (&a)[kRows], float bj, flo
                          (__builtin_amdgcn_ballot_w64(y1 > 0.0f) != 0ull ? 2u : 0u) |
                          (__builtin_amdgcn_ballot_w64(y2 > 0.0f) != 0ull ? 4u : 0u) |
                          (__builtin_amdgcn_ballot_w64(y3 > 0.0f) != 0ull ? 8u : 0u);
-    {
-        const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
-        const float r0 = xor2(s0), r1 = xor2(s1);
-        y0 = b1 ? r0 : y0;
-        y1 = b1 ? r1 : y1;
-        y2 = b1 ? y2 : r0;
-        y3 = b1 ? y3 : r1;
-    }
-    {
-        const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
-        const float r0 = xor1(s0), r1 = xor1(s1);
-        y0 = b0 ? r0 : y0;
-        y1 = b0 ? y1 : r0;
-        y2 = b0 ? r1 : y2;
-        y3 = b0 ? y3 : r1;
-    }
+    transpose_quartet(y0, y1, y2, y3);
     const int r = lane & 3;
     if (jok && r < nlive)
-        *reinterpret_cast<float4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)) = make_float4(y0, y1, y2, y3);
+        __builtin_nontemporal_store(f32x4{y0, y1, y2, y3}, reinterpret_cast<f32x4*>(Yout + (size_t)(row0 + r) * N + (j & ~3)));
     return pos;
 }
 

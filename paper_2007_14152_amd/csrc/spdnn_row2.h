@@ -146,30 +146,6 @@ __device__ __forceinline__ void fma_row2_block16(float (&acc)[kRows2], const uin
         : "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "memory");
 }
 
-// 4x4 transpose inside every quartet of lanes (two DPP exchanges): lane 4q+i ends up with
-// element i of lanes 4q .. 4q+3, in y0..y3.
-__device__ __forceinline__ void quartet_transpose(float& y0, float& y1, float& y2, float& y3, int lane) {
-    auto xor1 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true)); };
-    auto xor2 = [](float x) { return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true)); };
-    const bool b0 = lane & 1, b1 = lane & 2;
-    {
-        const float s0 = b1 ? y0 : y2, s1 = b1 ? y1 : y3;
-        const float r0 = xor2(s0), r1 = xor2(s1);
-        y0 = b1 ? r0 : y0;
-        y1 = b1 ? r1 : y1;
-        y2 = b1 ? y2 : r0;
-        y3 = b1 ? y3 : r1;
-    }
-    {
-        const float s0 = b0 ? y0 : y1, s1 = b0 ? y2 : y3;
-        const float r0 = xor1(s0), r1 = xor1(s1);
-        y0 = b0 ? r0 : y0;
-        y1 = b0 ? y1 : r0;
-        y2 = b0 ? r1 : y2;
-        y3 = b0 ? y3 : r1;
-    }
-}
-
 __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
     const float* __restrict__ Yin, float* __restrict__ Yout, uint8_t* __restrict__ flags,
     RowLists rl, Row2Weights w,
@@ -325,10 +301,10 @@ __global__ __launch_bounds__(kBlk) void fused_row2_kernel(
             float y2 = fminf(fmaxf(a1[0] + b1, 0.0f), kClip), y3 = fminf(fmaxf(a1[1] + b1, 0.0f), kClip);
             pos |= (__builtin_amdgcn_ballot_w64(y0 > 0.0f || y2 > 0.0f) != 0ull ? 1u : 0u) |
                    (__builtin_amdgcn_ballot_w64(y1 > 0.0f || y3 > 0.0f) != 0ull ? 2u : 0u);
-            quartet_transpose(y0, y1, y2, y3, lane);
+            transpose_quartet(y0, y1, y2, y3);
             if ((lane & 1) < nlive) {
                 const uint32_t nrn = (uint32_t)unit_neuron(u, (int)out_p + h * (2 * kBlk), w.seg_log2, w.seg_stride);
-                *reinterpret_cast<float4*>(out_row + (out_row_off + 4u * nrn)) = make_float4(y0, y1, y2, y3);
+                __builtin_nontemporal_store(f32x4{y0, y1, y2, y3}, reinterpret_cast<f32x4*>(out_row + (out_row_off + 4u * nrn)));  // see finish_rows
             }
         }
         if (lane < nlive && ((pos >> lane) & 1u)) flags[row0 + lane] = 1;  // lane r raises row r's flag
