@@ -226,7 +226,10 @@ def main():
         ptr, didx, dval = [g[0] for g in gen], [g[1] for g in gen], [g[2] for g in gen]
         nnz = [int(p[N]) for p in ptr]
         dbias = synth.gen_bias(N, c["bias"])
+        t_create = time.perf_counter()
         model = sp.Model.from_csr(ptr, didx, dval, dbias, device=dev)
+        torch.cuda.synchronize()
+        t_create = time.perf_counter() - t_create
     else:
         didx = torch.empty((L, N, 32), dtype=torch.int32, device=dev)
         for l in range(L):
@@ -238,8 +241,12 @@ def main():
                 didx[l] = synth.gen_layer_strided(N, strides[l % len(strides)], device=dev)
         dval = torch.full((L, N, 32), synth.WEIGHT, dtype=torch.float32, device=dev)
         dbias = synth.gen_bias(N, c["bias"], device=dev)
+        torch.cuda.synchronize()
+        t_create = time.perf_counter()
         model = sp.Model([didx[l] for l in range(L)], [dval[l] for l in range(L)], dbias, device=dev,
                          out_of_core=a.out_of_core)
+        torch.cuda.synchronize()
+        t_create = time.perf_counter() - t_create
     y0 = synth.gen_y0(batch, N, c["seed"], density=density, device=dev)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
@@ -299,7 +306,7 @@ def main():
             "kernels_of_launched_layers": kinds,
             "launches_per_inference": 1 if one_launch else layers_run,
             "n_active_final": int(n_active),
-            "setup_s": t_setup},
+            "setup_s": t_create, "generate_inputs_s": t_setup - t_create},
         # achieved = algorithmic bytes of all fused launches / their summed duration (HIP events on the
         # model's stream); full_launch_* = the launches on all `batch` rows alone
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
