@@ -18,6 +18,7 @@
 #include <vector>
 
 #include "spdnn_kernels.h"
+#include "spdnn_cut.h"
 
 // Work memory of spdnn_infer_static, the entry point for callers that cannot allocate: a fixed array in
 // every GPU's memory instead of a caller-made work arena.  In host code this name is only a stand-in for
@@ -546,81 +547,12 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
                 HIP_TRY(hipMemcpyAsync(hp.data(), ptr[ll], sizeof(int32_t) * hp.size(), hipMemcpyDeviceToHost, stream));
                 HIP_TRY(hipMemcpyAsync(qw.data(), qw_dev, sizeof(int2) * qw.size(), hipMemcpyDeviceToHost, stream));
                 HIP_TRY(hipStreamSynchronize(stream));
+                // how the layer's neurons are cut into workgroups: spdnn_cut.h (host code, tested without a GPU)
+                const std::vector<spdnn::NeuronRange> cut =
+                    spdnn::cut_workgroups(hp.data(), reinterpret_cast<const int*>(qw.data()), N, passes_of[ll], nblk, m->G,
+                                          spdnn::kBlk, spdnn::kNnz, spdnn::kCap);
                 virt_ranges.clear();
-                int first = 0, lanes = 0, lo = N, hi = -1;
-                for (int j = 0; j < N; j += 4) {  // N is a multiple of 4
-                    int q = 0;
-                    for (int i = 0; i < 4; ++i) q += (hp[j + i + 1] - hp[j + i] + spdnn::kNnz - 1) / spdnn::kNnz;
-                    const int2 w4 = qw[(size_t)j / 4];
-                    const int nlo = std::min(lo, w4.x), nhi = std::max(hi, w4.y);
-                    // a workgroup whose columns fit one LDS stage is not widened beyond it
-                    const bool widens = hi >= lo && hi - (lo & ~3) < spdnn::kCap && nhi - (nlo & ~3) >= spdnn::kCap;
-                    if (lanes + q > spdnn::kBlk || j - first == spdnn::kBlk || (j > first && widens)) {
-                        virt_ranges.push_back(make_int2(first, j - first));
-                        first = j;
-                        lanes = 0;
-                        lo = N;
-                        hi = -1;
-                    }
-                    lanes += q;  // a neuron has at most passes_of <= 256 parts: four of them always fit
-                    lo = std::min(lo, w4.x);
-                    hi = std::max(hi, w4.y);
-                }
-                virt_ranges.push_back(make_int2(first, N - first));
-                // The plain alternative: 1024 / passes_of neurons in every workgroup, as many as can all be of the
-                // longest kind.  Its workgroups are less full (their waves without connections do the finishing for
-                // free), so it is the faster one unless the packed workgroups are clearly fewer (measured: 128 plain
-                // against 112 packed workgroups 13.3 against 15.1 ms, 256 against 144: 27.3 against 22.6); it also
-                // always fits the arena, which has room for passes_of * nblk workgroups.
-                const int R = spdnn::kBlk / passes_of[ll];
-                const size_t plain = (size_t)(N + R - 1) / R;
-                if (virt_ranges.size() > (size_t)passes_of[ll] * nblk || 4 * virt_ranges.size() > 3 * plain) {
-                    virt_ranges.clear();
-                    // The workgroups that will share an XCD (a run of Gl: they read the same rows through one
-                    // window, and stay within reach of each other in the L2 only if they take equally long) get
-                    // equally many lanes rather than equally many neurons.
-                    int Gl = 1;
-                    for (int32_t g : {32, 16, 8, 4, 3, 2, 1})
-                        if (g <= m->G * passes_of[ll] && nblk % g == 0) {
-                            Gl = g;
-                            break;
-                        }
-                    auto lanes4 = [&](int j) {
-                        int q = 0;
-                        for (int i = 0; i < 4; ++i) q += (hp[j + i + 1] - hp[j + i] + spdnn::kNnz - 1) / spdnn::kNnz;
-                        return q;
-                    };
-                    for (int r0 = 0; r0 < N; r0 += Gl * R) {
-                        const int r1 = std::min(N, r0 + Gl * R);
-                        const int nW = (r1 - r0 + R - 1) / R;
-                        long left = 0;
-                        for (int j = r0; j < r1; j += 4) left += lanes4(j);
-                        const size_t mark = virt_ranges.size();
-                        int first = r0, lanes = 0, wleft = nW;
-                        long target = (left + wleft - 1) / wleft;
-                        bool ok = true;
-                        for (int j = r0; j < r1; j += 4) {
-                            const int q = lanes4(j);
-                            const bool full = lanes + q > spdnn::kBlk || j - first == spdnn::kBlk;
-                            if (j > first && (full || (wleft > 1 && lanes + q - target > target - lanes))) {
-                                virt_ranges.push_back(make_int2(first, j - first));
-                                left -= lanes;
-                                wleft = std::max(1, wleft - 1);
-                                target = (left + wleft - 1) / wleft;
-                                first = j;
-                                lanes = 0;
-                            }
-                            lanes += q;
-                        }
-                        virt_ranges.push_back(make_int2(first, r1 - first));
-                        ok = virt_ranges.size() - mark <= (size_t)nW;
-                        if (!ok) {  // (only if a workgroup overflowed on the way) the cut by neurons always fits
-                            virt_ranges.resize(mark);
-                            for (int j = r0; j < r1; j += R) virt_ranges.push_back(make_int2(j, std::min(R, r1 - j)));
-                        }
-                        while (virt_ranges.size() - mark < (size_t)nW) virt_ranges.push_back(make_int2(N, 0));
-                    }
-                }
+                for (const spdnn::NeuronRange& r : cut) virt_ranges.push_back(make_int2(r.first, r.count));
             }
             std::vector<int2> mine((size_t)nblk, make_int2(N, 0));
             for (int32_t b = 0; b < nblk; ++b) {

@@ -1,6 +1,7 @@
 // Host build of the connection-ordering routine (spdnn_order.h) and of the tile
 // layout functions (spdnn_layout.h), so that the set-up logic can be tested without a
 // GPU.  Not used by the inference path.
+#include "spdnn_cut.h"
 #include "spdnn_layout.h"
 #include "spdnn_order.h"
 
@@ -79,5 +80,18 @@ int spdnn_unit_neuron_host(int u, int p, int seg_log2, int seg_stride) { return 
 void spdnn_win_union_host(int ax, int ay, int cx, int cy, int N, int* out) { spdnn::win_union(ax, ay, cx, cy, N, out[0], out[1]); }
 int spdnn_win_rel_host(int c, int c_lo, int N) { return spdnn::win_rel(c, c_lo, N); }
 int spdnn_win_col_host(int c_lo, int rel, int N) { return spdnn::win_col(c_lo, rel, N); }
+
+// Workgroup cut of a general layer (spdnn_cut.h).  ptr: N + 1 row pointers; qw: 2 * (N / 4) ints, lowest and
+// highest column of every four neurons; out: room for cap pairs {first neuron, number of neurons}.  Returns the
+// number of workgroups, or -1 if there are more than cap.
+int spdnn_cut_workgroups_host(const int32_t* ptr, const int32_t* qw, int N, int P, int nblk, int G, int32_t* out, int cap) {
+    const std::vector<spdnn::NeuronRange> cut = spdnn::cut_workgroups(ptr, qw, N, P, nblk, G);
+    if ((int)cut.size() > cap) return -1;
+    for (size_t i = 0; i < cut.size(); ++i) {
+        out[2 * i] = cut[i].first;
+        out[2 * i + 1] = cut[i].count;
+    }
+    return (int)cut.size();
+}
 
 }  // extern "C"
