@@ -97,7 +97,6 @@ struct spdnn_model {
     const spdnn::LayerWeights* chain_layers = nullptr;  // device copy of the layers' descriptors (NULL: not possible)
     int* chain_rows = nullptr;                          // device, L + 1 counters
     int chain_lds_cols = 0;
-    hipEvent_t lag_ev[kLag] = {};
     // out-of-core weights: pass p's block lives in host memory and is copied into device slot p & 1
     const char* ooc_host = nullptr;
     char* ooc_slot[2] = {nullptr, nullptr};
@@ -397,7 +396,6 @@ int create_impl(spdnn_t* out, int32_t N, int32_t L, const std::vector<int32_t>& 
     constexpr size_t wide_lds = spdnn::kOrderThreads * sizeof(spdnn::WideScratch);
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&m->host_counts), sizeof(int) * (size_t)(L + 2),  // [L + 1]: see infer_impl
                           hipHostMallocDefault));
-    for (int i = 0; i < kLag; ++i) HIP_TRY(hipEventCreateWithFlags(&m->lag_ev[i], hipEventDisableTiming));
 
     // carve the arena: bias | P x (win, rel, val) | staging (raw idx, raw val, error flag)
     char* base = static_cast<char*>(weights_arena);
@@ -1038,20 +1036,20 @@ int infer_impl(spdnn_t h, const float* Y0_dev, int32_t batch, const WorkView& wv
         }
         if (h->profiling) HIP_TRY(hipEventRecord(h->t1[l], s));
         HIP_TRY(hipGetLastError());
-        HIP_TRY(hipEventRecord(h->lag_ev[l % kLag], s));
         run = l + 1;
         // Feedback with bounded lag: the number of rows active on entry to layer l+2-kLag bounds all later
         // ones.  That layer's kernel stores it to pinned host memory as it starts, which is polled here
-        // (so at most kLag-1 kernels are queued behind the running one); the layer's event is looked at
-        // only so that a failed launch ends the wait.
+        // (so at most kLag-1 kernels are queued behind the running one); the stream is asked now and then
+        // whether it has run dry, only so that a failed launch ends the wait.  Nothing else is put between two
+        // layers' kernels: an event recorded after every layer made the gap between them longer.
         if (l + 2 >= kLag) {
             const int32_t lr = l + 2 - kLag;
             volatile int* slot = h->host_counts + lr;
             int32_t c = *slot;
             for (uint32_t spin = 1; c < 0; ++spin) {
                 if ((spin & 1023u) == 0) {
-                    const hipError_t q = hipEventQuery(h->lag_ev[lr % kLag]);
-                    if (q == hipSuccess) {  // the layer is done: its count has been stored
+                    const hipError_t q = hipStreamQuery(s);
+                    if (q == hipSuccess) {  // everything launched is done: the count has been stored
                         c = *slot;
                         if (c < 0) return fail(SPDNN_EHIP, "layer %d finished without reporting its active rows", lr);
                         break;
@@ -1291,8 +1289,6 @@ int spdnn_destroy(spdnn_t h) {
     return guarded([&]() -> int {
         if (!h) return SPDNN_OK;
         if (h->host_counts) (void)hipHostFree(h->host_counts);
-        for (int i = 0; i < kLag; ++i)
-            if (h->lag_ev[i]) (void)hipEventDestroy(h->lag_ev[i]);
         for (int i = 0; i < 2; ++i) {
             if (h->ooc_ready[i]) (void)hipEventDestroy(h->ooc_ready[i]);
             if (h->ooc_freed[i]) (void)hipEventDestroy(h->ooc_freed[i]);
