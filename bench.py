@@ -158,13 +158,24 @@ def stream_probe(gib, dev):
     return out
 
 
-def timed_leg(model, y0, steps, warmup, N, nnz):
+def timed_leg(model, y0, steps, warmup, N, nnz, events_in_timed_region=True):
     """warmup + steps inferences of one resident input; HIP events on the model's stream around every
-    fused launch (the library's profile).  Returns wall seconds per step and the launch statistics."""
+    fused launch (the library's profile).  Returns wall seconds per step and the launch statistics.
+    events_in_timed_region=False: the steps are timed without the events (two per layer, 2.3 us each: a tenth of
+    an inference of 120 small layers) and the launch statistics come from the same number of steps run again
+    with them."""
     import numpy as np
     import torch
     for _ in range(warmup):
         model.infer(y0, want_Y=False)
+    dt_plain = None
+    if not events_in_timed_region:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            model.infer(y0, want_Y=False)
+        torch.cuda.synchronize()
+        dt_plain = time.perf_counter() - t0
     model.set_profiling(True)
     sum_ms = sum_bytes = full_ms = 0.0
     launches = full = 0
@@ -185,6 +196,8 @@ def timed_leg(model, y0, steps, warmup, N, nnz):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     model.set_profiling(False)
+    if dt_plain is not None:
+        dt = dt_plain
     return {"s_per_step": dt / steps, "sum_ms": sum_ms, "sum_bytes": sum_bytes, "launches": launches,
             "full_launches": full, "full_ms": full_ms, "rows_trace": np.asarray(rows_trace), "n_active": int(n_active),
             "rows_final": rows_final.cpu().numpy()}
@@ -330,10 +343,11 @@ def main():
         # which compaction and every layer's kernel matter.  Not part of `value`.
         del y0
         ym = synth.gen_y0(batch, N, c["seed"], density="mixed", device=dev)
-        sl = timed_leg(model, ym, a.sustained_steps, 1, N, nnz)
+        sl = timed_leg(model, ym, a.sustained_steps, 1, N, nnz, events_in_timed_region=False)
         ex = float(sum(int(r) for r in sl["rows_trace"])) * N * 32
         out["sustained_activity"] = {
-            "workload": "same model, Y0 rows of mixed density (ours): every layer runs",
+            "workload": "same model, Y0 rows of mixed density (ours): every layer runs; timed without the per-layer "
+                        "events, launch statistics from a second pass with them",
             "steps": a.sustained_steps, "ms_per_step": sl["s_per_step"] * 1e3,
             "nominal_TeraEdges_per_s": edges / sl["s_per_step"] / 1e12,
             "executed_TeraEdges_per_s": ex / sl["s_per_step"] / 1e12,
